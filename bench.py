@@ -1,0 +1,139 @@
+#!/usr/bin/env python3
+"""Benchmark of the multi-Bulyan hot path on one MI355X.
+
+A step = one mbulyan_aggregate call (distance pass, reduction, selection,
+coordinate pass) over one synthetic workload resident in HBM.  Prints ONE JSON
+line: whole-job GB/s of gradient input, the roofline of the dominant kernel
+(the distance pass) from HIP-event timings taken inside the timed region, and
+the CPU oracle timed on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--mode selected|alg1]
+"""
+import argparse
+import json
+import sys
+import time
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix, published
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4, help="workload 1..5 (default: the one the metric is quoted on)")
+    ap.add_argument("--d", type=int, default=None, help="override the number of coordinates")
+    ap.add_argument("--mode", choices=["selected", "alg1"], default="selected")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 24, help="coordinates the oracle is timed on")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the aggregation rule of one parameter server); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    import paper_1905_04374_amd as mb
+    import workloads as W
+
+    dev = "cuda:0"
+    spec = W.spec(a.config)
+    n, f = spec["n"], spec["f"]
+    d = a.d or spec["d"]
+    nchunks = spec["chunks"] if a.d is None else 1
+    mode = mb.MODE_SELECTED if a.mode == "selected" else mb.MODE_ALG1
+    theta, beta = mb.mbulyan_params(n, f, mode)
+
+    # ---- inputs resident in HBM before the timed region ----------------------
+    bounds = [d * k // nchunks for k in range(nchunks + 1)]
+    chunks = []
+    for k in range(nchunks):
+        g = torch.empty(n, bounds[k + 1] - bounds[k], device=dev, dtype=torch.float32)
+        W.fill(a.config, g, bounds[k])
+        chunks.append(g)
+    outs = [torch.empty(c.shape[1], device=dev, dtype=torch.float32) for c in chunks]
+    sel = torch.empty(theta, device=dev, dtype=torch.int32)
+    ws = torch.empty(mb.mbulyan_workspace_bytes(n, max(c.shape[1] for c in chunks)), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+
+    def step():
+        if nchunks == 1:
+            mb.mbulyan_aggregate_ex(chunks[0], f, mode=mode, out=outs[0], selected_idx=sel, workspace=ws)
+        else:
+            mb.mbulyan_aggregate_chunked(chunks, f, mode=mode, outs=outs, selected_idx=sel, workspace=ws)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    mb.mbulyan_timing_reset()
+    mb.mbulyan_timing_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    mb.mbulyan_timing_enable(False)
+    stages = mb.mbulyan_timing_read()
+
+    sec = (t1 - t0) / a.steps
+    in_bytes = 4.0 * n * d
+    rows2 = theta if mode == mb.MODE_SELECTED else None
+    value = in_bytes / sec / 1e9
+
+    # dominant kernel: the distance pass, 4*n bytes per coordinate, one launch per chunk
+    dist_ms, dist_launches = stages["dist"]
+    dist_avg_s = dist_ms / 1e3 / max(dist_launches, 1)
+    dist_bytes = in_bytes / nchunks
+    achieved = dist_bytes / dist_avg_s / 1e9
+    roofline = {"kernel": "dist_gram_kernel", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "avg_launch_ms": round(dist_avg_s * 1e3, 4), "launches": dist_launches}
+    nb = (n + 15) // 16
+    mfma_flops = nb * (nb + 1) // 2 * 256 * 2 * (d / nchunks)
+    roofline["mfma_fp32_tflops"] = round(mfma_flops / dist_avg_s / 1e12, 2)
+    roofline["mfma_fp32_frac"] = round(mfma_flops / dist_avg_s / 1e12 / MFMA_FP32_PEAK_TFLOPS, 4)
+
+    per_stage = {k: round(v[0] / a.steps, 4) for k, v in stages.items()}
+    coord_ms, coord_launches = stages["coord"]
+    if rows2 is not None and coord_launches:
+        coord_bytes = 4.0 * (rows2 + 1) * d / nchunks
+        per_stage["coord_GBps"] = round(coord_bytes / (coord_ms / 1e3 / coord_launches) / 1e9, 1)
+        alg_bytes = 4.0 * (n + rows2 + 1) * d
+        per_stage["hbm_frac_algorithmic_bytes"] = round(alg_bytes / sec / 1e9 / HBM_PEAK_GBS, 4)
+
+    res = {
+        "metric": "multi-Bulyan aggregation GB/s of gradient input (n*d*4B/s), 1 GPU",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(sec * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"configs[{a.config - 1}]: n={n} f={f} d={d} fp32, mode={a.mode}, "
+                               f"theta={theta} beta={beta}, chunks={nchunks}"},
+        "hbm_frac_input_bytes": round(value / HBM_PEAK_GBS, 4),
+        "stage_ms_per_step": per_stage,
+        "roofline": roofline,
+    }
+
+    if not a.no_cpu_baseline:
+        import numpy as np
+        import oracle as O
+        ds = min(a.cpu_sample, chunks[0].shape[1])
+        host = chunks[0][:, :ds].contiguous().cpu().numpy()
+        c0 = time.perf_counter()
+        O.mbulyan(host, f, O.MODE_SELECTED if mode == mb.MODE_SELECTED else O.MODE_ALG1)
+        c1 = time.perf_counter()
+        res["cpu_baseline"] = {"value": round(4.0 * n * ds / (c1 - c0) / 1e9, 3), "unit": "GB/s",
+                               "cores": O.last_threads(), "kind": "oracle",
+                               "sample": f"first {ds} of {d} coordinates, all {n} rows, whole rule, "
+                                         f"{round(c1 - c0, 2)} s"}
+        del host, np
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,229 @@
+/*
+ * mbulyan.h - C ABI of the MI355X (gfx950) multi-Bulyan library.
+ *
+ * multi-Bulyan is the gradient aggregation rule (GAR) of "Fast and Robust
+ * Distributed Learning in High Dimension" (arxiv 1905.04374), Algorithm 1:
+ * given n worker gradients of dimension d, at most f of them Byzantine, it
+ * runs theta rounds of multi-Krum on the pairwise squared distances, then,
+ * per coordinate, averages the beta values closest to a median.
+ *
+ * Conventions shared by every entry point
+ *   - Plain C, no exceptions.  Every call returns an MB_* status code.
+ *   - Pointers marked "device" are GPU global memory owned by the caller
+ *     (allocate them with anything that yields a HIP device pointer, e.g.
+ *     PyTorch); the library neither frees nor keeps them.  Pointers marked
+ *     "host" are ordinary process memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue their kernels on it and return without synchronising;
+ *     outputs are valid once the caller has synchronised the stream.
+ *   - Gradients: n rows of d floats (fp32), row i starting at grads + i*ld,
+ *     ld >= d the row stride in elements.  Fastest when grads is 16-byte
+ *     aligned and ld is a multiple of 4; other strides are handled by a
+ *     slower load path.  Inputs must be finite.
+ *   - n <= MB_MAX_N.
+ *   - Arguments are validated on the host before anything is launched; an
+ *     invalid call launches nothing.
+ *   - Calls that share a workspace (or the internal one) must not overlap.
+ */
+#ifndef MBULYAN_H
+#define MBULYAN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MB_MAX_N 64
+
+/* status codes */
+#define MB_OK 0
+#define MB_EINVAL 1       /* null pointer, n < 1, d < 1, ld < d, f < 0, bad mode / theta / beta */
+#define MB_EPRECOND 2     /* n < 4f+3 (multi-Bulyan) or n < 2f+3 (multi-Krum); Section II-B */
+#define MB_EUNSUPPORTED 3 /* n > MB_MAX_N */
+#define MB_EWORKSPACE 4   /* workspace too small or misaligned (256 bytes) */
+#define MB_EHIP 5         /* a HIP call failed; see mbulyan_last_hip_error() */
+
+/*
+ * The paper states the rule in two ways that differ; both are provided.
+ * MB_MODE_SELECTED: Section II-B (last sentence on Bulyan) and the proof of
+ *   Theorem 2(i): theta = n-2f rounds; median, beta closest and average are
+ *   taken over the theta extracted gradients.  beta = theta-2f = n-4f.
+ * MB_MODE_ALG1: Algorithm 1 as printed: theta = n-2f-2; the median is that
+ *   of the extracted gradients G^ext, the beta closest values are chosen
+ *   among, and averaged over, the multi-Krum averages G^agr.
+ *   beta = theta-2f = n-4f-2.
+ */
+#define MB_MODE_SELECTED 0
+#define MB_MODE_ALG1 1
+
+/* how pairwise_sqdist evaluates the distances */
+#define MB_DIST_AUTO 0   /* library picks */
+#define MB_DIST_DIRECT 1 /* sum of (x_i - x_j)^2 on the vector ALU, fp32 partial sums */
+#define MB_DIST_GRAM 2   /* Gram matrix on the fp32 matrix cores (MFMA), fp64 running sums,
+                            D_ij = G_ii + G_jj - 2 G_ij in fp64 */
+
+const char *mbulyan_strerror(int status);
+/* hipError_t (as int) of the last failing HIP call on this thread, 0 if none */
+int mbulyan_last_hip_error(void);
+const char *mbulyan_version(void);
+
+/*
+ * theta and beta of a mode (table above).  Host only.
+ * MB_EPRECOND if n < 4f+3 (Section II-B), MB_EINVAL for f < 0, n < 1 or an
+ * unknown mode, MB_EUNSUPPORTED if n > MB_MAX_N.
+ */
+int mbulyan_params(int n, int f, int mode, int *theta, int *beta);
+
+/*
+ * Bytes of device workspace that pairwise_sqdist and mbulyan_aggregate_ex need
+ * for n gradients of dimension d (per call, or per chunk for the chunked use).
+ * The workspace must be 256-byte aligned device memory.  Host only.
+ */
+int mbulyan_workspace_bytes(int n, int64_t d, size_t *bytes);
+
+/* Pick the distance algorithm used by MB_DIST_AUTO callers (process-wide; MB_DIST_AUTO restores
+ * the default choice).  Host only. */
+int mbulyan_set_dist_algo(int algo);
+
+/*
+ * GAR(f, [G_1..G_n]) = multi-Bulyan (Algorithm 1, function GAR), in
+ * MB_MODE_SELECTED, ld = d.
+ *   grads        device, n*d floats
+ *   out          device, d floats: the aggregated gradient
+ *   selected_idx device, n-2f int32 (may be NULL): the extracted workers in
+ *                extraction order
+ * Uses a workspace owned by the library (allocated on the first call on a
+ * device and grown when a later call needs more; freed by mbulyan_release).
+ * Launches: distance pass, its reduction, selection, coordinate pass.
+ */
+int mbulyan_aggregate(const float *grads, int n, int f, int64_t d, float *out,
+                      int32_t *selected_idx, void *stream);
+
+/*
+ * As mbulyan_aggregate with everything explicit.
+ *   mode          MB_MODE_SELECTED / MB_MODE_ALG1
+ *   theta, beta   0 = the mode's default; otherwise 1 <= beta <= theta <= n
+ *   workspace     device, ws_bytes >= mbulyan_workspace_bytes(n, d); NULL =
+ *                 the library's own
+ */
+int mbulyan_aggregate_ex(const float *grads, int n, int f, int64_t d,
+                         int64_t ld, int mode, int theta, int beta, float *out,
+                         int32_t *selected_idx, void *workspace,
+                         size_t ws_bytes, void *stream);
+
+/*
+ * The same rule over a matrix given as column chunks (for d too large for one
+ * buffer): chunk c holds columns [sum of chunk_d[0..c), +chunk_d[c]) as n rows
+ * of stride chunk_ld[c], and its part of the result goes to outs[c].
+ * Distances are accumulated over all chunks first (Algorithm 1 computes them
+ * over whole gradients), then one selection, then the coordinate pass per
+ * chunk.
+ *   chunks, outs      host arrays of nchunks device pointers
+ *   chunk_d, chunk_ld host arrays of nchunks sizes
+ */
+int mbulyan_aggregate_chunked(const float *const *chunks, int nchunks,
+                              const int64_t *chunk_d, const int64_t *chunk_ld,
+                              int n, int f, int mode, float *const *outs,
+                              int32_t *selected_idx, void *workspace,
+                              size_t ws_bytes, void *stream);
+
+/*
+ * Pairwise squared l2 distances (Algorithm 1, multi-Krum, the score line;
+ * Eq. 4): dist[i*n+j] = sum_c (G[i][c]-G[j][c])^2, symmetric, zero diagonal.
+ *   dist       device, n*n doubles
+ *   accumulate 0: overwrite dist; 1: add this call's distances to it (column
+ *              chunks of one matrix)
+ *   algo       MB_DIST_*
+ * Bit-identical rows get bit-identical distance rows and distance exactly 0
+ * to each other; the result does not depend on timing (no atomics).
+ */
+int pairwise_sqdist(const float *grads, int n, int64_t d, int64_t ld,
+                    double *dist, int accumulate, int algo, void *workspace,
+                    size_t ws_bytes, void *stream);
+
+/*
+ * Krum scores (Algorithm 1, multi-Krum; Eq. 4; footnote 1 of Section I):
+ * with k active gradients and q = max(k-f-2, 0), scores[i] = sum of the q
+ * smallest dist[i][j] over active j != i, added in ascending order in fp64.
+ * Inactive gradients get +inf.
+ *   dist   device, n*n doubles      active device, n bytes, NULL = all active
+ *   scores device, n doubles
+ */
+int krum_scores(const double *dist, int n, int f, const uint8_t *active,
+                double *scores, void *stream);
+
+/*
+ * theta rounds of multi-Krum on the gradients not yet extracted (Algorithm 1,
+ * multi-Bulyan, the loop).  Round t: scores on the n-t active gradients;
+ * order them by (score, index); selected_idx[t] = the first, which then
+ * leaves the active set; agr_sets[t*n+r] = 1 for the first m_t =
+ * max(n-t-f-2, 0) of them (the set multi-Krum averages), else 0.
+ *   selected_idx device, theta int32
+ *   agr_sets     device, theta*n bytes, may be NULL
+ *   m_out        device, theta int32, may be NULL
+ * Needs 1 <= theta <= n.  No precondition on (n, f) is imposed here.
+ */
+int multikrum_select(const double *dist, int n, int f, int theta,
+                     int32_t *selected_idx, uint8_t *agr_sets, int32_t *m_out,
+                     void *stream);
+
+/*
+ * Coordinate-wise phase (Algorithm 1, multi-Bulyan, after the loop; Section
+ * II-B).  For every coordinate c:
+ *   agr_sets == NULL: v_t = G[selected_idx[t]][c]; med = median of the v_t;
+ *     out[c] = average of the beta values v_t closest to med.
+ *   agr_sets != NULL: med = median over t of G[selected_idx[t]][c];
+ *     a_t = average of G[r][c] over the rows r with agr_sets[t*n+r] != 0;
+ *     out[c] = average of the beta values a_t closest to med.
+ * Median of an even count: 0.5*(lo+hi) in fp32.  Closeness: |v-med| as one
+ * fp32 subtraction; on equal closeness the smaller value is preferred.
+ *   selected_idx device, theta int32 in [0, n), validated on the device: an
+ *                out-of-range index makes the kernel write NaN to out
+ *   out          device, d floats
+ */
+int coordwise_trimmed_avg(const float *grads, int n, int64_t d, int64_t ld,
+                          const int32_t *selected_idx, int theta, int beta,
+                          const uint8_t *agr_sets, float *out, void *stream);
+
+/*
+ * Multi-Krum as a GAR (Algorithm 1, function multi-Krum, G^output): the
+ * average of the m = n-f-2 gradients of smallest score.  Needs n >= 2f+3.
+ *   selected_mask device, n bytes, may be NULL: 1 for the averaged gradients
+ */
+int multikrum_aggregate(const float *grads, int n, int f, int64_t d,
+                        int64_t ld, float *out, uint8_t *selected_mask,
+                        void *workspace, size_t ws_bytes, void *stream);
+
+/*
+ * Coordinate-wise median of all n gradients (the Median GAR the paper compares
+ * with in Section V).
+ */
+int coordwise_median(const float *grads, int n, int64_t d, int64_t ld,
+                     float *out, void *stream);
+
+/*
+ * Per-kernel timing of the calls above, with HIP events recorded on the call's
+ * own stream.  mbulyan_timing_enable(1) starts collecting, (0) stops.
+ * mbulyan_timing_read synchronises the recorded events and returns, per stage,
+ * the summed milliseconds and the number of launches since the last
+ * mbulyan_timing_reset.  Stages: 0 distance pass, 1 distance reduction,
+ * 2 selection, 3 coordinate pass.  Host only; not thread safe.
+ */
+#define MB_STAGE_DIST 0
+#define MB_STAGE_REDUCE 1
+#define MB_STAGE_SELECT 2
+#define MB_STAGE_COORD 3
+#define MB_NUM_STAGES 4
+int mbulyan_timing_enable(int on);
+int mbulyan_timing_reset(void);
+int mbulyan_timing_read(double *ms_per_stage, int64_t *launches_per_stage);
+
+/* Free the library's own workspaces and timing events (all devices). */
+int mbulyan_release(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MBULYAN_H */

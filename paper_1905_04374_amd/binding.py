@@ -1,0 +1,264 @@
+"""ctypes binding of libmbulyan.so: argument marshalling only.
+
+Every function has the name and meaning of the C entry point in
+include/mbulyan.h; tensors are torch CUDA tensors (device memory), the stream
+is torch's current stream unless given.  Nothing is computed here.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libmbulyan.so")
+
+MB_MAX_N = 64
+MB_OK, MB_EINVAL, MB_EPRECOND, MB_EUNSUPPORTED, MB_EWORKSPACE, MB_EHIP = range(6)
+MODE_SELECTED, MODE_ALG1 = 0, 1
+DIST_AUTO, DIST_DIRECT, DIST_GRAM = 0, 1, 2
+STAGES = ("dist", "reduce", "select", "coord")
+
+EXPORTS = [
+    "mbulyan_strerror", "mbulyan_last_hip_error", "mbulyan_version", "mbulyan_params",
+    "mbulyan_workspace_bytes", "mbulyan_set_dist_algo", "mbulyan_aggregate", "mbulyan_aggregate_ex",
+    "mbulyan_aggregate_chunked", "pairwise_sqdist", "krum_scores", "multikrum_select",
+    "coordwise_trimmed_avg", "multikrum_aggregate", "coordwise_median", "mbulyan_timing_enable",
+    "mbulyan_timing_reset", "mbulyan_timing_read", "mbulyan_release",
+]
+
+
+class MBulyanError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"mbulyan status {status}: {message}")
+        self.status = status
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_1905_04374_amd.build` "
+            "(there is no fallback implementation)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i64, sz = C.c_void_p, C.c_int64, C.c_size_t
+    ci = C.c_int
+    lib.mbulyan_strerror.restype = C.c_char_p
+    lib.mbulyan_strerror.argtypes = [ci]
+    lib.mbulyan_version.restype = C.c_char_p
+    lib.mbulyan_params.argtypes = [ci, ci, ci, C.POINTER(ci), C.POINTER(ci)]
+    lib.mbulyan_workspace_bytes.argtypes = [ci, i64, C.POINTER(sz)]
+    lib.mbulyan_set_dist_algo.argtypes = [ci]
+    lib.mbulyan_aggregate.argtypes = [vp, ci, ci, i64, vp, vp, vp]
+    lib.mbulyan_aggregate_ex.argtypes = [vp, ci, ci, i64, i64, ci, ci, ci, vp, vp, vp, sz, vp]
+    lib.mbulyan_aggregate_chunked.argtypes = [C.POINTER(vp), ci, C.POINTER(i64), C.POINTER(i64), ci, ci, ci,
+                                              C.POINTER(vp), vp, vp, sz, vp]
+    lib.pairwise_sqdist.argtypes = [vp, ci, i64, i64, vp, ci, ci, vp, sz, vp]
+    lib.krum_scores.argtypes = [vp, ci, ci, vp, vp, vp]
+    lib.multikrum_select.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
+    lib.coordwise_trimmed_avg.argtypes = [vp, ci, i64, i64, vp, ci, ci, vp, vp, vp]
+    lib.multikrum_aggregate.argtypes = [vp, ci, ci, i64, i64, vp, vp, vp, sz, vp]
+    lib.coordwise_median.argtypes = [vp, ci, i64, i64, vp, vp]
+    lib.mbulyan_timing_enable.argtypes = [ci]
+    lib.mbulyan_timing_read.argtypes = [C.POINTER(C.c_double), C.POINTER(i64)]
+    return lib
+
+
+lib = _load()
+
+
+def _check(status: int):
+    if status != MB_OK:
+        msg = lib.mbulyan_strerror(status).decode()
+        if status == MB_EHIP:
+            msg += f" (hipError {lib.mbulyan_last_hip_error()})"
+        raise MBulyanError(status, msg)
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _dev(t: torch.Tensor | None, dtype, name: str) -> int | None:
+    if t is None:
+        return None
+    if not t.is_cuda or t.dtype != dtype:
+        raise TypeError(f"{name} must be a CUDA tensor of dtype {dtype}")
+    return t.data_ptr()
+
+
+def _matrix(grads: torch.Tensor):
+    """(pointer, n, d, ld) of an (n, d) float32 CUDA tensor with unit column stride."""
+    if not grads.is_cuda or grads.dtype != torch.float32 or grads.dim() != 2:
+        raise TypeError("grads must be a 2-D float32 CUDA tensor")
+    n, d = grads.shape
+    if d > 1 and grads.stride(1) != 1:
+        raise ValueError("grads must have unit stride along the coordinates")
+    ld = grads.stride(0) if n > 1 else max(d, 1)
+    return grads.data_ptr(), n, d, ld
+
+
+def version() -> str:
+    return lib.mbulyan_version().decode()
+
+
+def mbulyan_params(n: int, f: int, mode: int = MODE_SELECTED):
+    th, be = C.c_int(), C.c_int()
+    _check(lib.mbulyan_params(n, f, mode, C.byref(th), C.byref(be)))
+    return th.value, be.value
+
+
+def mbulyan_workspace_bytes(n: int, d: int) -> int:
+    b = C.c_size_t()
+    _check(lib.mbulyan_workspace_bytes(n, d, C.byref(b)))
+    return b.value
+
+
+def mbulyan_set_dist_algo(algo: int):
+    _check(lib.mbulyan_set_dist_algo(algo))
+
+
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    if not workspace.is_cuda or workspace.dtype != torch.uint8:
+        raise TypeError("workspace must be a uint8 CUDA tensor")
+    return workspace.data_ptr(), workspace.numel()
+
+
+def mbulyan_aggregate(grads, f, out=None, selected_idx=None, stream=None):
+    """GAR(f, grads) in MB_MODE_SELECTED with the library's workspace.  Returns (out, selected_idx)."""
+    p, n, d, ld = _matrix(grads)
+    if ld != d:
+        raise ValueError("mbulyan_aggregate needs a dense matrix (ld == d); use mbulyan_aggregate_ex")
+    theta, _ = mbulyan_params(n, f, MODE_SELECTED)
+    if out is None:
+        out = torch.empty(d, device=grads.device, dtype=torch.float32)
+    if selected_idx is None:
+        selected_idx = torch.empty(theta, device=grads.device, dtype=torch.int32)
+    _check(lib.mbulyan_aggregate(p, n, f, d, _dev(out, torch.float32, "out"),
+                                 _dev(selected_idx, torch.int32, "selected_idx"), _stream(stream)))
+    return out, selected_idx
+
+
+def mbulyan_aggregate_ex(grads, f, mode=MODE_SELECTED, theta=0, beta=0, out=None, selected_idx=None,
+                         workspace=None, stream=None):
+    p, n, d, ld = _matrix(grads)
+    th_def, _ = mbulyan_params(n, f, mode)
+    th = theta or th_def
+    if out is None:
+        out = torch.empty(d, device=grads.device, dtype=torch.float32)
+    if selected_idx is None:
+        selected_idx = torch.empty(th, device=grads.device, dtype=torch.int32)
+    wp, wb = _ws(workspace)
+    _check(lib.mbulyan_aggregate_ex(p, n, f, d, ld, mode, theta, beta, _dev(out, torch.float32, "out"),
+                                    _dev(selected_idx, torch.int32, "selected_idx"), wp, wb, _stream(stream)))
+    return out, selected_idx
+
+
+def mbulyan_aggregate_chunked(chunks, f, mode=MODE_SELECTED, outs=None, selected_idx=None, workspace=None,
+                              stream=None):
+    """chunks: list of (n, d_c) float32 CUDA tensors, the column chunks of one matrix."""
+    k = len(chunks)
+    mats = [_matrix(c) for c in chunks]
+    n = mats[0][1]
+    if any(m[1] != n for m in mats):
+        raise ValueError("all chunks must have the same number of rows")
+    theta, _ = mbulyan_params(n, f, mode)
+    if outs is None:
+        outs = [torch.empty(m[2], device=chunks[0].device, dtype=torch.float32) for m in mats]
+    if selected_idx is None:
+        selected_idx = torch.empty(theta, device=chunks[0].device, dtype=torch.int32)
+    cp = (C.c_void_p * k)(*[m[0] for m in mats])
+    cd = (C.c_int64 * k)(*[m[2] for m in mats])
+    cl = (C.c_int64 * k)(*[m[3] for m in mats])
+    op = (C.c_void_p * k)(*[_dev(o, torch.float32, "out") for o in outs])
+    wp, wb = _ws(workspace)
+    _check(lib.mbulyan_aggregate_chunked(cp, k, cd, cl, n, f, mode, op,
+                                         _dev(selected_idx, torch.int32, "selected_idx"), wp, wb,
+                                         _stream(stream)))
+    return outs, selected_idx
+
+
+def pairwise_sqdist(grads, dist=None, accumulate=False, algo=DIST_AUTO, workspace=None, stream=None):
+    p, n, d, ld = _matrix(grads)
+    if dist is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing dist")
+        dist = torch.empty(n, n, device=grads.device, dtype=torch.float64)
+    wp, wb = _ws(workspace)
+    _check(lib.pairwise_sqdist(p, n, d, ld, _dev(dist, torch.float64, "dist"), int(accumulate), algo, wp, wb,
+                               _stream(stream)))
+    return dist
+
+
+def krum_scores(dist, f, active=None, scores=None, stream=None):
+    n = dist.shape[0]
+    if scores is None:
+        scores = torch.empty(n, device=dist.device, dtype=torch.float64)
+    _check(lib.krum_scores(_dev(dist, torch.float64, "dist"), n, f, _dev(active, torch.uint8, "active"),
+                           _dev(scores, torch.float64, "scores"), _stream(stream)))
+    return scores
+
+
+def multikrum_select(dist, f, theta, want_sets=True, stream=None):
+    n = dist.shape[0]
+    sel = torch.empty(max(theta, 0), device=dist.device, dtype=torch.int32)
+    sets = torch.empty(max(theta, 0), n, device=dist.device, dtype=torch.uint8) if want_sets else None
+    m = torch.empty(max(theta, 0), device=dist.device, dtype=torch.int32) if want_sets else None
+    _check(lib.multikrum_select(_dev(dist, torch.float64, "dist"), n, f, theta, _dev(sel, torch.int32, "sel"),
+                                _dev(sets, torch.uint8, "agr_sets"), _dev(m, torch.int32, "m_out"),
+                                _stream(stream)))
+    return sel, sets, m
+
+
+def coordwise_trimmed_avg(grads, selected_idx, beta, agr_sets=None, out=None, stream=None):
+    p, n, d, ld = _matrix(grads)
+    if out is None:
+        out = torch.empty(d, device=grads.device, dtype=torch.float32)
+    _check(lib.coordwise_trimmed_avg(p, n, d, ld, _dev(selected_idx, torch.int32, "selected_idx"),
+                                     selected_idx.numel(), beta, _dev(agr_sets, torch.uint8, "agr_sets"),
+                                     _dev(out, torch.float32, "out"), _stream(stream)))
+    return out
+
+
+def multikrum_aggregate(grads, f, out=None, selected_mask=None, workspace=None, stream=None):
+    p, n, d, ld = _matrix(grads)
+    if out is None:
+        out = torch.empty(d, device=grads.device, dtype=torch.float32)
+    if selected_mask is None:
+        selected_mask = torch.empty(n, device=grads.device, dtype=torch.uint8)
+    wp, wb = _ws(workspace)
+    _check(lib.multikrum_aggregate(p, n, f, d, ld, _dev(out, torch.float32, "out"),
+                                   _dev(selected_mask, torch.uint8, "selected_mask"), wp, wb, _stream(stream)))
+    return out, selected_mask
+
+
+def coordwise_median(grads, out=None, stream=None):
+    p, n, d, ld = _matrix(grads)
+    if out is None:
+        out = torch.empty(d, device=grads.device, dtype=torch.float32)
+    _check(lib.coordwise_median(p, n, d, ld, _dev(out, torch.float32, "out"), _stream(stream)))
+    return out
+
+
+def mbulyan_timing_enable(on: bool):
+    _check(lib.mbulyan_timing_enable(int(on)))
+
+
+def mbulyan_timing_reset():
+    _check(lib.mbulyan_timing_reset())
+
+
+def mbulyan_timing_read():
+    """{stage: (milliseconds, launches)} since the last reset (synchronises the recorded events)."""
+    ms = (C.c_double * len(STAGES))()
+    cnt = (C.c_int64 * len(STAGES))()
+    _check(lib.mbulyan_timing_read(ms, cnt))
+    return {s: (ms[i], cnt[i]) for i, s in enumerate(STAGES)}
+
+
+def mbulyan_release():
+    _check(lib.mbulyan_release())

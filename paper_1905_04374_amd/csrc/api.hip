@@ -1,0 +1,479 @@
+// C ABI of the multi-Bulyan library: argument checks, workspace layout, launch order.
+// Every step of the rule runs in the kernels of dist.hip, select.hip, coordwise.hip and
+// rowops.hip; nothing is computed on the host.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <vector>
+
+#include "../../include/mbulyan.h"
+#include "mb_internal.hpp"
+
+namespace {
+
+thread_local int tl_hip_error = 0;
+int g_dist_algo = MB_DIST_AUTO;
+
+int hip_fail(hipError_t e)
+{
+    tl_hip_error = (int)e;
+    return MB_EHIP;
+}
+#define MB_HIP(expr)                                   \
+    do {                                               \
+        hipError_t e_ = (expr);                        \
+        if (e_ != hipSuccess) return hip_fail(e_);     \
+    } while (0)
+
+// ---- workspace layout (offsets in bytes, every segment 256-byte aligned) ----
+constexpr size_t kOffDist = 0;                                   // 64*64 doubles
+constexpr size_t kOffReduced = kOffDist + 64 * 64 * 8;           // up to 2560 doubles
+constexpr size_t kOffSel = kOffReduced + 2560 * 8;               // 64 int32
+constexpr size_t kOffM = kOffSel + 256;                          // 64 int32
+constexpr size_t kOffSets = kOffM + 256;                         // 64*64 bytes
+constexpr size_t kOffPartials = kOffSets + 4096;
+
+struct Workspace {
+    char *base;
+    double *dist() const { return reinterpret_cast<double *>(base + kOffDist); }
+    double *reduced() const { return reinterpret_cast<double *>(base + kOffReduced); }
+    int32_t *sel() const { return reinterpret_cast<int32_t *>(base + kOffSel); }
+    int32_t *m() const { return reinterpret_cast<int32_t *>(base + kOffM); }
+    uint8_t *sets() const { return reinterpret_cast<uint8_t *>(base + kOffSets); }
+    double *partials() const { return reinterpret_cast<double *>(base + kOffPartials); }
+};
+
+int resolve_algo(int algo)
+{
+    if (algo == MB_DIST_AUTO) algo = g_dist_algo;
+    if (algo == MB_DIST_AUTO) algo = MB_DIST_GRAM;
+    return algo;
+}
+
+size_t partial_bytes(int n, int64_t d)
+{
+    const int b1 = mb::dist_grid_blocks(d, MB_DIST_DIRECT), b2 = mb::dist_grid_blocks(d, MB_DIST_GRAM);
+    const size_t s1 = (size_t)b1 * mb::kDirectSlots, s2 = (size_t)b2 * mb::gram_slots(n);
+    return (s1 > s2 ? s1 : s2) * sizeof(double);
+}
+
+size_t workspace_bytes(int n, int64_t d)
+{
+    return kOffPartials + ((partial_bytes(n, d) + 255) / 256) * 256;
+}
+
+// ---- the library's own workspace, one per device --------------------------
+struct Owned {
+    void *ptr = nullptr;
+    size_t bytes = 0;
+};
+std::mutex g_mu;
+std::map<int, Owned> g_owned;
+
+int own_workspace(size_t need, Workspace *ws)
+{
+    int dev = 0;
+    MB_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lock(g_mu);
+    Owned &o = g_owned[dev];
+    if (o.bytes < need) {
+        if (o.ptr) {
+            MB_HIP(hipDeviceSynchronize());
+            MB_HIP(hipFree(o.ptr));
+            o.ptr = nullptr;
+            o.bytes = 0;
+        }
+        MB_HIP(hipMalloc(&o.ptr, need));
+        o.bytes = need;
+    }
+    ws->base = static_cast<char *>(o.ptr);
+    return MB_OK;
+}
+
+int get_workspace(void *user, size_t user_bytes, int n, int64_t d, Workspace *ws)
+{
+    const size_t need = workspace_bytes(n, d);
+    if (user) {
+        if ((uintptr_t)user % 256 != 0 || user_bytes < need) return MB_EWORKSPACE;
+        ws->base = static_cast<char *>(user);
+        return MB_OK;
+    }
+    return own_workspace(need, ws);
+}
+
+// ---- per-stage timing -------------------------------------------------------
+struct Span {
+    int stage;
+    hipEvent_t a, b;
+};
+bool g_timing = false;
+std::vector<Span> g_spans;
+double g_ms[MB_NUM_STAGES] = {0, 0, 0, 0};
+int64_t g_launches[MB_NUM_STAGES] = {0, 0, 0, 0};
+
+struct StageTimer {
+    bool on;
+    Span sp;
+    hipStream_t s;
+    StageTimer(int stage, hipStream_t stream) : on(g_timing), s(stream)
+    {
+        if (!on) return;
+        sp.stage = stage;
+        if (hipEventCreate(&sp.a) != hipSuccess || hipEventCreate(&sp.b) != hipSuccess) { on = false; return; }
+        hipEventRecord(sp.a, s);
+    }
+    ~StageTimer()
+    {
+        if (!on) return;
+        hipEventRecord(sp.b, s);
+        g_spans.push_back(sp);
+    }
+};
+
+int drain_spans()
+{
+    for (Span &sp : g_spans) {
+        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(sp.b);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, sp.a, sp.b);
+        hipEventDestroy(sp.a);
+        hipEventDestroy(sp.b);
+        if (e != hipSuccess) { g_spans.clear(); return hip_fail(e); }
+        g_ms[sp.stage] += ms;
+        g_launches[sp.stage] += 1;
+    }
+    g_spans.clear();
+    return MB_OK;
+}
+
+// ---- argument checks ---------------------------------------------------------
+int check_matrix(const void *grads, int n, int64_t d, int64_t ld)
+{
+    if (!grads || n < 1 || d < 1 || ld < d) return MB_EINVAL;
+    if (n > MB_MAX_N) return MB_EUNSUPPORTED;
+    return MB_OK;
+}
+
+// distances of one matrix into ws.dist()
+int run_dist(const float *grads, int n, int64_t d, int64_t ld, double *dist, int accumulate, int algo,
+             const Workspace &ws, hipStream_t s)
+{
+    algo = resolve_algo(algo);
+    const int nblocks = mb::dist_grid_blocks(d, algo);
+    if (algo == MB_DIST_DIRECT) {
+        const int nb = (n + 7) / 8, slots = nb * (nb + 1) / 2 * 64;
+        {
+            StageTimer t(MB_STAGE_DIST, s);
+            MB_HIP(mb::launch_dist_direct(grads, n, d, ld, ws.partials(), nblocks, s));
+        }
+        StageTimer t(MB_STAGE_REDUCE, s);
+        MB_HIP(mb::launch_reduce(ws.partials(), nblocks, mb::kDirectSlots, slots, ws.reduced(), s));
+        MB_HIP(mb::launch_finalize_direct(ws.reduced(), n, dist, accumulate, s));
+    } else if (algo == MB_DIST_GRAM) {
+        const int slots = mb::gram_slots(n);
+        {
+            StageTimer t(MB_STAGE_DIST, s);
+            MB_HIP(mb::launch_dist_gram(grads, n, d, ld, ws.partials(), nblocks, s));
+        }
+        StageTimer t(MB_STAGE_REDUCE, s);
+        MB_HIP(mb::launch_reduce(ws.partials(), nblocks, slots, slots, ws.reduced(), s));
+        MB_HIP(mb::launch_finalize_gram(ws.reduced(), n, dist, accumulate, s));
+    } else {
+        return MB_EINVAL;
+    }
+    return MB_OK;
+}
+
+int run_coord(const float *grads, int n, int64_t d, int64_t ld, int mode, int theta, int beta,
+              const int32_t *sel, const uint8_t *sets, float *out, hipStream_t s)
+{
+    StageTimer t(MB_STAGE_COORD, s);
+    if (mode == MB_MODE_SELECTED) {
+        mb::CoordArgs a{grads, n, d, ld, sel, theta, beta, 0, out};
+        MB_HIP(mb::launch_coord_selected(a, s));
+    } else {
+        mb::CoordAlg1Args a{grads, n, d, ld, sel, sets, theta, beta, out};
+        MB_HIP(mb::launch_coord_alg1(a, s));
+    }
+    return MB_OK;
+}
+
+int resolve_params(int n, int f, int mode, int *theta, int *beta)
+{
+    int th = 0, be = 0;
+    const int rc = mbulyan_params(n, f, mode, &th, &be);
+    if (rc != MB_OK) return rc;
+    if (*theta == 0) *theta = th;
+    if (*beta == 0) *beta = (*theta == th) ? be : *theta - 2 * f;
+    if (*theta < 1 || *theta > n || *beta < 1 || *beta > *theta) return MB_EINVAL;
+    return MB_OK;
+}
+
+}  // namespace
+
+namespace mb {
+hipError_t launch_coord_selected(const CoordArgs &a, hipStream_t s)
+{
+    if (a.theta < 1 || a.theta > kMaxN) return hipErrorInvalidValue;
+    switch ((a.theta - 1) / 8) {
+        case 0: return launch_coord_group0(a, s);
+        case 1: return launch_coord_group1(a, s);
+        case 2: return launch_coord_group2(a, s);
+        case 3: return launch_coord_group3(a, s);
+        case 4: return launch_coord_group4(a, s);
+        case 5: return launch_coord_group5(a, s);
+        case 6: return launch_coord_group6(a, s);
+        default: return launch_coord_group7(a, s);
+    }
+}
+hipError_t launch_coord_alg1(const CoordAlg1Args &a, hipStream_t s)
+{
+    if (a.theta < 1 || a.theta > kMaxN) return hipErrorInvalidValue;
+    switch ((a.theta - 1) / 16) {
+        case 0: return launch_coord_alg1_group0(a, s);
+        case 1: return launch_coord_alg1_group1(a, s);
+        case 2: return launch_coord_alg1_group2(a, s);
+        default: return launch_coord_alg1_group3(a, s);
+    }
+}
+}  // namespace mb
+
+extern "C" {
+
+const char *mbulyan_strerror(int status)
+{
+    switch (status) {
+        case MB_OK: return "ok";
+        case MB_EINVAL: return "invalid argument";
+        case MB_EPRECOND: return "precondition violated: multi-Bulyan needs n >= 4f+3, multi-Krum n >= 2f+3";
+        case MB_EUNSUPPORTED: return "unsupported size: n exceeds MB_MAX_N";
+        case MB_EWORKSPACE: return "workspace too small or not 256-byte aligned";
+        case MB_EHIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+int mbulyan_last_hip_error(void) { return tl_hip_error; }
+
+const char *mbulyan_version(void) { return "mbulyan 0.1 (gfx950)"; }
+
+int mbulyan_params(int n, int f, int mode, int *theta, int *beta)
+{
+    if (n < 1 || f < 0 || (mode != MB_MODE_SELECTED && mode != MB_MODE_ALG1)) return MB_EINVAL;
+    if (n < 4 * f + 3) return MB_EPRECOND;
+    if (n > MB_MAX_N) return MB_EUNSUPPORTED;
+    const int th = mode == MB_MODE_SELECTED ? n - 2 * f : n - 2 * f - 2;
+    if (theta) *theta = th;
+    if (beta) *beta = th - 2 * f;
+    return MB_OK;
+}
+
+int mbulyan_workspace_bytes(int n, int64_t d, size_t *bytes)
+{
+    if (!bytes || n < 1 || d < 1) return MB_EINVAL;
+    if (n > MB_MAX_N) return MB_EUNSUPPORTED;
+    *bytes = workspace_bytes(n, d);
+    return MB_OK;
+}
+
+int mbulyan_set_dist_algo(int algo)
+{
+    if (algo != MB_DIST_AUTO && algo != MB_DIST_DIRECT && algo != MB_DIST_GRAM) return MB_EINVAL;
+    g_dist_algo = algo;
+    return MB_OK;
+}
+
+int pairwise_sqdist(const float *grads, int n, int64_t d, int64_t ld, double *dist, int accumulate,
+                    int algo, void *workspace, size_t ws_bytes, void *stream)
+{
+    int rc = check_matrix(grads, n, d, ld);
+    if (rc != MB_OK) return rc;
+    if (!dist) return MB_EINVAL;
+    if (algo != MB_DIST_AUTO && algo != MB_DIST_DIRECT && algo != MB_DIST_GRAM) return MB_EINVAL;
+    Workspace ws;
+    rc = get_workspace(workspace, ws_bytes, n, d, &ws);
+    if (rc != MB_OK) return rc;
+    return run_dist(grads, n, d, ld, dist, accumulate ? 1 : 0, algo, ws, (hipStream_t)stream);
+}
+
+int krum_scores(const double *dist, int n, int f, const uint8_t *active, double *scores, void *stream)
+{
+    if (!dist || !scores || n < 1 || f < 0) return MB_EINVAL;
+    if (n > MB_MAX_N) return MB_EUNSUPPORTED;
+    StageTimer t(MB_STAGE_SELECT, (hipStream_t)stream);
+    MB_HIP(mb::launch_select(dist, n, f, 1, active, nullptr, nullptr, nullptr, scores, (hipStream_t)stream));
+    return MB_OK;
+}
+
+int multikrum_select(const double *dist, int n, int f, int theta, int32_t *selected_idx,
+                     uint8_t *agr_sets, int32_t *m_out, void *stream)
+{
+    if (!dist || !selected_idx || n < 1 || f < 0 || theta < 1 || theta > n) return MB_EINVAL;
+    if (n > MB_MAX_N) return MB_EUNSUPPORTED;
+    StageTimer t(MB_STAGE_SELECT, (hipStream_t)stream);
+    MB_HIP(mb::launch_select(dist, n, f, theta, nullptr, selected_idx, agr_sets, m_out, nullptr,
+                             (hipStream_t)stream));
+    return MB_OK;
+}
+
+int coordwise_trimmed_avg(const float *grads, int n, int64_t d, int64_t ld, const int32_t *selected_idx,
+                          int theta, int beta, const uint8_t *agr_sets, float *out, void *stream)
+{
+    const int rc = check_matrix(grads, n, d, ld);
+    if (rc != MB_OK) return rc;
+    if (!selected_idx || !out || theta < 1 || theta > n || beta < 1 || beta > theta) return MB_EINVAL;
+    return run_coord(grads, n, d, ld, agr_sets ? MB_MODE_ALG1 : MB_MODE_SELECTED, theta, beta,
+                     selected_idx, agr_sets, out, (hipStream_t)stream);
+}
+
+int mbulyan_aggregate_chunked(const float *const *chunks, int nchunks, const int64_t *chunk_d,
+                              const int64_t *chunk_ld, int n, int f, int mode, float *const *outs,
+                              int32_t *selected_idx, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!chunks || !chunk_d || !chunk_ld || !outs || nchunks < 1) return MB_EINVAL;
+    int theta = 0, beta = 0;
+    int rc = resolve_params(n, f, mode, &theta, &beta);
+    if (rc != MB_OK) return rc;
+    int64_t dmax = 0;
+    for (int c = 0; c < nchunks; ++c) {
+        rc = check_matrix(chunks[c], n, chunk_d[c], chunk_ld[c]);
+        if (rc != MB_OK) return rc;
+        if (!outs[c]) return MB_EINVAL;
+        dmax = chunk_d[c] > dmax ? chunk_d[c] : dmax;
+    }
+    Workspace ws;
+    rc = get_workspace(workspace, ws_bytes, n, dmax, &ws);
+    if (rc != MB_OK) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    for (int c = 0; c < nchunks; ++c) {
+        rc = run_dist(chunks[c], n, chunk_d[c], chunk_ld[c], ws.dist(), c > 0, MB_DIST_AUTO, ws, s);
+        if (rc != MB_OK) return rc;
+    }
+    {
+        StageTimer t(MB_STAGE_SELECT, s);
+        MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, ws.sel(), ws.sets(), ws.m(), nullptr, s));
+    }
+    for (int c = 0; c < nchunks; ++c) {
+        rc = run_coord(chunks[c], n, chunk_d[c], chunk_ld[c], mode, theta, beta, ws.sel(), ws.sets(),
+                       outs[c], s);
+        if (rc != MB_OK) return rc;
+    }
+    if (selected_idx)
+        MB_HIP(hipMemcpyAsync(selected_idx, ws.sel(), sizeof(int32_t) * theta, hipMemcpyDeviceToDevice, s));
+    return MB_OK;
+}
+
+int mbulyan_aggregate_ex(const float *grads, int n, int f, int64_t d, int64_t ld, int mode, int theta,
+                         int beta, float *out, int32_t *selected_idx, void *workspace, size_t ws_bytes,
+                         void *stream)
+{
+    int rc = check_matrix(grads, n, d, ld);
+    if (rc != MB_OK) return rc;
+    if (!out) return MB_EINVAL;
+    rc = resolve_params(n, f, mode, &theta, &beta);
+    if (rc != MB_OK) return rc;
+    Workspace ws;
+    rc = get_workspace(workspace, ws_bytes, n, d, &ws);
+    if (rc != MB_OK) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    rc = run_dist(grads, n, d, ld, ws.dist(), 0, MB_DIST_AUTO, ws, s);
+    if (rc != MB_OK) return rc;
+    {
+        StageTimer t(MB_STAGE_SELECT, s);
+        MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, ws.sel(), ws.sets(), ws.m(), nullptr, s));
+    }
+    rc = run_coord(grads, n, d, ld, mode, theta, beta, ws.sel(), ws.sets(), out, s);
+    if (rc != MB_OK) return rc;
+    if (selected_idx)
+        MB_HIP(hipMemcpyAsync(selected_idx, ws.sel(), sizeof(int32_t) * theta, hipMemcpyDeviceToDevice, s));
+    return MB_OK;
+}
+
+int mbulyan_aggregate(const float *grads, int n, int f, int64_t d, float *out, int32_t *selected_idx,
+                      void *stream)
+{
+    return mbulyan_aggregate_ex(grads, n, f, d, d, MB_MODE_SELECTED, 0, 0, out, selected_idx, nullptr, 0,
+                                stream);
+}
+
+int multikrum_aggregate(const float *grads, int n, int f, int64_t d, int64_t ld, float *out,
+                        uint8_t *selected_mask, void *workspace, size_t ws_bytes, void *stream)
+{
+    int rc = check_matrix(grads, n, d, ld);
+    if (rc != MB_OK) return rc;
+    if (!out || f < 0) return MB_EINVAL;
+    if (n < 2 * f + 3) return MB_EPRECOND;
+    Workspace ws;
+    rc = get_workspace(workspace, ws_bytes, n, d, &ws);
+    if (rc != MB_OK) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    rc = run_dist(grads, n, d, ld, ws.dist(), 0, MB_DIST_AUTO, ws, s);
+    if (rc != MB_OK) return rc;
+    {
+        StageTimer t(MB_STAGE_SELECT, s);
+        MB_HIP(mb::launch_select(ws.dist(), n, f, 1, nullptr, ws.sel(), ws.sets(), ws.m(), nullptr, s));
+    }
+    {
+        StageTimer t(MB_STAGE_COORD, s);
+        MB_HIP(mb::launch_masked_mean(grads, n, d, ld, ws.sets(), out, s));
+    }
+    if (selected_mask) MB_HIP(hipMemcpyAsync(selected_mask, ws.sets(), (size_t)n, hipMemcpyDeviceToDevice, s));
+    return MB_OK;
+}
+
+int coordwise_median(const float *grads, int n, int64_t d, int64_t ld, float *out, void *stream)
+{
+    const int rc = check_matrix(grads, n, d, ld);
+    if (rc != MB_OK) return rc;
+    if (!out) return MB_EINVAL;
+    StageTimer t(MB_STAGE_COORD, (hipStream_t)stream);
+    mb::CoordArgs a{grads, n, d, ld, nullptr, n, 1, 1, out};
+    MB_HIP(mb::launch_coord_selected(a, (hipStream_t)stream));
+    return MB_OK;
+}
+
+int mbulyan_timing_enable(int on)
+{
+    g_timing = on != 0;
+    return MB_OK;
+}
+
+int mbulyan_timing_reset(void)
+{
+    const int rc = drain_spans();
+    for (int i = 0; i < MB_NUM_STAGES; ++i) { g_ms[i] = 0; g_launches[i] = 0; }
+    return rc;
+}
+
+int mbulyan_timing_read(double *ms_per_stage, int64_t *launches_per_stage)
+{
+    const int rc = drain_spans();
+    if (rc != MB_OK) return rc;
+    for (int i = 0; i < MB_NUM_STAGES; ++i) {
+        if (ms_per_stage) ms_per_stage[i] = g_ms[i];
+        if (launches_per_stage) launches_per_stage[i] = g_launches[i];
+    }
+    return MB_OK;
+}
+
+int mbulyan_release(void)
+{
+    drain_spans();
+    std::lock_guard<std::mutex> lock(g_mu);
+    int cur = 0;
+    if (hipGetDevice(&cur) != hipSuccess) return hip_fail(hipGetLastError());
+    for (auto &kv : g_owned) {
+        if (!kv.second.ptr) continue;
+        hipSetDevice(kv.first);
+        hipDeviceSynchronize();
+        hipFree(kv.second.ptr);
+        kv.second = Owned();
+    }
+    hipSetDevice(cur);
+    return MB_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,184 @@
+// Coordinate-wise phase of multi-Bulyan (Algorithm 1, multi-Bulyan, after the
+// loop; Section II-B): per coordinate, the median of the theta extracted
+// values, the beta values closest to it, their average.
+//
+// One lane owns VEC consecutive coordinates.  It loads the theta values of
+// each (theta coalesced row streams per wave, 16-byte loads when aligned),
+// sorts them in registers with a compile-time network and picks the window
+// around the median.  Nothing is staged in LDS: the working set is theta
+// floats per coordinate and fits the register file for theta <= 64.
+//
+// This file is compiled once per group of 8 values of theta (-DMB_GROUP=g).
+#include <hip/hip_runtime.h>
+
+#include "mb_internal.hpp"
+#include "sortnet.hpp"
+
+#ifndef MB_GROUP
+#error "compile with -DMB_GROUP=0..7"
+#endif
+
+namespace mb {
+namespace {
+
+constexpr float kInf = __builtin_huge_valf();
+
+// v ascending.  K = number of values to take besides the median itself (odd THETA: beta-1; even:
+// beta).  Candidates: left L[a] = v[H-1-a], right R[b] = v[H+ODD+b]; order by (distance to the
+// median, left before right).  WIN = candidates per side the caller may need (K <= WIN).
+template <int THETA, int WIN>
+__device__ __forceinline__ float closest_sum(const float (&v)[THETA], int K, bool median_only)
+{
+    constexpr bool ODD = (THETA & 1) != 0;
+    constexpr int H = THETA / 2;
+    float med;
+    if constexpr (ODD) med = v[H];
+    else med = 0.5f * (v[H - 1] + v[H]);
+    if (median_only) return med;
+    float sum = ODD ? med : 0.0f;
+    if constexpr (H > 0) {
+        if constexpr (WIN < H || H <= 3) {
+            // greedy two-sided walk held in shift registers (small windows)
+            constexpr int W = WIN < H ? WIN : H;
+            constexpr int STEPS = WIN < H ? WIN : 2 * H;   // a limited window is only used with K <= WIN
+            float L[W + 1], R[W + 1];
+#pragma unroll
+            for (int a = 0; a < W; ++a) {
+                L[a] = v[H - 1 - a];
+                R[a] = v[H + (ODD ? 1 : 0) + a];
+            }
+            L[W] = -kInf;
+            R[W] = kInf;
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s) {
+                if (s < K) {
+                    const float dl = med - L[0];
+                    const float dr = R[0] - med;
+                    const bool left = dl <= dr;      // equal closeness: the smaller value
+                    sum += left ? L[0] : R[0];
+#pragma unroll
+                    for (int a = 0; a < W; ++a) {
+                        L[a] = left ? L[a + 1] : L[a];
+                        R[a] = left ? R[a] : R[a + 1];
+                    }
+                }
+            }
+        } else {
+            // rank of every candidate in the merged order, by counting
+            float dL[H], dR[H];
+#pragma unroll
+            for (int a = 0; a < H; ++a) {
+                dL[a] = med - v[H - 1 - a];
+                dR[a] = v[H + (ODD ? 1 : 0) + a] - med;
+            }
+#pragma unroll
+            for (int a = 0; a < H; ++a) {
+                int rank = a;
+#pragma unroll
+                for (int b = 0; b < H; ++b) rank += (dR[b] < dL[a]) ? 1 : 0;
+                sum += (rank < K) ? v[H - 1 - a] : 0.0f;
+            }
+#pragma unroll
+            for (int b = 0; b < H; ++b) {
+                int rank = b;
+#pragma unroll
+                for (int a = 0; a < H; ++a) rank += (dL[a] <= dR[b]) ? 1 : 0;
+                sum += (rank < K) ? v[H + (ODD ? 1 : 0) + b] : 0.0f;
+            }
+        }
+    }
+    return sum;
+}
+
+template <int THETA, int VEC, int WIN>
+__global__ __launch_bounds__(256) void coord_selected_kernel(
+    const float *__restrict__ G, int n, int64_t d, int64_t ld, const int32_t *__restrict__ sel,
+    int K, int median_only, float scale, float *__restrict__ out)
+{
+    const int64_t c0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * VEC;
+    if (c0 >= d) return;
+    float v[VEC][THETA];
+    bool bad = false;
+    const bool full = (c0 + VEC <= d);
+#pragma unroll
+    for (int t = 0; t < THETA; ++t) {
+        int r = sel ? sel[t] : t;
+        if ((unsigned)r >= (unsigned)n) { bad = true; r = 0; }
+        const float *p = G + (int64_t)r * ld + c0;
+        if constexpr (VEC == 4) {
+            if (full) {
+                const float4 x = *reinterpret_cast<const float4 *>(p);
+                v[0][t] = x.x; v[1][t] = x.y; v[2][t] = x.z; v[3][t] = x.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) v[e][t] = (c0 + e < d) ? p[e] : 0.0f;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) v[e][t] = (c0 + e < d) ? p[e] : 0.0f;
+        }
+    }
+    float res[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        sort_registers<THETA>(v[e]);
+        res[e] = closest_sum<THETA, WIN>(v[e], K, median_only != 0) * scale;
+        if (bad) res[e] = __int_as_float(0x7fc00000);
+    }
+    if constexpr (VEC == 4) {
+        if (full) {
+            *reinterpret_cast<float4 *>(out + c0) = make_float4(res[0], res[1], res[2], res[3]);
+            return;
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e)
+        if (c0 + e < d) out[c0 + e] = res[e];
+}
+
+template <int THETA>
+hipError_t launch_theta(const CoordArgs &a, hipStream_t s)
+{
+    constexpr bool ODD = (THETA & 1) != 0;
+    constexpr int H = THETA / 2;
+    const int K = a.median_only ? 0 : a.beta - (ODD ? 1 : 0);
+    const float scale = a.median_only ? 1.0f : 1.0f / (float)a.beta;
+    const bool aligned = ((uintptr_t)a.G % 16 == 0) && ((uintptr_t)a.out % 16 == 0) && (a.ld % 4 == 0);
+    const dim3 block(256);
+    if (aligned) {
+        const dim3 grid((unsigned)((a.d + 1023) / 1024));
+        if (K <= 2 && H > 2)
+            coord_selected_kernel<THETA, 4, 2><<<grid, block, 0, s>>>(a.G, a.n, a.d, a.ld, a.sel, K,
+                                                                      a.median_only, scale, a.out);
+        else
+            coord_selected_kernel<THETA, 4, (H > 0 ? H : 1)><<<grid, block, 0, s>>>(
+                a.G, a.n, a.d, a.ld, a.sel, K, a.median_only, scale, a.out);
+    } else {
+        const dim3 grid((unsigned)((a.d + 255) / 256));
+        coord_selected_kernel<THETA, 1, (H > 0 ? H : 1)><<<grid, block, 0, s>>>(
+            a.G, a.n, a.d, a.ld, a.sel, K, a.median_only, scale, a.out);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+#define MB_CAT2(a, b) a##b
+#define MB_CAT(a, b) MB_CAT2(a, b)
+
+hipError_t MB_CAT(launch_coord_group, MB_GROUP)(const CoordArgs &a, hipStream_t s)
+{
+    switch (a.theta - 8 * MB_GROUP) {
+        case 1: return launch_theta<8 * MB_GROUP + 1>(a, s);
+        case 2: return launch_theta<8 * MB_GROUP + 2>(a, s);
+        case 3: return launch_theta<8 * MB_GROUP + 3>(a, s);
+        case 4: return launch_theta<8 * MB_GROUP + 4>(a, s);
+        case 5: return launch_theta<8 * MB_GROUP + 5>(a, s);
+        case 6: return launch_theta<8 * MB_GROUP + 6>(a, s);
+        case 7: return launch_theta<8 * MB_GROUP + 7>(a, s);
+        case 8: return launch_theta<8 * MB_GROUP + 8>(a, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace mb

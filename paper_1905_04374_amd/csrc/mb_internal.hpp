@@ -1,0 +1,79 @@
+// Internal launch interface between the C-ABI layer and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mb {
+
+constexpr int kMaxN = 64;
+
+// ---- distance pass -------------------------------------------------------
+// Layout of one block's partial results, in doubles.
+//   direct: kDirectSlots = 36 row-block pairs x 64 entries
+//   gram:   NT(NB) tiles x 256 entries, NB = ceil(n/16), NT = NB(NB+1)/2
+constexpr int kDirectSlots = 36 * 64;
+inline int gram_blocks(int n) { return (n + 15) / 16; }
+inline int gram_slots(int n) { int nb = gram_blocks(n); return nb * (nb + 1) / 2 * 256; }
+
+// Number of workgroups the distance kernels are launched with.
+int dist_grid_blocks(int64_t d, int algo);
+
+hipError_t launch_dist_direct(const float *G, int n, int64_t d, int64_t ld, double *partials,
+                              int nblocks, hipStream_t s);
+hipError_t launch_dist_gram(const float *G, int n, int64_t d, int64_t ld, double *partials,
+                            int nblocks, hipStream_t s);
+// partials[nblocks][stride] -> reduced[0..slots) (fixed summation order), then -> dist[n*n]
+hipError_t launch_reduce(const double *partials, int nblocks, int stride, int slots, double *reduced,
+                         hipStream_t s);
+hipError_t launch_finalize_direct(const double *reduced, int n, double *dist, int accumulate, hipStream_t s);
+hipError_t launch_finalize_gram(const double *reduced, int n, double *dist, int accumulate, hipStream_t s);
+
+// ---- selection -----------------------------------------------------------
+// rounds >= 1: multi-Krum rounds; scores_out (may be null) gets the scores of the first round.
+hipError_t launch_select(const double *dist, int n, int f, int rounds, const uint8_t *active_in,
+                         int32_t *sel, uint8_t *agr_sets, int32_t *m_out, double *scores_out,
+                         hipStream_t s);
+
+// ---- coordinate pass -----------------------------------------------------
+struct CoordArgs {
+    const float *G;
+    int n;
+    int64_t d;
+    int64_t ld;
+    const int32_t *sel;  // theta row indices, or null = rows 0..theta-1
+    int theta;
+    int beta;            // number of averaged values; ignored when median_only
+    int median_only;     // output the median itself
+    float *out;
+};
+hipError_t launch_coord_selected(const CoordArgs &a, hipStream_t s);
+// one per translation unit, covering theta in [8g+1, 8g+8]
+#define MB_DECL_GROUP(g) hipError_t launch_coord_group##g(const CoordArgs &a, hipStream_t s);
+MB_DECL_GROUP(0) MB_DECL_GROUP(1) MB_DECL_GROUP(2) MB_DECL_GROUP(3)
+MB_DECL_GROUP(4) MB_DECL_GROUP(5) MB_DECL_GROUP(6) MB_DECL_GROUP(7)
+#undef MB_DECL_GROUP
+
+// Algorithm-1 mode: values are averages over row sets.
+struct CoordAlg1Args {
+    const float *G;
+    int n;
+    int64_t d;
+    int64_t ld;
+    const int32_t *sel;      // theta winners
+    const uint8_t *agr_sets; // theta x n
+    int theta;
+    int beta;
+    float *out;
+};
+hipError_t launch_coord_alg1(const CoordAlg1Args &a, hipStream_t s);
+// one per translation unit, covering theta in [16g+1, 16g+16]
+hipError_t launch_coord_alg1_group0(const CoordAlg1Args &a, hipStream_t s);
+hipError_t launch_coord_alg1_group1(const CoordAlg1Args &a, hipStream_t s);
+hipError_t launch_coord_alg1_group2(const CoordAlg1Args &a, hipStream_t s);
+hipError_t launch_coord_alg1_group3(const CoordAlg1Args &a, hipStream_t s);
+
+// out[c] = mean over rows r with mask[r] of G[r][c]
+hipError_t launch_masked_mean(const float *G, int n, int64_t d, int64_t ld, const uint8_t *mask,
+                              float *out, hipStream_t s);
+
+}  // namespace mb

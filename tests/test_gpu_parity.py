@@ -1,0 +1,339 @@
+"""Parity of the HIP library (through its C ABI) with the CPU oracle, step by step and end
+to end, on seeded inputs that span several tiles and a ragged tail.
+
+Bars: indices, masks and counts bit-exact; scores bit-exact when fed the oracle's distances;
+distances within 1e-6 of the squared norms involved (Gram form) or 2e-6 relative (direct
+form); outputs within 1e-5 of max(|reference|, mean |averaged values|).
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_1905_04374_amd as mb
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(*a):
+    print("[case]", *a, flush=True)
+    sys.stdout.flush()
+
+
+def gpu(x):
+    return torch.as_tensor(x).to(DEV)
+
+
+def assert_out_close(got, ref, scale, rtol=1e-5, what="out"):
+    got = got.detach().cpu().numpy() if torch.is_tensor(got) else got
+    err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+    tol = rtol * np.maximum(np.abs(ref), scale).astype(np.float64) + 1e-37
+    bad = np.flatnonzero(~(err <= tol))
+    assert bad.size == 0, (f"{what}: {bad.size} of {ref.size} beyond tolerance; first {bad[:5]}, "
+                           f"got {got[bad[:5]]}, ref {ref[bad[:5]]}, worst ratio {np.max(err / tol):.3g}")
+
+
+def assert_dist_close(got, G, ref, algo):
+    """|D - ref| <= 1e-6 (|x_i|^2 + |x_j|^2) for the Gram form, 2e-6 D for the direct form."""
+    got = got.cpu().numpy()
+    sq = (G.astype(np.float64) ** 2).sum(1)
+    if algo == mb.DIST_DIRECT:
+        tol = 2e-6 * ref + 1e-30
+    else:
+        tol = 1e-6 * (sq[:, None] + sq[None, :]) + 1e-30
+    err = np.abs(got - ref)
+    assert np.all(err <= tol), f"dist: worst err/tol {np.max(err / tol):.3g}"
+    assert np.array_equal(got, got.T) and np.all(np.diag(got) == 0.0)
+
+
+# ------------------------------------------------------------------ distances
+SHAPES = [(1, 5), (2, 1), (3, 31), (8, 128), (11, 1000), (16, 4096), (17, 4099), (19, 70001),
+          (32, 33333), (39, 65537), (48, 8191), (51, 20000), (64, 12345)]
+
+
+@pytest.mark.parametrize("algo", [mb.DIST_DIRECT, mb.DIST_GRAM])
+@pytest.mark.parametrize("n,d", SHAPES)
+def test_pairwise_sqdist(n, d, algo):
+    say("pairwise_sqdist", n, d, algo)
+    rng = np.random.default_rng(n * 1000 + d)
+    G = (rng.standard_normal((n, d)) + 0.5).astype(np.float32)
+    ref = O.pairwise_sqdist(G)
+    got = mb.pairwise_sqdist(gpu(G), algo=algo)
+    torch.cuda.synchronize()
+    assert_dist_close(got, G, ref, algo)
+
+
+@pytest.mark.parametrize("algo", [mb.DIST_DIRECT, mb.DIST_GRAM])
+def test_pairwise_sqdist_strided_unaligned_and_chunked(algo):
+    say("pairwise_sqdist strided", algo)
+    rng = np.random.default_rng(5)
+    wide = rng.standard_normal((13, 5003)).astype(np.float32)
+    gw = gpu(wide)
+    for lo, hi in [(0, 5003), (1, 4000), (3, 5002), (4, 1028)]:    # ld = 5003 (odd), shifted starts
+        ref = O.pairwise_sqdist(wide[:, lo:hi])
+        got = mb.pairwise_sqdist(gw[:, lo:hi], algo=algo)
+        assert_dist_close(got, wide[:, lo:hi], ref, algo)
+    # column chunks accumulate into one matrix
+    ref = O.pairwise_sqdist(wide)
+    D = None
+    for lo, hi in [(0, 1000), (1000, 1001), (1001, 5003)]:
+        chunk = gw[:, lo:hi].contiguous()
+        D = mb.pairwise_sqdist(chunk, dist=D, accumulate=D is not None, algo=algo)
+    assert_dist_close(D, wide, ref, algo)
+
+
+@pytest.mark.parametrize("algo", [mb.DIST_DIRECT, mb.DIST_GRAM])
+def test_identical_rows_tie_exactly(algo):
+    say("identical rows", algo)
+    rng = np.random.default_rng(11)
+    G = rng.standard_normal((39, 50021)).astype(np.float32)
+    G[33] = G[2]
+    G[17] = G[2]
+    G[38] = G[20]
+    D = mb.pairwise_sqdist(gpu(G), algo=algo).cpu().numpy()
+    assert D[2, 33] == 0.0 and D[2, 17] == 0.0 and D[17, 33] == 0.0 and D[20, 38] == 0.0
+    assert np.array_equal(D[2], D[33]) and np.array_equal(D[2], D[17]) and np.array_equal(D[20], D[38])
+
+
+@pytest.mark.parametrize("algo", [mb.DIST_DIRECT, mb.DIST_GRAM])
+def test_distance_pass_is_deterministic(algo):
+    say("determinism", algo)
+    G = gpu(W.make(2, "cpu", d=300_001))
+    a = mb.pairwise_sqdist(G, algo=algo).clone()
+    b = mb.pairwise_sqdist(G, algo=algo)
+    assert torch.equal(a, b)
+
+
+# --------------------------------------------------------- scores, selection
+@pytest.mark.parametrize("n,f", [(3, 0), (7, 1), (11, 2), (19, 4), (39, 9), (51, 12), (64, 15), (64, 0), (20, 7)])
+def test_krum_scores_and_selection_match_oracle(n, f):
+    say("select", n, f)
+    rng = np.random.default_rng(n * 100 + f)
+    G = rng.standard_normal((n, 50)).astype(np.float32)
+    if n >= 11:
+        G[n - 1] = G[n - 2]            # an exact tie inside the matrix
+    D = O.pairwise_sqdist(G)
+    Dg = gpu(D)
+    assert np.array_equal(mb.krum_scores(Dg, f).cpu().numpy(), O.krum_scores(D, f))
+    active = (rng.random(n) < 0.7).astype(np.uint8)
+    active[:2] = 1
+    assert np.array_equal(mb.krum_scores(Dg, f, gpu(active)).cpu().numpy(), O.krum_scores(D, f, active))
+    for theta in sorted({1, max(1, n - 2 * f - 2), max(1, n - 2 * f), n}):
+        ext, sets, m = O.multikrum_select(D, f, theta)
+        sel_g, sets_g, m_g = mb.multikrum_select(Dg, f, theta)
+        assert sel_g.cpu().numpy().tolist() == ext.tolist()
+        assert np.array_equal(sets_g.cpu().numpy(), sets)
+        assert m_g.cpu().numpy().tolist() == m.tolist()
+
+
+def test_selection_handles_nan_distances():
+    say("select nan")
+    D = O.pairwise_sqdist(np.random.default_rng(1).standard_normal((11, 20)).astype(np.float32))
+    Dn = D.copy()
+    Dn[4, :] = np.nan
+    Dn[:, 4] = np.nan
+    Dn[4, 4] = 0.0
+    Di = np.where(np.isnan(Dn), np.inf, Dn)
+    sel_g, _, _ = mb.multikrum_select(gpu(Dn), 2, 7)
+    assert sel_g.cpu().numpy().tolist() == O.multikrum_select(Di, 2, 7)[0].tolist()
+
+
+# ----------------------------------------------------------- coordinate pass
+@pytest.mark.parametrize("theta,beta,d", [
+    (1, 1, 100), (2, 1, 1000), (2, 2, 1000), (3, 1, 1000), (3, 3, 1024), (4, 2, 4097), (5, 3, 999),
+    (6, 4, 5000), (7, 3, 100_000), (7, 7, 5001), (8, 3, 5000), (9, 5, 5000), (11, 3, 70_001), (13, 1, 3000),
+    (15, 3, 50_000), (16, 6, 3000), (21, 3, 100_003), (21, 11, 3000), (27, 3, 40_000), (31, 31, 2000),
+    (32, 10, 2000), (33, 3, 2000), (47, 17, 1500), (63, 3, 1500), (64, 34, 1500), (64, 64, 1027), (64, 1, 1027),
+])
+def test_coordwise_selected(theta, beta, d):
+    say("coordwise_selected", theta, beta, d)
+    rng = np.random.default_rng(theta * 1000 + beta)
+    n = min(64, theta + 5)
+    G = rng.standard_normal((n, d)).astype(np.float32)
+    G[:, : d // 4] = rng.integers(-4, 5, size=(n, d // 4))      # exact ties and duplicates
+    ext = rng.permutation(n)[:theta].astype(np.int32)
+    ref, scale = O.coordwise_selected(G, ext, beta, want_scale=True)
+    got = mb.coordwise_trimmed_avg(gpu(G), gpu(ext), beta)
+    assert_out_close(got, ref, scale)
+
+
+def test_coordwise_selected_strided_unaligned():
+    say("coordwise strided")
+    rng = np.random.default_rng(8)
+    wide = rng.standard_normal((15, 6007)).astype(np.float32)
+    gw = gpu(wide)
+    ext = rng.permutation(15)[:9].astype(np.int32)
+    for lo, hi in [(0, 6007), (1, 6000), (2, 4099), (4, 1028)]:
+        ref, scale = O.coordwise_selected(wide[:, lo:hi], ext, 5, want_scale=True)
+        out = torch.empty(hi - lo + 3, device=DEV)[3 * (lo % 2):][: hi - lo]     # sometimes misaligned out
+        mb.coordwise_trimmed_avg(gw[:, lo:hi], gpu(ext), 5, out=out)
+        assert_out_close(out, ref, scale)
+
+
+def test_coordwise_rejects_bad_indices_with_nan():
+    say("coordwise bad idx")
+    G = gpu(np.ones((7, 100), np.float32))
+    out = mb.coordwise_trimmed_avg(G, gpu(np.array([0, 1, 9], np.int32)), 1)
+    assert torch.isnan(out).all()
+
+
+def test_coordwise_median():
+    say("median")
+    rng = np.random.default_rng(9)
+    for n in (1, 2, 7, 11, 20, 39, 64):
+        G = rng.standard_normal((n, 3001)).astype(np.float32)
+        ref = O.coordwise_median(G)
+        got = mb.coordwise_median(gpu(G)).cpu().numpy()
+        assert_out_close(got, ref, np.abs(ref), rtol=1e-6, what=f"median n={n}")
+        if n % 2:
+            assert np.array_equal(got, ref)
+
+
+def alg1_compare(got, ref, scale, margin, alt, a_scale):
+    """Accept the reference, or, where the decision margin is below the rounding noise of
+    an fp32 evaluation of the multi-Krum averages, the other candidate."""
+    got = got.cpu().numpy()
+    tol = 1e-5 * np.maximum(np.abs(ref), scale) + 1e-37
+    ok = np.abs(got - ref) <= tol
+    close_call = margin <= 4e-6 * a_scale
+    ok_alt = close_call & (np.abs(got - alt) <= 1e-5 * np.maximum(np.abs(alt), scale) + 1e-37)
+    assert np.all(ok | ok_alt), f"{np.sum(~(ok | ok_alt))} coordinates differ beyond an ambiguous choice"
+    return int(np.sum(~ok & ok_alt))
+
+
+@pytest.mark.parametrize("n,f,d", [(7, 1, 3000), (11, 2, 100_000), (13, 2, 5001), (19, 4, 30_000), (39, 9, 20_011),
+                                   (51, 12, 9000), (64, 15, 3000), (64, 0, 2000)])
+def test_coordwise_alg1(n, f, d):
+    say("coordwise_alg1", n, f, d)
+    rng = np.random.default_rng(n * 7 + f)
+    G = rng.standard_normal((n, d)).astype(np.float32)
+    theta, beta = O.params(n, f, O.MODE_ALG1)
+    D = O.pairwise_sqdist(G)
+    ext, sets, m = O.multikrum_select(D, f, theta)
+    ref, scale, margin, alt = O.coordwise_alg1(G, ext, sets, beta, want_extra=True)
+    got = mb.coordwise_trimmed_avg(gpu(G), gpu(ext), beta, agr_sets=gpu(sets))
+    flips = alg1_compare(got, ref, scale, margin, alt, np.abs(G).max(0))
+    assert flips <= max(2, d // 1000)
+
+
+# ------------------------------------------------------------------ whole GAR
+@pytest.mark.parametrize("algo", [mb.DIST_DIRECT, mb.DIST_GRAM])
+@pytest.mark.parametrize("cfg,d,placement", [(1, None, "tail"), (1, None, "random"), (2, None, "tail"),
+                                             (3, 300_007, "tail"), (4, 200_003, "random"), (5, 100_001, "tail")])
+def test_aggregate_matches_oracle(cfg, d, placement, algo):
+    say("aggregate", cfg, d, placement, algo)
+    s = W.spec(cfg)
+    Gt = W.make(cfg, DEV, d=d, placement=placement)
+    G = Gt.cpu().numpy()
+    ref, ext = O.mbulyan(G, s["f"])
+    theta, beta = O.params(s["n"], s["f"])
+    _, scale = O.coordwise_selected(G, ext, beta, want_scale=True)
+    mb.mbulyan_set_dist_algo(algo)
+    try:
+        out, sel = mb.mbulyan_aggregate(Gt, s["f"])
+        torch.cuda.synchronize()
+    finally:
+        mb.mbulyan_set_dist_algo(mb.DIST_AUTO)
+    assert sel.cpu().numpy().tolist() == ext.tolist()
+    assert_out_close(out, ref, scale)
+    out2, sel2 = mb.mbulyan_aggregate(Gt, s["f"])
+    if algo == mb.DIST_GRAM:
+        assert torch.equal(out, out2) and torch.equal(sel, sel2)      # run-to-run bit-identical
+
+
+@pytest.mark.parametrize("cfg,d", [(1, None), (2, 400_000), (4, 100_003)])
+def test_aggregate_alg1_mode(cfg, d):
+    say("aggregate alg1", cfg, d)
+    s = W.spec(cfg)
+    n, f = s["n"], s["f"]
+    Gt = W.make(cfg, DEV, d=d)
+    G = Gt.cpu().numpy()
+    theta, beta = O.params(n, f, O.MODE_ALG1)
+    D = O.pairwise_sqdist(G)
+    ext, sets, m = O.multikrum_select(D, f, theta)
+    ref, scale, margin, alt = O.coordwise_alg1(G, ext, sets, beta, want_extra=True)
+    ws = torch.empty(mb.mbulyan_workspace_bytes(n, G.shape[1]), dtype=torch.uint8, device=DEV)
+    out, sel = mb.mbulyan_aggregate_ex(Gt, f, mode=mb.MODE_ALG1, workspace=ws)
+    assert sel.cpu().numpy().tolist() == ext.tolist()
+    flips = alg1_compare(out, ref, scale, margin, alt, np.abs(G).max(0))
+    assert flips <= max(2, G.shape[1] // 1000)
+
+
+def test_aggregate_chunked_equals_whole():
+    say("chunked")
+    s = W.spec(5)
+    d = 150_001
+    Gt = W.make(5, DEV, d=d)
+    G = Gt.cpu().numpy()
+    ref, ext = O.mbulyan(G, s["f"])
+    _, scale = O.coordwise_selected(G, ext, 3, want_scale=True)
+    cuts = [0, 40_000, 40_001, 100_004, d]
+    chunks = [Gt[:, a:b].contiguous() for a, b in zip(cuts[:-1], cuts[1:])]
+    outs, sel = mb.mbulyan_aggregate_chunked(chunks, s["f"])
+    assert sel.cpu().numpy().tolist() == ext.tolist()
+    assert_out_close(torch.cat(outs), ref, scale)
+    views = [Gt[:, a:b] for a, b in zip(cuts[:-1], cuts[1:])]            # ld = d views, unaligned starts
+    outs2, sel2 = mb.mbulyan_aggregate_chunked(views, s["f"])
+    assert sel2.cpu().numpy().tolist() == ext.tolist()
+    assert_out_close(torch.cat(outs2), ref, scale)
+
+
+def test_explicit_theta_beta_and_no_byzantine():
+    say("explicit theta/beta, f=0")
+    rng = np.random.default_rng(3)
+    G = rng.standard_normal((9, 10_001)).astype(np.float32)
+    out, sel = mb.mbulyan_aggregate(gpu(G), 0)
+    assert sorted(sel.cpu().numpy().tolist()) == list(range(9))
+    mean = G.astype(np.float64).mean(0)
+    assert_out_close(out, mean.astype(np.float32), np.abs(G).mean(0))
+    out, sel = mb.mbulyan_aggregate_ex(gpu(G), 1, theta=5, beta=2)
+    D = O.pairwise_sqdist(G)
+    ext, _, _ = O.multikrum_select(D, 1, 5)
+    ref, scale = O.coordwise_selected(G, ext, 2, want_scale=True)
+    assert sel.cpu().numpy().tolist() == ext.tolist()
+    assert_out_close(out, ref, scale)
+
+
+def test_multikrum_aggregate():
+    say("multikrum_aggregate")
+    for cfg, d in [(1, 50_001), (2, 20_000)]:
+        s = W.spec(cfg)
+        Gt = W.make(cfg, DEV, d=d)
+        G = Gt.cpu().numpy()
+        ref, mask = O.multikrum_aggregate(G, s["f"])
+        out, mask_g = mb.multikrum_aggregate(Gt, s["f"])
+        assert np.array_equal(mask_g.cpu().numpy(), mask)
+        assert_out_close(out, ref, np.abs(G[mask.astype(bool)]).mean(0))
+
+
+def test_stream_argument_is_honoured():
+    say("stream")
+    s = W.spec(1)
+    Gt = W.make(1, DEV, d=65_536)
+    ref, ext = O.mbulyan(Gt.cpu().numpy(), s["f"])
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(st):
+        out, sel = mb.mbulyan_aggregate(Gt, s["f"])
+    st.synchronize()
+    assert sel.cpu().numpy().tolist() == ext.tolist()
+    assert np.allclose(out.cpu().numpy(), ref, rtol=1e-5, atol=1e-6)
+
+
+def test_timing_hooks():
+    say("timing")
+    Gt = W.make(1, DEV, d=65_536)
+    mb.mbulyan_timing_reset()
+    mb.mbulyan_timing_enable(True)
+    for _ in range(3):
+        mb.mbulyan_aggregate(Gt, 2)
+    mb.mbulyan_timing_enable(False)
+    t = mb.mbulyan_timing_read()
+    assert t["dist"][1] == 3 and t["coord"][1] == 3 and t["select"][1] == 3 and t["reduce"][1] == 3
+    assert all(0 < t[k][0] < 1000 for k in t)
+    mb.mbulyan_timing_reset()
+    assert mb.mbulyan_timing_read()["dist"] == (0.0, 0)
