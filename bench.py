@@ -26,6 +26,7 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="workload 1..5 (default: the one the metric is quoted on)")
     ap.add_argument("--d", type=int, default=None, help="override the number of coordinates")
     ap.add_argument("--mode", choices=["selected", "alg1"], default="selected")
+    ap.add_argument("--dist-algo", choices=["auto", "direct", "gram"], default="auto")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=1 << 24, help="coordinates the oracle is timed on")
     a = ap.parse_args()
@@ -42,6 +43,7 @@ def main():
     import workloads as W
 
     dev = "cuda:0"
+    mb.mbulyan_set_dist_algo({"auto": mb.DIST_AUTO, "direct": mb.DIST_DIRECT, "gram": mb.DIST_GRAM}[a.dist_algo])
     spec = W.spec(a.config)
     n, f = spec["n"], spec["f"]
     d = a.d or spec["d"]
@@ -91,7 +93,7 @@ def main():
     dist_avg_s = dist_ms / 1e3 / max(dist_launches, 1)
     dist_bytes = in_bytes / nchunks
     achieved = dist_bytes / dist_avg_s / 1e9
-    roofline = {"kernel": "dist_gram_kernel", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+    roofline = {"kernel": "dist_direct_kernel" if a.dist_algo == "direct" else "dist_gram_kernel", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                 "avg_launch_ms": round(dist_avg_s * 1e3, 4), "launches": dist_launches}
     nb = (n + 15) // 16

@@ -293,6 +293,9 @@ void orc_coordwise_selected(const float *G, int64_t d, int64_t ld,
  * (fp64 sum in ascending r, divided by m_t, rounded to fp32: the precision
  * the method works in); out[c] = average of the beta values G^agr[.][c]
  * closest to M[c].
+ * scale (may be NULL): the largest, over the rounds, of the mean absolute value
+ * of the gradients averaged into G^agr[t][c]: the conditioning scale of an
+ * fp32 evaluation of those averages.
  * margin (may be NULL): gap, in fp32, between the beta-th and the (beta+1)-th
  * smallest |G^agr - M|; alt (may be NULL): the output if the (beta+1)-th
  * replaced the beta-th.  A comparison may accept alt where margin is below
@@ -312,18 +315,23 @@ void orc_coordwise_alg1(const float *G, int n, int64_t d, int64_t ld,
         for (int t = 0; t < theta; ++t) e[t] = G[(int64_t)ext[t] * ld + c];
         sort_floats(e, theta);
         float med = median_sorted(e, theta);
+        double cond = 0.0;
         for (int t = 0; t < theta; ++t) {
-            double s = 0.0;
+            double s = 0.0, sabs = 0.0;
             int m = 0;
             for (int r = 0; r < n; ++r)
-                if (agr_sets[t * n + r]) { s += (double)G[(int64_t)r * ld + c]; ++m; }
+                if (agr_sets[t * n + r]) {
+                    s += (double)G[(int64_t)r * ld + c];
+                    sabs += fabs((double)G[(int64_t)r * ld + c]);
+                    ++m;
+                }
             a[t] = (m > 0) ? (float)(s / (double)m) : 0.0f;
+            if (m > 0 && sabs / (double)m > cond) cond = sabs / (double)m;
         }
         sort_floats(a, theta);
-        double sa;
-        double s = pick_closest(a, theta, med, beta, &sa, picked);
+        double s = pick_closest(a, theta, med, beta, NULL, picked);
         out[c] = (float)(s / (double)beta);
-        if (scale) scale[c] = (float)(sa / (double)beta);
+        if (scale) scale[c] = (float)cond;
         if (margin || alt) {
             /* worst picked and best not-picked, by (delta, position) */
             int worst = -1, next = -1;
