@@ -28,6 +28,9 @@ def main():
     ap.add_argument("--mode", choices=["selected", "alg1"], default="selected")
     ap.add_argument("--dist-algo", choices=["auto", "direct", "gram"], default="auto")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="also run one plain device copy of this many MiB before the timed region "
+                         "(a kernel of known traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--cpu-sample", type=int, default=1 << 24, help="coordinates the oracle is timed on")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -69,6 +72,12 @@ def main():
         else:
             mb.mbulyan_aggregate_chunked(chunks, f, mode=mode, outs=outs, selected_idx=sel, workspace=ws)
 
+    if a.copy_calibration:
+        src = torch.ones(a.copy_calibration << 18, device=dev, dtype=torch.float32)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()
