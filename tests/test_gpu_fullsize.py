@@ -1,0 +1,129 @@
+"""Parity at the full sizes of the workloads, in the launch configuration bench.py times
+(mbulyan_aggregate_ex with a caller workspace; the chunked driver for workload 5).
+
+Workloads 3 and 4 are compared with the oracle element by element over the whole output.
+Workload 5 (n=51, d=1e9 in 4 chunks, 204 GB) runs at one tenth of its d by default and at
+full size when MB_FULL_CFG5=1 (the oracle then needs several minutes of host time).
+"""
+import os
+import sys
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_1905_04374_amd as mb
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(*a):
+    print("[case]", *a, flush=True)
+    sys.stdout.flush()
+
+
+def check_chunk(got, ref, scale):
+    err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+    tol = 1e-5 * np.maximum(np.abs(ref), scale).astype(np.float64) + 1e-37
+    worst = float(np.max(err / tol))
+    assert worst <= 1.0, f"worst err/tol {worst:.3g} at {int(np.argmax(err / tol))}"
+    return worst
+
+
+def check_separation(D, f, theta, ext):
+    """Scores of every round: the winner beats every gradient that is not a bit-identical copy
+    of it by more than 1e-3 relative (otherwise the extracted list would hang on rounding)."""
+    _, _, _, log = O.multikrum_select(D, f, theta, want_scores=True)
+    worst = np.inf
+    for t in range(theta):
+        S, w = log[t], ext[t]
+        for j in np.flatnonzero(np.isfinite(S)):
+            if j != w and D[w, j] != 0.0:
+                worst = min(worst, (S[j] - S[w]) / max(S[j], 1e-300))
+    assert worst > 1e-3, f"scores separated by only {worst:.2e}"
+    return worst
+
+
+@pytest.mark.parametrize("cfg", [3, 4])
+def test_full_size_single_buffer(cfg):
+    s = W.spec(cfg)
+    n, f, d = s["n"], s["f"], s["d"]
+    say("full size", cfg, n, f, d)
+    theta, beta = O.params(n, f)
+    Gt = W.make(cfg, DEV)
+    ws = torch.empty(mb.mbulyan_workspace_bytes(n, d), dtype=torch.uint8, device=DEV)
+    out, sel = mb.mbulyan_aggregate_ex(Gt, f, workspace=ws)
+    Dg = mb.pairwise_sqdist(Gt, workspace=ws).cpu().numpy()
+    torch.cuda.synchronize()
+    say("gpu done; copying", round(4e-9 * n * d, 1), "GB to the host")
+    G = np.empty((n, d), np.float32)
+    for r in range(n):
+        G[r] = Gt[r].cpu().numpy()
+    got = out.cpu().numpy()
+    sel = sel.cpu().numpy()
+    del Gt, out
+    torch.cuda.empty_cache()
+    t0 = time.time()
+    D = O.pairwise_sqdist(G)
+    say("oracle distances", round(time.time() - t0, 1), "s")
+    ext, _, _ = O.multikrum_select(D, f, theta)
+    gap = check_separation(D, f, theta, ext)
+    assert sel.tolist() == ext.tolist()
+    sq = np.array([float(np.dot(G[r, :1 << 20].astype(np.float64), G[r, :1 << 20])) for r in range(n)]) * (d / (1 << 20))
+    assert np.all(np.abs(Dg - D) <= 1e-6 * (sq[:, None] + sq[None, :]))
+    rel = np.abs(Dg - D)[D > 0] / D[D > 0]
+    t0 = time.time()
+    worst = 0.0
+    step = 1 << 24
+    for lo in range(0, d, step):                       # oracle coordinate phase in slabs
+        hi = min(d, lo + step)
+        ref, scale = O.coordwise_selected(G[:, lo:hi], ext, beta, want_scale=True)
+        worst = max(worst, check_chunk(got[lo:hi], ref, scale))
+    say(f"cfg {cfg}: selected {ext.tolist()}, score gap {gap:.2e}, dist rel err max {rel.max():.2e}, "
+        f"out worst err/tol {worst:.3g}, oracle coordinate phase {time.time() - t0:.1f} s")
+
+
+def test_full_size_chunked():
+    s = W.spec(5)
+    n, f, nchunks = s["n"], s["f"], s["chunks"]
+    d = s["d"] if os.environ.get("MB_FULL_CFG5") == "1" else s["d"] // 10
+    say("chunked", n, f, d, nchunks)
+    theta, beta = O.params(n, f)
+    bounds = [d * k // nchunks for k in range(nchunks + 1)]
+    chunks = []
+    for k in range(nchunks):
+        g = torch.empty(n, bounds[k + 1] - bounds[k], device=DEV, dtype=torch.float32)
+        W.fill(5, g, bounds[k])
+        chunks.append(g)
+    ws = torch.empty(mb.mbulyan_workspace_bytes(n, max(c.shape[1] for c in chunks)), dtype=torch.uint8, device=DEV)
+    outs, sel = mb.mbulyan_aggregate_chunked(chunks, f, workspace=ws)
+    torch.cuda.synchronize()
+    sel = sel.cpu().numpy()
+    D = np.zeros((n, n))
+    host = np.empty((n, chunks[0].shape[1]), np.float32)
+    for k in range(nchunks):                           # distances accumulate over the chunks
+        w = chunks[k].shape[1]
+        for r in range(n):
+            host[r, :w] = chunks[k][r].cpu().numpy()
+        O.pairwise_sqdist(host[:, :w], D)
+        say("oracle distances of chunk", k)
+    ext, _, _ = O.multikrum_select(D, f, theta)
+    gap = check_separation(D, f, theta, ext)
+    assert sel.tolist() == ext.tolist()
+    worst = 0.0
+    for k in range(nchunks):
+        w = chunks[k].shape[1]
+        for r in range(n):
+            host[r, :w] = chunks[k][r].cpu().numpy()
+        got = outs[k].cpu().numpy()
+        step = 1 << 24
+        for lo in range(0, w, step):
+            hi = min(w, lo + step)
+            ref, scale = O.coordwise_selected(host[:, lo:hi], ext, beta, want_scale=True)
+            worst = max(worst, check_chunk(got[lo:hi], ref, scale))
+        say("oracle coordinate phase of chunk", k)
+    say(f"cfg 5 (d={d}): selected {ext.tolist()}, score gap {gap:.2e}, out worst err/tol {worst:.3g}")
