@@ -26,7 +26,7 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="workload 1..5 (default: the one the metric is quoted on)")
     ap.add_argument("--d", type=int, default=None, help="override the number of coordinates")
     ap.add_argument("--mode", choices=["selected", "alg1"], default="selected")
-    ap.add_argument("--dist-algo", choices=["auto", "direct", "gram"], default="auto")
+    ap.add_argument("--dist-algo", choices=["auto", "direct", "gram", "gram_bf16"], default="auto")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run one plain device copy of this many MiB before the timed region "
@@ -46,7 +46,8 @@ def main():
     import workloads as W
 
     dev = "cuda:0"
-    mb.mbulyan_set_dist_algo({"auto": mb.DIST_AUTO, "direct": mb.DIST_DIRECT, "gram": mb.DIST_GRAM}[a.dist_algo])
+    mb.mbulyan_set_dist_algo({"auto": mb.DIST_AUTO, "direct": mb.DIST_DIRECT, "gram": mb.DIST_GRAM,
+                              "gram_bf16": mb.DIST_GRAM_BF16}[a.dist_algo])
     spec = W.spec(a.config)
     n, f = spec["n"], spec["f"]
     d = a.d or spec["d"]

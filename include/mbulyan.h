@@ -63,6 +63,10 @@ extern "C" {
 #define MB_DIST_DIRECT 1 /* sum of (x_i - x_j)^2 on the vector ALU, fp32 partial sums */
 #define MB_DIST_GRAM 2   /* Gram matrix on the fp32 matrix cores (MFMA), fp64 running sums,
                             D_ij = G_ii + G_jj - 2 G_ij in fp64 */
+#define MB_DIST_GRAM_BF16 3 /* the same Gram matrix on the bf16 matrix cores: every fp32 value is
+                            split exactly into three bf16 pieces and the six significant piece
+                            products are accumulated in fp32 (error of the order of one fp32
+                            rounding per product) */
 
 const char *mbulyan_strerror(int status);
 /* hipError_t (as int) of the last failing HIP call on this thread, 0 if none */

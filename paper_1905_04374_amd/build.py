@@ -41,6 +41,7 @@ def units():
     """(object name, source, extra flags)"""
     u = [("api.o", "api.hip", []),
          ("dist.o", "dist.hip", []),
+         ("dist_gram.o", "dist_gram.hip", []),
          ("select.o", "select.hip", []),
          ("rowops.o", "rowops.hip", [])]
     for g in range(8):
@@ -76,9 +77,13 @@ def build(jobs: int = 8, force: bool = True, verbose: bool = False) -> str:
             raise RuntimeError(f"hipcc failed on {src} ({obj}):\n{r.stdout}\n{r.stderr}")
         return objp
 
-    # biggest units first so the pool stays busy
-    order = sorted(units(), key=lambda u: (not u[0].startswith("coordwise"), u[0]), reverse=False)
-    order.sort(key=lambda u: -int(u[0].split("_g")[1].split(".")[0]) if "_g" in u[0] else 1)
+    # biggest units first so the pool stays busy: the sorting networks for large theta
+    def weight(u):
+        name = u[0]
+        if name.startswith("coordwise") and name[-4] == "g":
+            return -int(name[-3])
+        return 1
+    order = sorted(units(), key=weight)
     with ThreadPoolExecutor(max_workers=max(1, jobs)) as pool:
         objs = list(pool.map(compile_one, order))
     cmd = [cc, f"--offload-arch={ARCH}", "-shared", "-fPIC", "-o", LIB, *objs]

@@ -49,7 +49,7 @@ struct Workspace {
 int resolve_algo(int algo)
 {
     if (algo == MB_DIST_AUTO) algo = g_dist_algo;
-    if (algo == MB_DIST_AUTO) algo = MB_DIST_GRAM;
+    if (algo == MB_DIST_AUTO) algo = MB_DIST_GRAM_BF16;   // fastest at every n measured (11..51)
     return algo;
 }
 
@@ -123,12 +123,12 @@ struct StageTimer {
         if (!on) return;
         sp.stage = stage;
         if (hipEventCreate(&sp.a) != hipSuccess || hipEventCreate(&sp.b) != hipSuccess) { on = false; return; }
-        hipEventRecord(sp.a, s);
+        (void)hipEventRecord(sp.a, s);
     }
     ~StageTimer()
     {
         if (!on) return;
-        hipEventRecord(sp.b, s);
+        (void)hipEventRecord(sp.b, s);
         g_spans.push_back(sp);
     }
 };
@@ -139,8 +139,8 @@ int drain_spans()
         float ms = 0.f;
         hipError_t e = hipEventSynchronize(sp.b);
         if (e == hipSuccess) e = hipEventElapsedTime(&ms, sp.a, sp.b);
-        hipEventDestroy(sp.a);
-        hipEventDestroy(sp.b);
+        (void)hipEventDestroy(sp.a);
+        (void)hipEventDestroy(sp.b);
         if (e != hipSuccess) { g_spans.clear(); return hip_fail(e); }
         g_ms[sp.stage] += ms;
         g_launches[sp.stage] += 1;
@@ -162,7 +162,7 @@ int run_dist(const float *grads, int n, int64_t d, int64_t ld, double *dist, int
              const Workspace &ws, hipStream_t s)
 {
     algo = resolve_algo(algo);
-    const int nblocks = mb::dist_grid_blocks(d, algo);
+    int nblocks = mb::dist_grid_blocks(d, algo);
     if (algo == MB_DIST_DIRECT) {
         const int nb = (n + 7) / 8, slots = nb * (nb + 1) / 2 * 64;
         {
@@ -172,15 +172,15 @@ int run_dist(const float *grads, int n, int64_t d, int64_t ld, double *dist, int
         StageTimer t(MB_STAGE_REDUCE, s);
         MB_HIP(mb::launch_reduce(ws.partials(), nblocks, mb::kDirectSlots, slots, ws.reduced(), s));
         MB_HIP(mb::launch_finalize_direct(ws.reduced(), n, dist, accumulate, s));
-    } else if (algo == MB_DIST_GRAM) {
+    } else if (algo == MB_DIST_GRAM || algo == MB_DIST_GRAM_BF16) {
         const int slots = mb::gram_slots(n);
         {
             StageTimer t(MB_STAGE_DIST, s);
-            MB_HIP(mb::launch_dist_gram(grads, n, d, ld, ws.partials(), nblocks, s));
+            MB_HIP(mb::launch_dist_gram(grads, n, d, ld, ws.partials(), algo == MB_DIST_GRAM_BF16, &nblocks, s));
         }
         StageTimer t(MB_STAGE_REDUCE, s);
         MB_HIP(mb::launch_reduce(ws.partials(), nblocks, slots, slots, ws.reduced(), s));
-        MB_HIP(mb::launch_finalize_gram(ws.reduced(), n, dist, accumulate, s));
+        MB_HIP(mb::launch_finalize_gram(ws.reduced(), n, dist, accumulate, algo == MB_DIST_GRAM_BF16, s));
     } else {
         return MB_EINVAL;
     }
@@ -281,7 +281,7 @@ int mbulyan_workspace_bytes(int n, int64_t d, size_t *bytes)
 
 int mbulyan_set_dist_algo(int algo)
 {
-    if (algo != MB_DIST_AUTO && algo != MB_DIST_DIRECT && algo != MB_DIST_GRAM) return MB_EINVAL;
+    if (algo < MB_DIST_AUTO || algo > MB_DIST_GRAM_BF16) return MB_EINVAL;
     g_dist_algo = algo;
     return MB_OK;
 }
@@ -292,7 +292,7 @@ int pairwise_sqdist(const float *grads, int n, int64_t d, int64_t ld, double *di
     int rc = check_matrix(grads, n, d, ld);
     if (rc != MB_OK) return rc;
     if (!dist) return MB_EINVAL;
-    if (algo != MB_DIST_AUTO && algo != MB_DIST_DIRECT && algo != MB_DIST_GRAM) return MB_EINVAL;
+    if (algo < MB_DIST_AUTO || algo > MB_DIST_GRAM_BF16) return MB_EINVAL;
     Workspace ws;
     rc = get_workspace(workspace, ws_bytes, n, d, &ws);
     if (rc != MB_OK) return rc;
@@ -467,12 +467,12 @@ int mbulyan_release(void)
     if (hipGetDevice(&cur) != hipSuccess) return hip_fail(hipGetLastError());
     for (auto &kv : g_owned) {
         if (!kv.second.ptr) continue;
-        hipSetDevice(kv.first);
-        hipDeviceSynchronize();
-        hipFree(kv.second.ptr);
+        (void)hipSetDevice(kv.first);
+        (void)hipDeviceSynchronize();
+        (void)hipFree(kv.second.ptr);
         kv.second = Owned();
     }
-    hipSetDevice(cur);
+    (void)hipSetDevice(cur);
     return MB_OK;
 }
 

@@ -3,7 +3,7 @@
 // values, the beta values closest to it, their average.
 //
 // One lane owns VEC consecutive coordinates.  It loads the theta values of
-// each (theta coalesced row streams per wave, 16-byte loads when aligned),
+// each (theta coalesced row streams per wave, 8-byte non-temporal loads when aligned),
 // sorts them in registers with a compile-time network and picks the window
 // around the median.  Nothing is staged in LDS: the working set is theta
 // floats per coordinate and fits the register file for theta <= 64.
@@ -90,33 +90,53 @@ __device__ __forceinline__ float closest_sum(const float (&v)[THETA], int K, boo
     return sum;
 }
 
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+#ifndef MB_COORD_MINBLOCKS
+#define MB_COORD_MINBLOCKS 1
+#endif
+
 template <int THETA, int VEC, int WIN>
-__global__ __launch_bounds__(256) void coord_selected_kernel(
+__global__ __launch_bounds__(256, MB_COORD_MINBLOCKS) void coord_selected_kernel(
     const float *__restrict__ G, int n, int64_t d, int64_t ld, const int32_t *__restrict__ sel,
     int K, int median_only, float scale, float *__restrict__ out)
 {
     const int64_t c0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * VEC;
     if (c0 >= d) return;
-    float v[VEC][THETA];
+    // row offsets of the theta extracted gradients (uniform: scalar loads), validated
+    int64_t roff[THETA];
     bool bad = false;
-    const bool full = (c0 + VEC <= d);
 #pragma unroll
     for (int t = 0; t < THETA; ++t) {
         int r = sel ? sel[t] : t;
         if ((unsigned)r >= (unsigned)n) { bad = true; r = 0; }
-        const float *p = G + (int64_t)r * ld + c0;
-        if constexpr (VEC == 4) {
-            if (full) {
-                const float4 x = *reinterpret_cast<const float4 *>(p);
-                v[0][t] = x.x; v[1][t] = x.y; v[2][t] = x.z; v[3][t] = x.w;
-            } else {
+        roff[t] = (int64_t)r * ld;
+    }
+    float v[VEC][THETA];
+    const bool full = (c0 + VEC <= d);
+    if (VEC == 4 && full) {
+        // the input is read once and never again: non-temporal loads keep it from displacing
+        // anything useful in the caches
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) v[e][t] = (c0 + e < d) ? p[e] : 0.0f;
-            }
-        } else {
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) v[e][t] = (c0 + e < d) ? p[e] : 0.0f;
+        for (int t = 0; t < THETA; ++t) {
+            const floatx4 x = __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(G + roff[t] + c0));
+            v[0][t] = x.x; v[1 % VEC][t] = x.y; v[2 % VEC][t] = x.z; v[3 % VEC][t] = x.w;
         }
+    } else if (VEC == 2 && full) {
+#pragma unroll
+        for (int t = 0; t < THETA; ++t) {
+            const floatx2 x = __builtin_nontemporal_load(reinterpret_cast<const floatx2 *>(G + roff[t] + c0));
+            v[0][t] = x.x; v[1 % VEC][t] = x.y;
+        }
+    } else if (VEC == 1) {
+#pragma unroll
+        for (int t = 0; t < THETA; ++t) v[0][t] = __builtin_nontemporal_load(G + roff[t] + c0);
+    } else {
+#pragma unroll
+        for (int t = 0; t < THETA; ++t)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) v[e][t] = (c0 + e < d) ? G[roff[t] + c0 + e] : 0.0f;
     }
     float res[VEC];
 #pragma unroll
@@ -125,11 +145,15 @@ __global__ __launch_bounds__(256) void coord_selected_kernel(
         res[e] = closest_sum<THETA, WIN>(v[e], K, median_only != 0) * scale;
         if (bad) res[e] = __int_as_float(0x7fc00000);
     }
-    if constexpr (VEC == 4) {
-        if (full) {
-            *reinterpret_cast<float4 *>(out + c0) = make_float4(res[0], res[1], res[2], res[3]);
-            return;
-        }
+    if (VEC == 4 && full) {
+        const floatx4 o = {res[0], res[1 % VEC], res[2 % VEC], res[3 % VEC]};
+        __builtin_nontemporal_store(o, reinterpret_cast<floatx4 *>(out + c0));
+        return;
+    }
+    if (VEC == 2 && full) {
+        const floatx2 o = {res[0], res[1 % VEC]};
+        __builtin_nontemporal_store(o, reinterpret_cast<floatx2 *>(out + c0));
+        return;
     }
 #pragma unroll
     for (int e = 0; e < VEC; ++e)
@@ -143,15 +167,17 @@ hipError_t launch_theta(const CoordArgs &a, hipStream_t s)
     constexpr int H = THETA / 2;
     const int K = a.median_only ? 0 : a.beta - (ODD ? 1 : 0);
     const float scale = a.median_only ? 1.0f : 1.0f / (float)a.beta;
-    const bool aligned = ((uintptr_t)a.G % 16 == 0) && ((uintptr_t)a.out % 16 == 0) && (a.ld % 4 == 0);
+    // two coordinates per lane (8-byte loads) measured faster than four at every theta tried
+    // (11, 15, 21, 27): fewer live registers, more waves in flight
+    const bool aligned = ((uintptr_t)a.G % 8 == 0) && ((uintptr_t)a.out % 8 == 0) && (a.ld % 2 == 0);
     const dim3 block(256);
     if (aligned) {
-        const dim3 grid((unsigned)((a.d + 1023) / 1024));
+        const dim3 grid((unsigned)((a.d + 511) / 512));
         if (K <= 2 && H > 2)
-            coord_selected_kernel<THETA, 4, 2><<<grid, block, 0, s>>>(a.G, a.n, a.d, a.ld, a.sel, K,
+            coord_selected_kernel<THETA, 2, 2><<<grid, block, 0, s>>>(a.G, a.n, a.d, a.ld, a.sel, K,
                                                                       a.median_only, scale, a.out);
         else
-            coord_selected_kernel<THETA, 4, (H > 0 ? H : 1)><<<grid, block, 0, s>>>(
+            coord_selected_kernel<THETA, 2, (H > 0 ? H : 1)><<<grid, block, 0, s>>>(
                 a.G, a.n, a.d, a.ld, a.sel, K, a.median_only, scale, a.out);
     } else {
         const dim3 grid((unsigned)((a.d + 255) / 256));

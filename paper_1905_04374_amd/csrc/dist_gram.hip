@@ -1,0 +1,327 @@
+// Distance pass, Gram form on the matrix cores (Algorithm 1, multi-Krum, the score line; Eq. 4):
+// G = X X^T accumulated over all coordinates, D_ij = G_ii + G_jj - 2 G_ij afterwards in fp64.
+//
+// Rows are padded to NB = ceil(n/16) blocks of 16 and only the lower block triangle of G is
+// computed: NT = NB(NB+1)/2 tiles of 16x16.  A wave owns steps of 32 columns, walked
+// grid-strided so that neighbouring waves read neighbouring 128-byte lines of every row.  In a
+// step lane (r = lane%16, q = lane/16) loads the 8 floats of row 16I+r at columns 8q..8q+7 for
+// every row block I: exactly the operand layout of the MFMA instructions (row = lane%16, k
+// group = lane/16), and the A and B operands of a Gram product share it, so tile (I,J) is
+// mfma(x[I], x[J]).  Nothing is staged in LDS and the main loop has no data-dependent barrier.
+// Loads run DEPTH steps ahead in a register ring.
+//
+// Two arithmetic variants:
+//  fp32:  v_mfma_f32_16x16x4_f32, eight k-slices per step.  At n = 39 its 1536 MACs per
+//         coordinate take exactly as long as the 156 bytes take from HBM: on the ridge.
+//  bf16:  every fp32 value is split exactly into three bf16 pieces x = hi + mid + lo (8
+//         significand bits each, by truncation, so the remainders are exact).  A product x*y is
+//         the sum of nine piece products, each exact in fp32; the six largest (hi*hi, hi*mid,
+//         mid*hi, hi*lo, lo*hi, mid*mid) are accumulated, the dropped ones are below 2^-24 of
+//         x*y - the size of one fp32 rounding.  v_mfma_f32_16x16x32_bf16 consumes a whole step
+//         per instruction: six of them at 16 cycles replace eight at 32, so the matrix cores
+//         stop being the limit and the kernel is bound by the HBM stream.
+//
+// Precision: the MFMA accumulators are fp32; every 8 steps (256 columns) the four waves of a
+// workgroup hand them over through LDS and each thread adds its share into fp64 sums in wave
+// order.  Workgroup sums are written as fp64 partial tiles and added over workgroups in index
+// order by reduce_partials_kernel.  No atomics: the result is a function of the data only.
+#include <hip/hip_runtime.h>
+
+#include "mb_internal.hpp"
+
+namespace mb {
+namespace {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;  // 4 waves
+constexpr int kCols = 32;      // columns per wave step
+constexpr int kFlush = 8;      // steps between hand-overs of the fp32 accumulators to fp64
+
+struct Pieces {
+    uintx4 hi, mid, lo;   // 8 bf16 each: element e in half (e & 1) of word e / 2
+};
+
+// two floats -> one packed word of each piece
+__device__ __forceinline__ void split_pair(float a, float b, unsigned &hi, unsigned &mid, unsigned &lo)
+{
+    constexpr unsigned kTop = 0xffff0000u, kSel = 0x07060302u;   // upper halves of (b, a)
+    const unsigned ua = __float_as_uint(a), ub = __float_as_uint(b);
+    hi = __builtin_amdgcn_perm(ub, ua, kSel);
+    const float ra = a - __uint_as_float(ua & kTop);
+    const float rb = b - __uint_as_float(ub & kTop);
+    const unsigned va = __float_as_uint(ra), vb = __float_as_uint(rb);
+    mid = __builtin_amdgcn_perm(vb, va, kSel);
+    const float sa = ra - __uint_as_float(va & kTop);
+    const float sb = rb - __uint_as_float(vb & kTop);
+    lo = __builtin_amdgcn_perm(__float_as_uint(sb), __float_as_uint(sa), kSel);
+}
+
+__device__ __forceinline__ Pieces split8(const float4 &u, const float4 &w)
+{
+    unsigned h[4], m[4], l[4];
+    split_pair(u.x, u.y, h[0], m[0], l[0]);
+    split_pair(u.z, u.w, h[1], m[1], l[1]);
+    split_pair(w.x, w.y, h[2], m[2], l[2]);
+    split_pair(w.z, w.w, h[3], m[3], l[3]);
+    Pieces p;
+    p.hi = uintx4{h[0], h[1], h[2], h[3]};
+    p.mid = uintx4{m[0], m[1], m[2], m[3]};
+    p.lo = uintx4{l[0], l[1], l[2], l[3]};
+    return p;
+}
+
+struct Raw {
+    float4 u, w;   // columns 8q..8q+3 and 8q+4..8q+7 of one row
+};
+
+template <int NB>
+struct Tiles {
+    static constexpr int NT = NB * (NB + 1) / 2;
+    floatx4 acc[NT];
+
+    __device__ __forceinline__ void clear()
+    {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // fp32 variant: eight k-slices, slice e = element e of every lane
+    __device__ __forceinline__ void mac_fp32(const Raw (&x)[NB])
+    {
+#define MB_SLICE(FIELD)                                                                          \
+    {                                                                                            \
+        int t = 0;                                                                               \
+        _Pragma("unroll") for (int I = 0; I < NB; ++I)                                           \
+            _Pragma("unroll") for (int J = 0; J <= I; ++J, ++t)                                  \
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[I].FIELD, x[J].FIELD, acc[t], 0, 0, 0); \
+    }
+        MB_SLICE(u.x) MB_SLICE(u.y) MB_SLICE(u.z) MB_SLICE(u.w)
+        MB_SLICE(w.x) MB_SLICE(w.y) MB_SLICE(w.z) MB_SLICE(w.w)
+#undef MB_SLICE
+    }
+
+    // bf16 variant: six piece products, the small ones first
+    __device__ __forceinline__ void mac_bf16(const Pieces (&x)[NB])
+    {
+#define MB_TERM(PA, PB)                                                                        \
+    {                                                                                          \
+        int t = 0;                                                                             \
+        _Pragma("unroll") for (int I = 0; I < NB; ++I)                                         \
+            _Pragma("unroll") for (int J = 0; J <= I; ++J, ++t)                                \
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                              \
+                    __builtin_bit_cast(bf16x8, x[I].PA), __builtin_bit_cast(bf16x8, x[J].PB),  \
+                    acc[t], 0, 0, 0);                                                          \
+    }
+        MB_TERM(lo, hi) MB_TERM(hi, lo) MB_TERM(mid, mid) MB_TERM(mid, hi) MB_TERM(hi, mid) MB_TERM(hi, hi)
+#undef MB_TERM
+    }
+};
+
+template <int NB, bool BF16, int DEPTH>
+__global__ __launch_bounds__(kThreads) void gram_kernel(const float *__restrict__ G, int n, int64_t d,
+                                                        int64_t ld, int aligned,
+                                                        double *__restrict__ partials)
+{
+    constexpr int NT = NB * (NB + 1) / 2;
+    __shared__ float stage[4][NT * 256];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int r = lane & 15;   // row within a block of 16
+    const int q = lane >> 4;   // group of 8 consecutive columns
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    const int64_t gw = (int64_t)blockIdx.x * 4 + wave;
+
+    // Lanes of padded rows (16I + r >= n) read row n-1 instead: they fill Gram entries of rows
+    // that do not exist and that nothing reads, the addresses are those another lane loads
+    // anyway, and the main loop stays free of branches.
+    const float *rowp[NB];
+    bool rowok[NB];
+#pragma unroll
+    for (int I = 0; I < NB; ++I) {
+        const int row = 16 * I + r;
+        rowok[I] = row < n;
+        rowp[I] = G + (int64_t)(rowok[I] ? row : n - 1) * ld + 8 * q;
+    }
+
+    Tiles<NB> tiles;
+    tiles.clear();
+    double sums[NT];   // thread tid owns entry tid of every tile
+#pragma unroll
+    for (int t = 0; t < NT; ++t) sums[t] = 0.0;
+
+    // hand the fp32 accumulators of the four waves over to the fp64 sums (whole workgroup)
+    auto flush = [&]() {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) stage[wave][t * 256 + v * 64 + lane] = tiles.acc[t][v];
+            tiles.acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+        }
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int w = 0; w < 4; ++w) sums[t] += (double)stage[w][t * 256 + tid];
+        __syncthreads();
+    };
+
+    auto load = [&](Raw (&b)[NB], int64_t step) {
+        const int64_t c = step * kCols;
+#pragma unroll
+        for (int I = 0; I < NB; ++I) {
+            b[I].u = *reinterpret_cast<const float4 *>(rowp[I] + c);
+            b[I].w = *reinterpret_cast<const float4 *>(rowp[I] + c + 4);
+        }
+    };
+
+    // ---- main part: every wave of the grid runs the same number of whole steps -------------
+    const int64_t nfull = aligned ? d / kCols : 0;   // steps of 32 whole columns, 16-byte loads
+    const int64_t iters = nfull / nwaves;            // step gw + i*nwaves exists for all i < iters
+    if (iters > 0) {
+        const int64_t last = iters - 1;
+        auto step_of = [&](int64_t i) { return gw + (i < last ? i : last) * nwaves; };  // clamped
+        Raw raw[DEPTH][NB];
+#pragma unroll
+        for (int k = 0; k < DEPTH; ++k) load(raw[k], step_of(k));
+        for (int64_t i = 0; i <= last; i += DEPTH) {
+#pragma unroll
+            for (int k = 0; k < DEPTH; ++k) {
+                if (i + k <= last) {
+                    if constexpr (BF16) {
+                        Pieces x[NB];
+#pragma unroll
+                        for (int I = 0; I < NB; ++I) x[I] = split8(raw[k][I].u, raw[k][I].w);
+                        load(raw[k], step_of(i + k + DEPTH));
+                        tiles.mac_bf16(x);
+                    } else {
+                        tiles.mac_fp32(raw[k]);
+                        load(raw[k], step_of(i + k + DEPTH));
+                    }
+                    if (((i + k) & (kFlush - 1)) == kFlush - 1) flush();
+                }
+            }
+        }
+    }
+
+    // ---- what is left: fewer than one step per wave, or everything when the matrix is not
+    //      16-byte aligned; element loads guarded against the end of the row --------------------
+    {
+        const int64_t c_begin = iters * nwaves * kCols;
+        const int64_t tsteps = (d - c_begin + kCols - 1) / kCols;
+        const int64_t first = (int64_t)blockIdx.x * 4;
+        const int64_t titers = first < tsteps ? (tsteps - first + nwaves - 1) / nwaves : 0;  // same for 4 waves
+        for (int64_t i = 0; i < titers; ++i) {
+            const int64_t step = gw + i * nwaves;
+            if (step < tsteps) {
+                const int64_t c = c_begin + step * kCols;     // rowp already holds + 8q
+                Raw x[NB];
+#pragma unroll
+                for (int I = 0; I < NB; ++I) {
+                    float v[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v[e] = (c + 8 * q + e < d) ? rowp[I][c + e] : 0.0f;
+                    x[I].u = make_float4(v[0], v[1], v[2], v[3]);
+                    x[I].w = make_float4(v[4], v[5], v[6], v[7]);
+                }
+                if constexpr (BF16) {
+                    Pieces p[NB];
+#pragma unroll
+                    for (int I = 0; I < NB; ++I) p[I] = split8(x[I].u, x[I].w);
+                    tiles.mac_bf16(p);
+                } else {
+                    tiles.mac_fp32(x);
+                }
+            }
+            if ((i & (kFlush - 1)) == kFlush - 1) flush();
+        }
+    }
+    flush();
+
+    double *dst = partials + (int64_t)blockIdx.x * (NT * 256);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) dst[t * 256 + tid] = sums[t];
+}
+
+template <int NB, bool BF16, int DEPTH>
+hipError_t launch_one(const float *G, int n, int64_t d, int64_t ld, double *partials, int nblocks,
+                      hipStream_t s)
+{
+    const int aligned = ((uintptr_t)G % 16 == 0) && (ld % 4 == 0);
+    gram_kernel<NB, BF16, DEPTH><<<dim3(nblocks), dim3(kThreads), 0, s>>>(G, n, d, ld, aligned, partials);
+    return hipGetLastError();
+}
+
+template <int NB, bool BF16, int DEPTH>
+int resident_blocks()
+{
+    static int cached = 0;
+    if (cached) return cached;
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 1024;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 1024;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gram_kernel<NB, BF16, DEPTH>, kThreads, 0) !=
+        hipSuccess)
+        return 1024;
+    if (per_cu < 1) per_cu = 1;
+    cached = cus * per_cu;
+    return cached;
+}
+
+template <int NB, bool BF16, int DEPTH>
+int grid_for(int64_t d)
+{
+    const int64_t steps = (d + 4 * kCols - 1) / (4 * kCols);   // one step for each of the 4 waves
+    int64_t g = resident_blocks<NB, BF16, DEPTH>();
+    if (g > kGramMaxBlocks) g = kGramMaxBlocks;
+    if (steps < g) g = steps < 1 ? 1 : steps;
+    return (int)g;
+}
+
+// prefetch depth per variant and row-block count (register budget: 24 VGPRs per step at NB = 3)
+template <int NB, bool BF16>
+struct Depth {
+#ifdef MB_GRAM_DEPTH
+    static constexpr int value = MB_GRAM_DEPTH;
+#else
+    static constexpr int value = 4;   // measured: 1..4 within 2 % of each other at n = 39, 4 best at n = 51
+#endif
+};
+
+template <int NB, bool BF16>
+hipError_t launch_nb(const float *G, int n, int64_t d, int64_t ld, double *partials, int *nblocks,
+                     hipStream_t s)
+{
+    constexpr int D = Depth<NB, BF16>::value;
+    *nblocks = grid_for<NB, BF16, D>(d);
+    return launch_one<NB, BF16, D>(G, n, d, ld, partials, *nblocks, s);
+}
+
+}  // namespace
+
+hipError_t launch_dist_gram(const float *G, int n, int64_t d, int64_t ld, double *partials, bool bf16,
+                            int *nblocks, hipStream_t s)
+{
+    const int nb = gram_blocks(n);
+    if (bf16) {
+        switch (nb) {
+            case 1: return launch_nb<1, true>(G, n, d, ld, partials, nblocks, s);
+            case 2: return launch_nb<2, true>(G, n, d, ld, partials, nblocks, s);
+            case 3: return launch_nb<3, true>(G, n, d, ld, partials, nblocks, s);
+            case 4: return launch_nb<4, true>(G, n, d, ld, partials, nblocks, s);
+        }
+    } else {
+        switch (nb) {
+            case 1: return launch_nb<1, false>(G, n, d, ld, partials, nblocks, s);
+            case 2: return launch_nb<2, false>(G, n, d, ld, partials, nblocks, s);
+            case 3: return launch_nb<3, false>(G, n, d, ld, partials, nblocks, s);
+            case 4: return launch_nb<4, false>(G, n, d, ld, partials, nblocks, s);
+        }
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace mb

@@ -12,21 +12,24 @@ constexpr int kMaxN = 64;
 //   direct: kDirectSlots = 36 row-block pairs x 64 entries
 //   gram:   NT(NB) tiles x 256 entries, NB = ceil(n/16), NT = NB(NB+1)/2
 constexpr int kDirectSlots = 36 * 64;
+constexpr int kGramMaxBlocks = 2048;
 inline int gram_blocks(int n) { return (n + 15) / 16; }
 inline int gram_slots(int n) { int nb = gram_blocks(n); return nb * (nb + 1) / 2 * 256; }
 
-// Number of workgroups the distance kernels are launched with.
+// Upper bound on the number of workgroups the distance kernels are launched with (sizes the partials).
 int dist_grid_blocks(int64_t d, int algo);
 
 hipError_t launch_dist_direct(const float *G, int n, int64_t d, int64_t ld, double *partials,
                               int nblocks, hipStream_t s);
-hipError_t launch_dist_gram(const float *G, int n, int64_t d, int64_t ld, double *partials,
-                            int nblocks, hipStream_t s);
+// launches with as many workgroups as stay resident (at most dist_grid_blocks) and reports the count
+hipError_t launch_dist_gram(const float *G, int n, int64_t d, int64_t ld, double *partials, bool bf16,
+                            int *nblocks, hipStream_t s);
 // partials[nblocks][stride] -> reduced[0..slots) (fixed summation order), then -> dist[n*n]
 hipError_t launch_reduce(const double *partials, int nblocks, int stride, int slots, double *reduced,
                          hipStream_t s);
 hipError_t launch_finalize_direct(const double *reduced, int n, double *dist, int accumulate, hipStream_t s);
-hipError_t launch_finalize_gram(const double *reduced, int n, double *dist, int accumulate, hipStream_t s);
+hipError_t launch_finalize_gram(const double *reduced, int n, double *dist, int accumulate, bool canon,
+                                hipStream_t s);
 
 // ---- selection -----------------------------------------------------------
 // rounds >= 1: multi-Krum rounds; scores_out (may be null) gets the scores of the first round.

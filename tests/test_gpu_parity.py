@@ -20,6 +20,9 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
+ALGOS = [mb.DIST_DIRECT, mb.DIST_GRAM, mb.DIST_GRAM_BF16]
+
+
 def say(*a):
     print("[case]", *a, flush=True)
     sys.stdout.flush()
@@ -56,7 +59,7 @@ SHAPES = [(1, 5), (2, 1), (3, 31), (8, 128), (11, 1000), (16, 4096), (17, 4099),
           (32, 33333), (39, 65537), (48, 8191), (51, 20000), (64, 12345)]
 
 
-@pytest.mark.parametrize("algo", [mb.DIST_DIRECT, mb.DIST_GRAM])
+@pytest.mark.parametrize("algo", ALGOS)
 @pytest.mark.parametrize("n,d", SHAPES)
 def test_pairwise_sqdist(n, d, algo):
     say("pairwise_sqdist", n, d, algo)
@@ -68,7 +71,7 @@ def test_pairwise_sqdist(n, d, algo):
     assert_dist_close(got, G, ref, algo)
 
 
-@pytest.mark.parametrize("algo", [mb.DIST_DIRECT, mb.DIST_GRAM])
+@pytest.mark.parametrize("algo", ALGOS)
 def test_pairwise_sqdist_strided_unaligned_and_chunked(algo):
     say("pairwise_sqdist strided", algo)
     rng = np.random.default_rng(5)
@@ -87,7 +90,7 @@ def test_pairwise_sqdist_strided_unaligned_and_chunked(algo):
     assert_dist_close(D, wide, ref, algo)
 
 
-@pytest.mark.parametrize("algo", [mb.DIST_DIRECT, mb.DIST_GRAM])
+@pytest.mark.parametrize("algo", ALGOS)
 def test_identical_rows_tie_exactly(algo):
     say("identical rows", algo)
     rng = np.random.default_rng(11)
@@ -100,7 +103,7 @@ def test_identical_rows_tie_exactly(algo):
     assert np.array_equal(D[2], D[33]) and np.array_equal(D[2], D[17]) and np.array_equal(D[20], D[38])
 
 
-@pytest.mark.parametrize("algo", [mb.DIST_DIRECT, mb.DIST_GRAM])
+@pytest.mark.parametrize("algo", ALGOS)
 def test_distance_pass_is_deterministic(algo):
     say("determinism", algo)
     G = gpu(W.make(2, "cpu", d=300_001))
@@ -222,7 +225,7 @@ def test_coordwise_alg1(n, f, d):
 
 
 # ------------------------------------------------------------------ whole GAR
-@pytest.mark.parametrize("algo", [mb.DIST_DIRECT, mb.DIST_GRAM])
+@pytest.mark.parametrize("algo", ALGOS)
 @pytest.mark.parametrize("cfg,d,placement", [(1, None, "tail"), (1, None, "random"), (2, None, "tail"),
                                              (3, 300_007, "tail"), (4, 200_003, "random"), (5, 100_001, "tail")])
 def test_aggregate_matches_oracle(cfg, d, placement, algo):
@@ -242,7 +245,7 @@ def test_aggregate_matches_oracle(cfg, d, placement, algo):
     assert sel.cpu().numpy().tolist() == ext.tolist()
     assert_out_close(out, ref, scale)
     out2, sel2 = mb.mbulyan_aggregate(Gt, s["f"])
-    if algo == mb.DIST_GRAM:
+    if algo != mb.DIST_DIRECT:
         assert torch.equal(out, out2) and torch.equal(sel, sel2)      # run-to-run bit-identical
 
 
