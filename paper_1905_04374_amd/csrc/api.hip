@@ -354,7 +354,8 @@ int mbulyan_aggregate_chunked(const float *const *chunks, int nchunks, const int
     }
     {
         StageTimer t(MB_STAGE_SELECT, s);
-        MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, ws.sel(), ws.sets(), ws.m(), nullptr, s));
+        MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, ws.sel(),
+                                 mode == MB_MODE_ALG1 ? ws.sets() : nullptr, ws.m(), nullptr, s));
     }
     for (int c = 0; c < nchunks; ++c) {
         rc = run_coord(chunks[c], n, chunk_d[c], chunk_ld[c], mode, theta, beta, ws.sel(), ws.sets(),
@@ -383,7 +384,8 @@ int mbulyan_aggregate_ex(const float *grads, int n, int f, int64_t d, int64_t ld
     if (rc != MB_OK) return rc;
     {
         StageTimer t(MB_STAGE_SELECT, s);
-        MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, ws.sel(), ws.sets(), ws.m(), nullptr, s));
+        MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, ws.sel(),
+                                 mode == MB_MODE_ALG1 ? ws.sets() : nullptr, ws.m(), nullptr, s));
     }
     rc = run_coord(grads, n, d, ld, mode, theta, beta, ws.sel(), ws.sets(), out, s);
     if (rc != MB_OK) return rc;

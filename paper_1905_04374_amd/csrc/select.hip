@@ -2,11 +2,12 @@
 // gradients (Algorithm 1, function multi-Krum and the loop of multi-Bulyan).
 //
 // O(theta n^2) scalar work on an n x n matrix, n <= 64: one workgroup.
-// All 16 waves first order every row of the distance matrix once (rank by
+// All 4 waves first order every row of the distance matrix once (rank by
 // counting, keys (distance, index)); then a single wave, lane i = gradient i,
-// plays the rounds: walk the own ordered row skipping extracted gradients,
-// add the q nearest distances in ascending order in fp64, rank the scores by
-// (score, index) with wave shuffles, extract the first.
+// plays the rounds with its ordered row held in registers and a bit mask of the
+// ranks still active: add the q nearest distances in ascending order in fp64,
+// find the smallest (score, index) by a wave reduction (or rank all scores through
+// LDS broadcasts when the averaged sets are wanted), extract it.
 #include <hip/hip_runtime.h>
 
 #include "mb_internal.hpp"
@@ -14,7 +15,8 @@
 namespace mb {
 namespace {
 
-constexpr int kSelThreads = 1024;
+constexpr int kSelThreads = 256;   // 4 waves: one per SIMD, so the round-playing wave may use the whole register file
+constexpr int kPerThread = kMaxN * kMaxN / kSelThreads;
 
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const double *__restrict__ dist, int n, int f, int rounds, const uint8_t *__restrict__ active_in,
@@ -23,6 +25,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
 {
     __shared__ double sD[kMaxN * kMaxN];        // first dist[i][j], then row i in ascending order
     __shared__ unsigned char sJ[kMaxN * kMaxN]; // neighbour index by rank within row i
+    __shared__ unsigned char sR[kMaxN * kMaxN]; // rank of neighbour j within row i
+    __shared__ double sS[kMaxN];
     const int tid = threadIdx.x;
     const double inf = __builtin_huge_val();
 
@@ -34,10 +38,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     __syncthreads();
 
     // rank of j among the neighbours of i (everything but i itself), keys (distance, index)
-    double myv[4];
-    int myrank[4];
+    double myv[kPerThread];
+    int myrank[kPerThread];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
+    for (int k = 0; k < kPerThread; ++k) {
         const int e = tid + k * kSelThreads;
         myrank[k] = -1;
         myv[k] = 0.0;
@@ -57,53 +61,97 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     }
     __syncthreads();
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
+    for (int k = 0; k < kPerThread; ++k) {
         const int e = tid + k * kSelThreads;
         if (myrank[k] >= 0) {
             const int i = e / n, j = e % n;
             sD[i * kMaxN + myrank[k]] = myv[k];
             sJ[i * kMaxN + myrank[k]] = (unsigned char)j;
+            sR[i * kMaxN + j] = (unsigned char)myrank[k];
         }
     }
     __syncthreads();
-    if (tid >= 64) return;   // no barrier below this line
+    if (tid >= 64) return;   // one wave plays the rounds; no workgroup barrier below this line
 
+    // Lane i keeps its ordered row in registers and a bit mask over ranks: bit r is set while the
+    // r-th nearest neighbour of i is still active.  A round then needs no dependent LDS reads.
     const int i = tid;
-    unsigned long long act = 0;   // same value in every lane
+    const int row = i < n ? i : 0;
+    double v[kMaxN - 1];
+#pragma unroll
+    for (int r = 0; r < kMaxN - 1; ++r) v[r] = (r < n - 1) ? sD[row * kMaxN + r] : 0.0;
+
+    unsigned long long act = 0;   // active gradients, same value in every lane
     for (int j = 0; j < n; ++j)
         if (!active_in || active_in[j]) act |= 1ull << j;
+    unsigned long long near = 0;  // active neighbours of i, by rank
+    for (int r = 0; r < n - 1; ++r)
+        if ((act >> sJ[row * kMaxN + r]) & 1ull) near |= 1ull << r;
 
     for (int t = 0; t < rounds; ++t) {
         const int k = __popcll(act);
         int q = k - f - 2;
         q = q < 0 ? 0 : q;
         const bool mine = i < n && ((act >> i) & 1ull);
-        double S = inf;
-        if (mine) {
-            S = 0.0;
-            int cnt = 0;
-            for (int r = 0; r < n - 1 && cnt < q; ++r) {
-                const int j = sJ[i * kMaxN + r];
-                if ((act >> j) & 1ull) {
-                    S += sD[i * kMaxN + r];
-                    ++cnt;
-                }
+        // ranks of the q nearest active neighbours: the q lowest set bits of `near`
+        unsigned long long take = near;
+        {
+            // drop set bits from the top until q are left (binary search on the cut position)
+            int lo = 0, hi = 64;                       // smallest cut with popc(near & below(cut)) >= q
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                const unsigned long long below = mid >= 64 ? ~0ull : ((1ull << mid) - 1ull);
+                if (__popcll(near & below) >= q) hi = mid; else lo = mid + 1;
+            }
+            take = near & (lo >= 64 ? ~0ull : ((1ull << lo) - 1ull));
+        }
+        const unsigned tlo = (unsigned)take, thi = (unsigned)(take >> 32);
+        double S = 0.0;   // added in ascending order of distance
+#pragma unroll
+        for (int r = 0; r < kMaxN - 1; ++r) {
+            if (r < n - 1) {
+                const bool in = r < 32 ? (tlo & (1u << (r & 31))) != 0 : (thi & (1u << (r & 31))) != 0;
+                S += in ? v[r] : 0.0;
             }
         }
+        if (!mine) S = inf;
         if (t == 0 && scores_out && i < n) scores_out[i] = S;
-        // position of i in the order (score, index) of the active gradients
-        int pos = 0;
-        for (int j = 0; j < n; ++j) {
-            const double Sj = __shfl(S, j, 64);
-            const bool aj = (act >> j) & 1ull;
-            pos += (aj && (Sj < S || (Sj == S && j < i))) ? 1 : 0;
+
+        int w;            // the first of the active gradients in the order (score, index)
+        int pos = 0;      // position of i in that order (only needed for the averaged sets)
+        if (agr_sets) {
+            sS[i] = S;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __builtin_amdgcn_wave_barrier();
+            for (int j = 0; j < n; ++j) {
+                const double Sj = sS[j];
+                const bool aj = (act >> j) & 1ull;
+                pos += (aj && (Sj < S || (Sj == S && j < i))) ? 1 : 0;
+            }
+            __builtin_amdgcn_wave_barrier();
+            const unsigned long long first = __ballot(mine && pos == 0);
+            w = first ? (int)__builtin_ctzll(first) : 0;
+            if (i < n) agr_sets[t * n + i] = (mine && pos < q) ? 1 : 0;
+        } else {
+            double bs = S;
+            int bi = mine ? i : kMaxN;
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                const double os = __shfl_xor(bs, off, 64);
+                const int oi = __shfl_xor(bi, off, 64);
+                const bool better = os < bs || (os == bs && oi < bi);
+                bs = better ? os : bs;
+                bi = better ? oi : bi;
+            }
+            w = bi < kMaxN ? bi : 0;
         }
-        const unsigned long long first = __ballot(mine && pos == 0);
-        const int w = first ? (int)__builtin_ctzll(first) : 0;
         if (sel && i == 0) sel[t] = w;
-        if (agr_sets && i < n) agr_sets[t * n + i] = (mine && pos < q) ? 1 : 0;
         if (m_out && i == 0) m_out[t] = q < k ? q : k;
-        if (first) act &= ~(1ull << w);
+        if (k > 0) {
+            act &= ~(1ull << w);
+            const int rw = sR[row * kMaxN + w];          // rank of the extracted gradient in row i
+            if (w != row) near &= ~(1ull << rw);
+        }
     }
 }
 
