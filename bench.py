@@ -15,7 +15,12 @@ import sys
 import time
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+# HBM bytes per launch of the distance kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
+# scaled by what the same counter reads for a 4 GiB device copy (FETCH_SIZE reads half the bytes
+# of the copy, WRITE_SIZE all of them); see profiles/gram_kernel_cfg4_n39_d250M_hbm_traffic.md
+MEASURED_TRAFFIC_BYTES = {(4, "gram_bf16"): 2 * 19040000 * 1024 + 6144 * 1024}
 MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix, published
 
 
 def main():
@@ -31,7 +36,7 @@ def main():
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run one plain device copy of this many MiB before the timed region "
                          "(a kernel of known traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE)")
-    ap.add_argument("--cpu-sample", type=int, default=1 << 24, help="coordinates the oracle is timed on")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 28, help="coordinates the oracle is timed on")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the aggregation rule of one parameter server); "
@@ -103,13 +108,23 @@ def main():
     dist_avg_s = dist_ms / 1e3 / max(dist_launches, 1)
     dist_bytes = in_bytes / nchunks
     achieved = dist_bytes / dist_avg_s / 1e9
-    roofline = {"kernel": "dist_direct_kernel" if a.dist_algo == "direct" else "dist_gram_kernel", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                "avg_launch_ms": round(dist_avg_s * 1e3, 4), "launches": dist_launches}
+    bf16 = a.dist_algo in ("auto", "gram_bf16")
     nb = (n + 15) // 16
-    mfma_flops = nb * (nb + 1) // 2 * 256 * 2 * (d / nchunks)
-    roofline["mfma_fp32_tflops"] = round(mfma_flops / dist_avg_s / 1e12, 2)
-    roofline["mfma_fp32_frac"] = round(mfma_flops / dist_avg_s / 1e12 / MFMA_FP32_PEAK_TFLOPS, 4)
+    kname = {"direct": "dist_direct_kernel", "gram": f"gram_kernel<{nb}, fp32>"}.get(
+        a.dist_algo, f"gram_kernel<{nb}, bf16>")
+    roofline = {"kernel": kname, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get((a.config, "gram_bf16")) if (bf16 and a.d is None) else None,
+                "algorithmic_bytes": dist_bytes,
+                "avg_launch_ms": round(dist_avg_s * 1e3, 4), "launches": dist_launches}
+    if a.dist_algo != "direct":
+        # matrix-core work of the same kernel: lower block triangle of 16x16 tiles, one (fp32) or six
+        # (split bf16) products per tile and coordinate
+        tiles = nb * (nb + 1) // 2
+        flops = tiles * 256 * 2 * (6 if bf16 else 1) * (d / nchunks)
+        peak = MFMA_BF16_PEAK_TFLOPS if bf16 else MFMA_FP32_PEAK_TFLOPS
+        roofline["matrix_cores"] = {"dtype": "bf16" if bf16 else "f32", "tflops": round(flops / dist_avg_s / 1e12, 1),
+                                    "peak": peak, "frac": round(flops / dist_avg_s / 1e12 / peak, 4)}
 
     per_stage = {k: round(v[0] / a.steps, 4) for k, v in stages.items()}
     coord_ms, coord_launches = stages["coord"]
