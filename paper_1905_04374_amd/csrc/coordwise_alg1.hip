@@ -3,8 +3,11 @@
 // that round t of multi-Krum averaged; out[c] = average of the beta values
 // G^agr[.][c] closest to M[c].
 //
-// G^agr is never materialised.  Consecutive rounds average almost the same
-// set of gradients, so each workgroup first turns the theta x n membership
+// G^agr is never materialised.  In the regular case a round's set is the
+// previous one minus its winner; the averages are then running sums over the
+// winners' values (needed for the median anyway) on top of the last round's
+// set: theta + f row streams, all in registers.  Otherwise (the order of the
+// scores changed between rounds) each workgroup turns the theta x n membership
 // matrix into a list of signed row updates (rows entering or leaving the set
 // from one round to the next); the running sum S_t = S_{t-1} +- few rows then
 // costs a handful of adds per round.  A wave stages the values of the rows it
@@ -28,26 +31,68 @@ namespace {
 constexpr int kThreads = 128;   // 2 waves: the staging area is n x 256 bytes per wave
 constexpr int kWaves = kThreads / 64;
 
+// average of the beta values a[.] closest to med (closeness |a - med| in fp32, ties to the smaller value)
 template <int THETA>
+__device__ __forceinline__ float pick_closest(float (&a)[THETA], float med, int beta)
+{
+    if (beta == 1) {
+        float best = a[0], bd = fabsf(a[0] - med);
+#pragma unroll
+        for (int t = 1; t < THETA; ++t) {
+            const float dt = fabsf(a[t] - med);
+            const bool take = dt < bd || (dt == bd && a[t] < best);
+            best = take ? a[t] : best;
+            bd = take ? dt : bd;
+        }
+        return best;
+    }
+    sort_registers<THETA>(a);
+    float dlt[THETA];
+#pragma unroll
+    for (int p = 0; p < THETA; ++p) dlt[p] = fabsf(a[p] - med);
+    float sum = 0.0f;
+#pragma unroll
+    for (int p = 0; p < THETA; ++p) {
+        int rank = 0;
+#pragma unroll
+        for (int o = 0; o < THETA; ++o) {
+            if (o < p) rank += (dlt[o] <= dlt[p]) ? 1 : 0;
+            if (o > p) rank += (dlt[o] < dlt[p]) ? 1 : 0;
+        }
+        sum += (rank < beta) ? a[p] : 0.0f;
+    }
+    return sum / (float)beta;
+}
+
+// FAST = true handles the regular case and does nothing otherwise; FAST = false the reverse.  Both
+// are launched: which case holds is only known on the device.
+template <int THETA, bool FAST>
 __global__ __launch_bounds__(kThreads) void coord_alg1_kernel(
     const float *__restrict__ G, int n, int64_t d, int64_t ld, const int32_t *__restrict__ sel,
     const uint8_t *__restrict__ sets, int beta, float *__restrict__ out)
 {
-    extern __shared__ float stage[];                 // [kWaves][n][64]
-    __shared__ unsigned char ops[kMaxN * kMaxN];     // row | 0x80 if the row leaves the set
+    extern __shared__ float stage[];                 // [kWaves][slots][64]
+    __shared__ unsigned char ops[kMaxN * kMaxN];     // slot | 0x80 if the row leaves the set
     __shared__ int off[kMaxN + 1];                   // ops of round t: [off[t], off[t+1])
     __shared__ float inv_m[kMaxN];
     __shared__ unsigned char need[kMaxN];            // row is read at all
-    __shared__ int winner[kMaxN];
+    __shared__ unsigned char slot_of[kMaxN];         // row -> slot among the rows that are read
+    __shared__ int rows[kMaxN];                      // slot -> row
+    __shared__ int wslot[kMaxN];                     // slot of the winner of round t
+    __shared__ int nslots;
     __shared__ int bad_flag;
+    __shared__ int not_nested;                       // some round's set is not "previous set minus its winner"
+    __shared__ int brows[kMaxN];                     // rows of the last round's set, its winner left out
+    __shared__ int nbase;
+    __shared__ int wrow[kMaxN];                      // winner of round t
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
 
-    // ---- plan: signed row updates per round --------------------------------
-    if (tid == 0) bad_flag = 0;
-    if (tid < n) need[tid] = 0;
+    // ---- plan: which rows are read, and the signed row updates of every round -------------
+    if (tid == 0) { bad_flag = 0; not_nested = 0; }
+    if (tid < kMaxN) need[tid] = 0;
     __syncthreads();
     int my_count = 0, my_m = 0;
     if (tid < THETA) {
@@ -59,15 +104,33 @@ __global__ __launch_bounds__(kThreads) void coord_alg1_kernel(
             if (cur) need[r] = 1;
         }
         const int w = sel[tid];
-        if ((unsigned)w >= (unsigned)n) { bad_flag = 1; winner[tid] = 0; }
-        else { winner[tid] = w; need[w] = 1; }
+        if ((unsigned)w >= (unsigned)n) bad_flag = 1;
+        else need[w] = 1;
+        wrow[tid] = ((unsigned)w < (unsigned)n) ? w : 0;
         inv_m[tid] = my_m > 0 ? 1.0f / (float)my_m : 0.0f;
         off[tid + 1] = my_count;
+        // the regular case: from one round to the next the set only loses its winner
+        bool ok = (unsigned)w < (unsigned)n && sets[tid * n + ((unsigned)w < (unsigned)n ? w : 0)] != 0;
+        if (tid + 1 < THETA)
+            for (int r = 0; r < n; ++r) {
+                const int cur = sets[tid * n + r] ? 1 : 0;
+                const int nxt = sets[(tid + 1) * n + r] ? 1 : 0;
+                ok = ok && (nxt == ((r == w) ? 0 : cur));
+            }
+        if (!ok) not_nested = 1;
     }
     __syncthreads();
     if (tid == 0) {
         off[0] = 0;
         for (int t = 0; t < THETA; ++t) off[t + 1] += off[t];
+        int ns = 0;
+        for (int r = 0; r < n; ++r)
+            if (need[r]) { slot_of[r] = (unsigned char)ns; rows[ns] = r; ++ns; }
+        nslots = ns;
+        int nb = 0;
+        for (int r = 0; r < n; ++r)
+            if (sets[(THETA - 1) * n + r] && r != sel[THETA - 1]) brows[nb++] = r;
+        nbase = nb;
     }
     __syncthreads();
     if (tid < THETA) {
@@ -75,32 +138,78 @@ __global__ __launch_bounds__(kThreads) void coord_alg1_kernel(
         for (int r = 0; r < n; ++r) {
             const int cur = sets[tid * n + r] ? 1 : 0;
             const int prev = (tid > 0 && sets[(tid - 1) * n + r]) ? 1 : 0;
-            if (cur != prev) ops[k++] = (unsigned char)(r | (cur ? 0 : 0x80));
+            if (cur != prev) ops[k++] = (unsigned char)(slot_of[r] | (cur ? 0 : 0x80));
         }
+        const int w = sel[tid];
+        wslot[tid] = ((unsigned)w < (unsigned)n) ? slot_of[w] : 0;
     }
     __syncthreads();
     const bool bad = bad_flag != 0;
+    const int U = nslots;
 
-    float *my = stage + (size_t)wave * n * 64;
     const int64_t ntiles = (d + kThreads - 1) / kThreads;
+    const bool regular = !not_nested && !bad;
+    if (regular != FAST) return;
+    if constexpr (FAST) {
+        // Regular case: set_t = set_{theta-1} + {winner_t .. winner_{theta-2}}.  The averages are
+        // then running sums over the winners' values, which the median needs anyway: theta + f
+        // coalesced row streams, everything in registers, no LDS.
+        const int nb = nbase;
+        for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+            const int64_t c = tile * kThreads + tid;
+            if (c >= d) continue;
+            float e[THETA], a[THETA];
+#pragma unroll
+            for (int t = 0; t < THETA; ++t)
+                e[t] = __builtin_nontemporal_load(G + (int64_t)__builtin_amdgcn_readfirstlane(wrow[t]) * ld + c);
+            float S = 0.0f;
+            for (int s0 = 0; s0 < nb; s0 += 8) {     // base rows, eight loads in flight at a time
+                float xb[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int row = __builtin_amdgcn_readfirstlane(brows[s0 + j < nb ? s0 + j : s0]);
+                    xb[j] = __builtin_nontemporal_load(G + (int64_t)row * ld + c);
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) S += (s0 + j < nb) ? xb[j] : 0.0f;
+            }
+#pragma unroll
+            for (int t = THETA - 1; t >= 0; --t) {
+                S += e[t];
+                a[t] = S * inv_m[t];
+            }
+            sort_registers<THETA>(e);
+            float med;
+            if constexpr (THETA & 1) med = e[THETA / 2];
+            else med = 0.5f * (e[THETA / 2 - 1] + e[THETA / 2]);
+            out[c] = pick_closest<THETA>(a, med, beta);
+        }
+    } else {
+    float *my = stage + (size_t)wave * U * 64;
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const int64_t c = tile * kThreads + tid;
         const bool live = c < d;
-        // stage the needed rows of this wave's 64 coordinates
-        for (int r = 0; r < n; ++r)
-            if (need[r]) my[r * 64 + lane] = live ? G[(int64_t)r * ld + c] : 0.0f;
-        // (a wave only reads what it wrote itself: no workgroup barrier needed, LDS
-        //  operations of one wave complete in order)
+        const int64_t cc = live ? c : d - 1;
+        // every needed row once, all loads in flight together, then parked in LDS where the
+        // update lists can index them (a lane only ever reads back what it wrote itself)
+        float x[kMaxN];
+#pragma unroll
+        for (int s = 0; s < kMaxN; ++s)
+            if (s < U) x[s] = __builtin_nontemporal_load(G + (int64_t)rows[s] * ld + cc);
+#pragma unroll
+        for (int s = 0; s < kMaxN; ++s)
+            if (s < U) my[s * 64 + lane] = x[s];
+
         float e[THETA], a[THETA];
         float S = 0.0f;
 #pragma unroll
         for (int t = 0; t < THETA; ++t) {
-            e[t] = my[winner[t] * 64 + lane];
+            e[t] = my[wslot[t] * 64 + lane];
             const int k1 = off[t + 1];
             for (int k = off[t]; k < k1; ++k) {
                 const int op = ops[k];
-                const float x = my[(op & 63) * 64 + lane];
-                S += (op & 0x80) ? -x : x;
+                const float xv = my[(op & 63) * 64 + lane];
+                S += (op & 0x80) ? -xv : xv;
             }
             a[t] = S * inv_m[t];
         }
@@ -109,49 +218,23 @@ __global__ __launch_bounds__(kThreads) void coord_alg1_kernel(
         if constexpr (THETA & 1) med = e[THETA / 2];
         else med = 0.5f * (e[THETA / 2 - 1] + e[THETA / 2]);
 
-        float res;
-        if (beta == 1) {
-            // the value closest to the median; equal closeness: the smaller value
-            float best = a[0], bd = fabsf(a[0] - med);
-#pragma unroll
-            for (int t = 1; t < THETA; ++t) {
-                const float dt = fabsf(a[t] - med);
-                const bool take = dt < bd || (dt == bd && a[t] < best);
-                best = take ? a[t] : best;
-                bd = take ? dt : bd;
-            }
-            res = best;
-        } else {
-            sort_registers<THETA>(a);
-            float dlt[THETA];
-#pragma unroll
-            for (int p = 0; p < THETA; ++p) dlt[p] = fabsf(a[p] - med);
-            float sum = 0.0f;
-#pragma unroll
-            for (int p = 0; p < THETA; ++p) {
-                int rank = 0;
-#pragma unroll
-                for (int o = 0; o < THETA; ++o) {
-                    if (o < p) rank += (dlt[o] <= dlt[p]) ? 1 : 0;
-                    if (o > p) rank += (dlt[o] < dlt[p]) ? 1 : 0;
-                }
-                sum += (rank < beta) ? a[p] : 0.0f;
-            }
-            res = sum / (float)beta;
-        }
+        float res = pick_closest<THETA>(a, med, beta);
         if (bad) res = __int_as_float(0x7fc00000);
         if (live) out[c] = res;
+    }
     }
 }
 
 template <int THETA>
 hipError_t launch_theta(const CoordAlg1Args &a, hipStream_t s)
 {
-    const size_t lds = (size_t)kWaves * a.n * 64 * sizeof(float);
+    const size_t lds = (size_t)kWaves * a.n * 64 * sizeof(float);   // at most n rows are parked
     const int64_t ntiles = (a.d + kThreads - 1) / kThreads;
     const int grid = (int)(ntiles < 2048 ? ntiles : 2048);
-    coord_alg1_kernel<THETA><<<dim3(grid), dim3(kThreads), lds, s>>>(a.G, a.n, a.d, a.ld, a.sel, a.agr_sets,
-                                                                     a.beta, a.out);
+    coord_alg1_kernel<THETA, true><<<dim3(grid), dim3(kThreads), 0, s>>>(a.G, a.n, a.d, a.ld, a.sel,
+                                                                         a.agr_sets, a.beta, a.out);
+    coord_alg1_kernel<THETA, false><<<dim3(grid), dim3(kThreads), lds, s>>>(a.G, a.n, a.d, a.ld, a.sel,
+                                                                            a.agr_sets, a.beta, a.out);
     return hipGetLastError();
 }
 

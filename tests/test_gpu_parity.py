@@ -224,6 +224,43 @@ def test_coordwise_alg1(n, f, d):
     assert flips <= max(2, d // 1000)
 
 
+@pytest.mark.parametrize("n,theta,beta,d", [(9, 4, 1, 3001), (20, 7, 3, 5000), (39, 19, 1, 20_000), (64, 30, 2, 2000)])
+def test_coordwise_alg1_arbitrary_sets(n, theta, beta, d):
+    """Membership matrices that no run of multi-Krum would produce (rows enter and leave at will):
+    the general path of the kernel, against the oracle's plain evaluation of the same sets."""
+    say("coordwise_alg1 arbitrary sets", n, theta, beta, d)
+    rng = np.random.default_rng(n * 31 + theta)
+    G = rng.standard_normal((n, d)).astype(np.float32)
+    ext = rng.permutation(n)[:theta].astype(np.int32)
+    sets = (rng.random((theta, n)) < 0.4).astype(np.uint8)
+    sets[np.arange(theta), ext] = 1
+    sets[theta // 2] = 0                                     # an empty set averages to 0
+    ref, scale, margin, alt = O.coordwise_alg1(G, ext, sets, beta, want_extra=True)
+    got = mb.coordwise_trimmed_avg(gpu(G), gpu(ext), beta, agr_sets=gpu(sets))
+    flips = alg1_compare(got, ref, scale, margin, alt)
+    assert flips <= max(2, d // 500)
+
+
+def test_coordwise_alg1_regular_sets_take_the_register_path():
+    """Sets of the regular shape (each round's set = the previous one minus its winner), built by
+    hand, so the register-only path is certainly the one compared."""
+    say("coordwise_alg1 regular sets")
+    rng = np.random.default_rng(77)
+    n, theta, beta, d = 23, 9, 3, 10_007
+    G = rng.standard_normal((n, d)).astype(np.float32)
+    order = rng.permutation(n)
+    ext = order[:theta].astype(np.int32)
+    base = order[theta:theta + 5]
+    sets = np.zeros((theta, n), np.uint8)
+    for t in range(theta):
+        sets[t, ext[t:]] = 1
+        sets[t, base] = 1
+    ref, scale, margin, alt = O.coordwise_alg1(G, ext, sets, beta, want_extra=True)
+    got = mb.coordwise_trimmed_avg(gpu(G), gpu(ext), beta, agr_sets=gpu(sets))
+    flips = alg1_compare(got, ref, scale, margin, alt)
+    assert flips <= 20
+
+
 # ------------------------------------------------------------------ whole GAR
 @pytest.mark.parametrize("algo", ALGOS)
 @pytest.mark.parametrize("cfg,d,placement", [(1, None, "tail"), (1, None, "random"), (2, None, "tail"),
