@@ -23,8 +23,55 @@ MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix, published
 
 
+def paper_protocol(fn, sync):
+    """Section V-A: synchronise, start the timer, run, synchronise, stop; 7 runs, drop the 2 furthest
+    from the median, mean and standard deviation (ms) of the remaining 5."""
+    runs = []
+    for _ in range(7):
+        sync()
+        r0 = time.perf_counter()
+        fn()
+        sync()
+        runs.append((time.perf_counter() - r0) * 1e3)
+    med = sorted(runs)[3]
+    kept = sorted(runs, key=lambda x: abs(x - med))[:5]
+    mean5 = sum(kept) / 5
+    return mean5, (sum((x - mean5) ** 2 for x in kept) / 5) ** 0.5
+
+
+def sweep():
+    """The paper's aggregation-time sweep (Section V-A): n in 7, 9, .., 39, d in 1e5, 1e6, 1e7,
+    f = floor((n-3)/4), n gradients drawn from U(0,1)^d; multi-Bulyan (both readings), multi-Krum and
+    the coordinate-wise median, each timed with the paper's protocol.  One JSON line per (n, d)."""
+    import torch
+    import paper_1905_04374_amd as mb
+    import workloads as W
+    dev = "cuda:0"
+    sync = torch.cuda.synchronize
+    for d in (100_000, 1_000_000, 10_000_000):
+        for n in range(7, 40, 2):
+            f = (n - 3) // 4
+            G = W.uniform(n, d, dev)
+            out = torch.empty(d, device=dev)
+            ws = torch.empty(mb.mbulyan_workspace_bytes(n, d), dtype=torch.uint8, device=dev)
+            row = {"n": n, "f": f, "d": d}
+            calls = {
+                "multi_bulyan_ms": lambda: mb.mbulyan_aggregate_ex(G, f, out=out, workspace=ws),
+                "multi_bulyan_alg1_ms": lambda: mb.mbulyan_aggregate_ex(G, f, mode=mb.MODE_ALG1, out=out, workspace=ws),
+                "multi_krum_ms": lambda: mb.multikrum_aggregate(G, f, out=out, workspace=ws),
+                "median_ms": lambda: mb.coordwise_median(G, out=out),
+            }
+            for name, fn in calls.items():
+                fn()
+                mean5, std5 = paper_protocol(fn, sync)
+                row[name] = round(mean5, 4)
+                row[name.replace("_ms", "_std")] = round(std5, 4)
+            print(json.dumps(row), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--sweep", action="store_true", help="run the paper's (n, d) sweep on U(0,1) inputs instead")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
@@ -38,6 +85,8 @@ def main():
                          "(a kernel of known traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--cpu-sample", type=int, default=1 << 28, help="coordinates the oracle is timed on")
     a = ap.parse_args()
+    if a.sweep:
+        return sweep()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the aggregation rule of one parameter server); "
               "--gpus must be 1", file=sys.stderr)
@@ -98,6 +147,8 @@ def main():
     mb.mbulyan_timing_enable(False)
     stages = mb.mbulyan_timing_read()
 
+    mean5, std5 = paper_protocol(step, torch.cuda.synchronize)
+
     sec = (t1 - t0) / a.steps
     in_bytes = 4.0 * n * d
     rows2 = theta if mode == mb.MODE_SELECTED else None
@@ -143,6 +194,7 @@ def main():
                                f"theta={theta} beta={beta}, chunks={nchunks}"},
         "hbm_frac_input_bytes": round(value / HBM_PEAK_GBS, 4),
         "stage_ms_per_step": per_stage,
+        "paper_protocol_ms": {"mean_of_5": round(mean5, 4), "std_of_5": round(std5, 4), "runs": 7},
         "roofline": roofline,
     }
 

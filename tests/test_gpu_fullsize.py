@@ -87,6 +87,48 @@ def test_full_size_single_buffer(cfg):
         f"out worst err/tol {worst:.3g}, oracle coordinate phase {time.time() - t0:.1f} s")
 
 
+@pytest.mark.parametrize("cfg", [3, 4])
+def test_full_size_alg1_mode(cfg):
+    """Algorithm-1 mode at full size: extracted list exact, output compared over a sample of 2^24
+    coordinates spread over the whole range (the oracle evaluates theta averages per coordinate)."""
+    s = W.spec(cfg)
+    n, f, d = s["n"], s["f"], s["d"]
+    say("full size alg1", cfg, n, f, d)
+    theta, beta = O.params(n, f, O.MODE_ALG1)
+    Gt = W.make(cfg, DEV)
+    ws = torch.empty(mb.mbulyan_workspace_bytes(n, d), dtype=torch.uint8, device=DEV)
+    out, sel = mb.mbulyan_aggregate_ex(Gt, f, mode=mb.MODE_ALG1, workspace=ws)
+    Dg = mb.pairwise_sqdist(Gt, workspace=ws).cpu().numpy()
+    torch.cuda.synchronize()
+    G = np.empty((n, d), np.float32)
+    for r in range(n):
+        G[r] = Gt[r].cpu().numpy()
+    got = out.cpu().numpy()
+    sel = sel.cpu().numpy()
+    del Gt, out
+    torch.cuda.empty_cache()
+    D = O.pairwise_sqdist(G)
+    ext, sets, m = O.multikrum_select(D, f, theta)
+    assert sel.tolist() == ext.tolist()
+    assert np.max(np.abs(Dg - D)[D > 0] / D[D > 0]) < 1e-5
+    blocks = 64
+    width = (1 << 24) // blocks
+    flips = 0
+    worst = 0.0
+    for b in range(blocks):
+        lo = (d - width) * b // (blocks - 1)
+        ref, scale, margin, alt = O.coordwise_alg1(G[:, lo:lo + width], ext, sets, beta, want_extra=True)
+        g = got[lo:lo + width]
+        tol = 1e-5 * np.maximum(np.abs(ref), scale) + 1e-37
+        ok = np.abs(g - ref) <= tol
+        ok_alt = (margin <= 4e-6 * scale) & (np.abs(g - alt) <= 1e-5 * np.maximum(np.abs(alt), scale) + 1e-37)
+        assert np.all(ok | ok_alt), f"block {b}: {int(np.sum(~(ok | ok_alt)))} coordinates off"
+        flips += int(np.sum(~ok & ok_alt))
+        worst = max(worst, float(np.max(np.where(ok, np.abs(g - ref) / tol, 0.0))))
+    assert flips <= (1 << 24) // 1000
+    say(f"cfg {cfg} alg1: selected {ext.tolist()}, worst err/tol {worst:.3g}, ambiguous choices {flips} of {1 << 24}")
+
+
 def test_full_size_chunked():
     s = W.spec(5)
     n, f, nchunks = s["n"], s["f"], s["chunks"]
