@@ -51,13 +51,13 @@ def units():
     return u
 
 
-def _deps_newer(obj: str) -> bool:
+def _deps_newer(obj: str, src: str) -> bool:
+    """An object depends on its own source, every header beside it, the public headers and this file."""
     t = os.path.getmtime(obj)
-    for root in (CSRC, INCLUDE):
-        for name in os.listdir(root):
-            if os.path.getmtime(os.path.join(root, name)) > t:
-                return True
-    return os.path.getmtime(__file__) > t
+    deps = [os.path.join(CSRC, src), __file__]
+    deps += [os.path.join(CSRC, name) for name in os.listdir(CSRC) if name.endswith(".hpp")]
+    deps += [os.path.join(INCLUDE, name) for name in os.listdir(INCLUDE)]
+    return any(os.path.getmtime(dep) > t for dep in deps)
 
 
 def build(jobs: int = 8, force: bool = True, verbose: bool = False) -> str:
@@ -67,7 +67,7 @@ def build(jobs: int = 8, force: bool = True, verbose: bool = False) -> str:
     def compile_one(unit):
         obj, src, extra = unit
         objp = os.path.join(OBJ, obj)
-        if not force and os.path.exists(objp) and not _deps_newer(objp):
+        if not force and os.path.exists(objp) and not _deps_newer(objp, src):
             return objp
         cmd = [cc, *COMMON, *extra, "-c", os.path.join(CSRC, src), "-o", objp]
         if verbose:

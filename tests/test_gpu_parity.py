@@ -90,26 +90,58 @@ def test_pairwise_sqdist_strided_unaligned_and_chunked(algo):
     assert_dist_close(D, wide, ref, algo)
 
 
+@pytest.mark.parametrize("algo", [mb.DIST_GRAM, mb.DIST_GRAM_BF16])
+def test_pairwise_sqdist_every_n_with_aligned_rows(algo):
+    """Rows that start on 16-byte boundaries take the kernel that streams tiles of 128 columns into
+    LDS: every n (every count of load instructions per wave, with and without a missing last row
+    pair), one tile, a few tiles and many tiles per workgroup, each with an element tail."""
+    say("pairwise_sqdist aligned rows, every n", algo)
+    rng = np.random.default_rng(77)
+    wide = (rng.standard_normal((64, 128 * 40 + 64)) + 0.25).astype(np.float32)   # ld % 4 == 0
+    gw = gpu(wide)
+    for n in range(1, 65):
+        for d in (128, 128 * 3 + 77, 128 * 40 + 61):
+            ref = O.pairwise_sqdist(wide[:n, :d])
+            got = mb.pairwise_sqdist(gw[:n, :d], algo=algo)
+            assert_dist_close(got, wide[:n, :d], ref, algo)
+
+
+@pytest.mark.parametrize("algo", [mb.DIST_GRAM, mb.DIST_GRAM_BF16])
+@pytest.mark.parametrize("n", [39, 51])
+def test_pairwise_sqdist_aligned_rows_many_tiles_per_workgroup(n, algo):
+    """More tiles than resident workgroups, so every workgroup walks its tile ring several times."""
+    d = 128 * 5000 + 100
+    say("pairwise_sqdist aligned rows, long", n, d, algo)
+    G = torch.empty(n, d + 28, device=DEV).uniform_(-1.0, 1.0, generator=torch.Generator(DEV).manual_seed(n))[:, :d]
+    assert G.data_ptr() % 16 == 0 and G.stride(0) % 4 == 0
+    Gh = G.cpu().numpy()
+    ref = O.pairwise_sqdist(np.ascontiguousarray(Gh))
+    got = mb.pairwise_sqdist(G, algo=algo)
+    assert_dist_close(got, Gh, ref, algo)
+
+
 @pytest.mark.parametrize("algo", ALGOS)
 def test_identical_rows_tie_exactly(algo):
     say("identical rows", algo)
     rng = np.random.default_rng(11)
-    G = rng.standard_normal((39, 50021)).astype(np.float32)
-    G[33] = G[2]
-    G[17] = G[2]
-    G[38] = G[20]
-    D = mb.pairwise_sqdist(gpu(G), algo=algo).cpu().numpy()
-    assert D[2, 33] == 0.0 and D[2, 17] == 0.0 and D[17, 33] == 0.0 and D[20, 38] == 0.0
-    assert np.array_equal(D[2], D[33]) and np.array_equal(D[2], D[17]) and np.array_equal(D[20], D[38])
+    for d in (50021, 50020):                          # rows not aligned / aligned to 16 bytes
+        G = rng.standard_normal((39, d)).astype(np.float32)
+        G[33] = G[2]
+        G[17] = G[2]
+        G[38] = G[20]
+        D = mb.pairwise_sqdist(gpu(G), algo=algo).cpu().numpy()
+        assert D[2, 33] == 0.0 and D[2, 17] == 0.0 and D[17, 33] == 0.0 and D[20, 38] == 0.0
+        assert np.array_equal(D[2], D[33]) and np.array_equal(D[2], D[17]) and np.array_equal(D[20], D[38])
 
 
 @pytest.mark.parametrize("algo", ALGOS)
 def test_distance_pass_is_deterministic(algo):
     say("determinism", algo)
-    G = gpu(W.make(2, "cpu", d=300_001))
-    a = mb.pairwise_sqdist(G, algo=algo).clone()
-    b = mb.pairwise_sqdist(G, algo=algo)
-    assert torch.equal(a, b)
+    for d in (300_001, 300_032):                      # rows not aligned / aligned to 16 bytes
+        G = gpu(W.make(2, "cpu", d=d))
+        a = mb.pairwise_sqdist(G, algo=algo).clone()
+        b = mb.pairwise_sqdist(G, algo=algo)
+        assert torch.equal(a, b)
 
 
 # --------------------------------------------------------- scores, selection
