@@ -17,8 +17,8 @@ import time
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch of the distance kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
 # scaled by what the same counter reads for a 4 GiB device copy (FETCH_SIZE reads half the bytes
-# of the copy, WRITE_SIZE all of them); see profiles/gram_kernel_cfg4_n39_d250M_hbm_traffic.md
-MEASURED_TRAFFIC_BYTES = {(4, "gram_bf16"): 2 * 19040000 * 1024 + 6144 * 1024}
+# of the copy, WRITE_SIZE all of them); see profiles/gram_dma_kernel_cfg4_n39_d250M_hbm_traffic.md
+MEASURED_TRAFFIC_BYTES = {(4, "gram_bf16"): 2 * 19043035 * 1024 + 9216 * 1024}
 MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix, published
 
@@ -161,8 +161,10 @@ def main():
     achieved = dist_bytes / dist_avg_s / 1e9
     bf16 = a.dist_algo in ("auto", "gram_bf16")
     nb = (n + 15) // 16
-    kname = {"direct": "dist_direct_kernel", "gram": f"gram_kernel<{nb}, fp32>"}.get(
-        a.dist_algo, f"gram_kernel<{nb}, bf16>")
+    # rows that start on 16-byte boundaries take the kernel that streams tiles into LDS
+    gram = "gram_dma_kernel" if (d // nchunks) % 4 == 0 and d // nchunks >= 128 else "gram_kernel"
+    kname = {"direct": "dist_direct_kernel", "gram": f"{gram}<{nb}, fp32>"}.get(
+        a.dist_algo, f"{gram}<{nb}, bf16>")
     roofline = {"kernel": kname, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": MEASURED_TRAFFIC_BYTES.get((a.config, "gram_bf16")) if (bf16 and a.d is None) else None,
