@@ -46,7 +46,7 @@ def units():
          ("rowops.o", "rowops.hip", [])]
     for g in range(8):
         u.append((f"coordwise_g{g}.o", "coordwise.hip", NO_NANS + [f"-DMB_GROUP={g}"]))
-    for g in range(4):
+    for g in range(8):
         u.append((f"coordwise_alg1_g{g}.o", "coordwise_alg1.hip", NO_NANS + [f"-DMB_GROUP={g}"]))
     return u
 
@@ -77,11 +77,12 @@ def build(jobs: int = 8, force: bool = True, verbose: bool = False) -> str:
             raise RuntimeError(f"hipcc failed on {src} ({obj}):\n{r.stdout}\n{r.stderr}")
         return objp
 
-    # biggest units first so the pool stays busy: the sorting networks for large theta
+    # biggest units first so the pool stays busy: the sorting networks for large theta, and the
+    # Algorithm-1 units (two kernels per theta) before the others
     def weight(u):
         name = u[0]
         if name.startswith("coordwise") and name[-4] == "g":
-            return -int(name[-3])
+            return -2 * int(name[-3]) - (1 if "alg1" in name else 0)
         return 1
     order = sorted(units(), key=weight)
     with ThreadPoolExecutor(max_workers=max(1, jobs)) as pool:

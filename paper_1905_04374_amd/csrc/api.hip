@@ -232,11 +232,15 @@ hipError_t launch_coord_selected(const CoordArgs &a, hipStream_t s)
 hipError_t launch_coord_alg1(const CoordAlg1Args &a, hipStream_t s)
 {
     if (a.theta < 1 || a.theta > kMaxN) return hipErrorInvalidValue;
-    switch ((a.theta - 1) / 16) {
+    switch ((a.theta - 1) / 8) {
         case 0: return launch_coord_alg1_group0(a, s);
         case 1: return launch_coord_alg1_group1(a, s);
         case 2: return launch_coord_alg1_group2(a, s);
-        default: return launch_coord_alg1_group3(a, s);
+        case 3: return launch_coord_alg1_group3(a, s);
+        case 4: return launch_coord_alg1_group4(a, s);
+        case 5: return launch_coord_alg1_group5(a, s);
+        case 6: return launch_coord_alg1_group6(a, s);
+        default: return launch_coord_alg1_group7(a, s);
     }
 }
 }  // namespace mb

@@ -15,14 +15,14 @@
 // the update lists index rows at run time.  Rows that no round uses are not
 // read at all.
 //
-// Compiled once per group of 16 values of theta (-DMB_GROUP=0..3).
+// Compiled once per group of 8 values of theta (-DMB_GROUP=0..7).
 #include <hip/hip_runtime.h>
 
 #include "mb_internal.hpp"
 #include "sortnet.hpp"
 
 #ifndef MB_GROUP
-#error "compile with -DMB_GROUP=0..3"
+#error "compile with -DMB_GROUP=0..7"
 #endif
 
 namespace mb {
@@ -243,13 +243,12 @@ hipError_t launch_theta(const CoordAlg1Args &a, hipStream_t s)
 #define MB_CAT2(a, b) a##b
 #define MB_CAT(a, b) MB_CAT2(a, b)
 #define MB_CASE(k) \
-    case k: return launch_theta<16 * MB_GROUP + k>(a, s);
+    case k: return launch_theta<8 * MB_GROUP + k>(a, s);
 
 hipError_t MB_CAT(launch_coord_alg1_group, MB_GROUP)(const CoordAlg1Args &a, hipStream_t s)
 {
-    switch (a.theta - 16 * MB_GROUP) {
+    switch (a.theta - 8 * MB_GROUP) {
         MB_CASE(1) MB_CASE(2) MB_CASE(3) MB_CASE(4) MB_CASE(5) MB_CASE(6) MB_CASE(7) MB_CASE(8)
-        MB_CASE(9) MB_CASE(10) MB_CASE(11) MB_CASE(12) MB_CASE(13) MB_CASE(14) MB_CASE(15) MB_CASE(16)
         default: return hipErrorInvalidValue;
     }
 }

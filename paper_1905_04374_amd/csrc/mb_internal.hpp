@@ -69,11 +69,15 @@ struct CoordAlg1Args {
     float *out;
 };
 hipError_t launch_coord_alg1(const CoordAlg1Args &a, hipStream_t s);
-// one per translation unit, covering theta in [16g+1, 16g+16]
+// one per translation unit, covering theta in [8g+1, 8g+8]
 hipError_t launch_coord_alg1_group0(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_group1(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_group2(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_group3(const CoordAlg1Args &a, hipStream_t s);
+hipError_t launch_coord_alg1_group4(const CoordAlg1Args &a, hipStream_t s);
+hipError_t launch_coord_alg1_group5(const CoordAlg1Args &a, hipStream_t s);
+hipError_t launch_coord_alg1_group6(const CoordAlg1Args &a, hipStream_t s);
+hipError_t launch_coord_alg1_group7(const CoordAlg1Args &a, hipStream_t s);
 
 // out[c] = mean over rows r with mask[r] of G[r][c]
 hipError_t launch_masked_mean(const float *G, int n, int64_t d, int64_t ld, const uint8_t *mask,
