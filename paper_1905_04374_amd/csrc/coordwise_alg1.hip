@@ -64,9 +64,11 @@ __device__ __forceinline__ float pick_closest(float (&a)[THETA], float med, int 
     return sum / (float)beta;
 }
 
-// FAST = true handles the regular case and does nothing otherwise; FAST = false the reverse.  Both
-// are launched: which case holds is only known on the device.
-template <int THETA, bool FAST>
+// MODE 1 and 2 handle the regular case and do nothing otherwise; MODE 0 the reverse.  Two kernels
+// are launched (0 and one of 1, 2): which case holds is only known on the device.  MODE 2 is the
+// regular case with beta = 1: the one value closest to the median is picked while the running sums
+// are formed, which keeps the kernel at half the registers and twice the waves.
+template <int THETA, int MODE>
 __global__ __launch_bounds__(kThreads) void coord_alg1_kernel(
     const float *__restrict__ G, int n, int64_t d, int64_t ld, const int32_t *__restrict__ sel,
     const uint8_t *__restrict__ sets, int beta, float *__restrict__ out)
@@ -149,40 +151,87 @@ __global__ __launch_bounds__(kThreads) void coord_alg1_kernel(
 
     const int64_t ntiles = (d + kThreads - 1) / kThreads;
     const bool regular = !not_nested && !bad;
+    constexpr bool FAST = MODE != 0;
     if (regular != FAST) return;
     if constexpr (FAST) {
         // Regular case: set_t = set_{theta-1} + {winner_t .. winner_{theta-2}}.  The averages are
         // then running sums over the winners' values, which the median needs anyway: theta + f
         // coalesced row streams, everything in registers, no LDS.
-        const int nb = nbase;
+        const int nb = __builtin_amdgcn_readfirstlane(nbase);
+        // the plan is the same for every tile: winners and weights go to scalar registers once
+        // (with the default theta the last round's set has f + 1 members: f <= 15 base rows)
+        constexpr int kBaseRegs = 16;
+        int wr[THETA], br[kBaseRegs];
+        float im[THETA];
+#pragma unroll
+        for (int t = 0; t < THETA; ++t) {
+            wr[t] = __builtin_amdgcn_readfirstlane(wrow[t]);
+            im[t] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(inv_m[t])));
+        }
+#pragma unroll
+        for (int j = 0; j < kBaseRegs; ++j) br[j] = __builtin_amdgcn_readfirstlane(brows[j < nb ? j : 0]);
         for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
             const int64_t c = tile * kThreads + tid;
             if (c >= d) continue;
-            float e[THETA], a[THETA];
+            float e[THETA];
 #pragma unroll
-            for (int t = 0; t < THETA; ++t)
-                e[t] = __builtin_nontemporal_load(G + (int64_t)__builtin_amdgcn_readfirstlane(wrow[t]) * ld + c);
+            for (int t = 0; t < THETA; ++t) e[t] = __builtin_nontemporal_load(G + (int64_t)wr[t] * ld + c);
             float S = 0.0f;
-            for (int s0 = 0; s0 < nb; s0 += 8) {     // base rows, eight loads in flight at a time
+            {
+                float xb[kBaseRegs];
+#pragma unroll
+                for (int j = 0; j < kBaseRegs; ++j) {
+                    xb[j] = 0.0f;
+                    if (j < nb)                      // same for the whole workgroup
+                        xb[j] = __builtin_nontemporal_load(G + (int64_t)br[j] * ld + c);
+                }
+#pragma unroll
+                for (int j = 0; j < kBaseRegs; ++j) S += xb[j];
+            }
+            for (int s0 = kBaseRegs; s0 < nb; s0 += 8) {   // more base rows than registers were set aside for
                 float xb[8];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const int row = __builtin_amdgcn_readfirstlane(brows[s0 + j < nb ? s0 + j : s0]);
-                    xb[j] = __builtin_nontemporal_load(G + (int64_t)row * ld + c);
+                    xb[j] = 0.0f;
+                    if (s0 + j < nb)
+                        xb[j] = __builtin_nontemporal_load(
+                            G + (int64_t)__builtin_amdgcn_readfirstlane(brows[s0 + j]) * ld + c);
                 }
 #pragma unroll
-                for (int j = 0; j < 8; ++j) S += (s0 + j < nb) ? xb[j] : 0.0f;
+                for (int j = 0; j < 8; ++j) S += xb[j];
             }
+            if constexpr (MODE == 2) {
+                float es[THETA];
 #pragma unroll
-            for (int t = THETA - 1; t >= 0; --t) {
-                S += e[t];
-                a[t] = S * inv_m[t];
+                for (int t = 0; t < THETA; ++t) es[t] = e[t];
+                sort_registers<THETA>(es);
+                float med;
+                if constexpr (THETA & 1) med = es[THETA / 2];
+                else med = 0.5f * (es[THETA / 2 - 1] + es[THETA / 2]);
+                float best = 0.0f, bd = __builtin_huge_valf();
+#pragma unroll
+                for (int t = THETA - 1; t >= 0; --t) {
+                    S += e[t];
+                    const float at = S * im[t];
+                    const float dt = fabsf(at - med);
+                    const bool take = dt < bd || (dt == bd && at < best);
+                    best = take ? at : best;
+                    bd = take ? dt : bd;
+                }
+                out[c] = best;
+            } else {
+                float a[THETA];
+#pragma unroll
+                for (int t = THETA - 1; t >= 0; --t) {
+                    S += e[t];
+                    a[t] = S * im[t];
+                }
+                sort_registers<THETA>(e);
+                float med;
+                if constexpr (THETA & 1) med = e[THETA / 2];
+                else med = 0.5f * (e[THETA / 2 - 1] + e[THETA / 2]);
+                out[c] = pick_closest<THETA>(a, med, beta);
             }
-            sort_registers<THETA>(e);
-            float med;
-            if constexpr (THETA & 1) med = e[THETA / 2];
-            else med = 0.5f * (e[THETA / 2 - 1] + e[THETA / 2]);
-            out[c] = pick_closest<THETA>(a, med, beta);
         }
     } else {
     float *my = stage + (size_t)wave * U * 64;
@@ -231,10 +280,14 @@ hipError_t launch_theta(const CoordAlg1Args &a, hipStream_t s)
     const size_t lds = (size_t)kWaves * a.n * 64 * sizeof(float);   // at most n rows are parked
     const int64_t ntiles = (a.d + kThreads - 1) / kThreads;
     const int grid = (int)(ntiles < 2048 ? ntiles : 2048);
-    coord_alg1_kernel<THETA, true><<<dim3(grid), dim3(kThreads), 0, s>>>(a.G, a.n, a.d, a.ld, a.sel,
-                                                                         a.agr_sets, a.beta, a.out);
-    coord_alg1_kernel<THETA, false><<<dim3(grid), dim3(kThreads), lds, s>>>(a.G, a.n, a.d, a.ld, a.sel,
-                                                                            a.agr_sets, a.beta, a.out);
+    if (a.beta == 1)
+        coord_alg1_kernel<THETA, 2><<<dim3(grid), dim3(kThreads), 0, s>>>(a.G, a.n, a.d, a.ld, a.sel, a.agr_sets,
+                                                                          a.beta, a.out);
+    else
+        coord_alg1_kernel<THETA, 1><<<dim3(grid), dim3(kThreads), 0, s>>>(a.G, a.n, a.d, a.ld, a.sel, a.agr_sets,
+                                                                          a.beta, a.out);
+    coord_alg1_kernel<THETA, 0><<<dim3(grid), dim3(kThreads), lds, s>>>(a.G, a.n, a.d, a.ld, a.sel, a.agr_sets,
+                                                                        a.beta, a.out);
     return hipGetLastError();
 }
 
