@@ -30,6 +30,7 @@ namespace {
 
 constexpr int kThreads = 128;   // 2 waves: the staging area is n x 256 bytes per wave
 constexpr int kWaves = kThreads / 64;
+typedef float floatx2 __attribute__((ext_vector_type(2)));
 
 // average of the beta values a[.] closest to med (closeness |a - med| in fp32, ties to the smaller value)
 template <int THETA>
@@ -170,67 +171,112 @@ __global__ __launch_bounds__(kThreads) void coord_alg1_kernel(
         }
 #pragma unroll
         for (int j = 0; j < kBaseRegs; ++j) br[j] = __builtin_amdgcn_readfirstlane(brows[j < nb ? j : 0]);
-        for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-            const int64_t c = tile * kThreads + tid;
+        // With beta = 1 a lane owns two neighbouring coordinates (8-byte loads when the rows allow it).
+        constexpr int VEC = MODE == 2 ? 2 : 1;
+        const bool pairs_ok = VEC == 2 && ((uintptr_t)G % 8 == 0) && (ld % 2 == 0) && ((uintptr_t)out % 8 == 0);
+        const int64_t nvt = (d + VEC * kThreads - 1) / (VEC * kThreads);
+        for (int64_t tile = blockIdx.x; tile < nvt; tile += gridDim.x) {
+            const int64_t c = (tile * kThreads + tid) * VEC;
             if (c >= d) continue;
-            float e[THETA];
+            const bool two = VEC == 2 && c + 1 < d;
+            const bool vec = pairs_ok && two;
+            float x[2];
+            auto load = [&](int row) {
+                const float *p = G + (int64_t)row * ld + c;
+                if (vec) {
+                    const floatx2 v = __builtin_nontemporal_load(reinterpret_cast<const floatx2 *>(p));
+                    x[0] = v[0];
+                    x[1] = v[1];
+                } else {
+                    x[0] = __builtin_nontemporal_load(p);
+                    x[1] = two ? __builtin_nontemporal_load(p + 1) : x[0];
+                }
+            };
+            float e[VEC][THETA];
 #pragma unroll
-            for (int t = 0; t < THETA; ++t) e[t] = __builtin_nontemporal_load(G + (int64_t)wr[t] * ld + c);
-            float S = 0.0f;
+            for (int t = 0; t < THETA; ++t) {
+                load(wr[t]);
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) e[k][t] = x[k];
+            }
+            float S[VEC];
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) S[k] = 0.0f;
             {
-                float xb[kBaseRegs];
+                float xb[VEC][kBaseRegs];
 #pragma unroll
                 for (int j = 0; j < kBaseRegs; ++j) {
-                    xb[j] = 0.0f;
-                    if (j < nb)                      // same for the whole workgroup
-                        xb[j] = __builtin_nontemporal_load(G + (int64_t)br[j] * ld + c);
+#pragma unroll
+                    for (int k = 0; k < VEC; ++k) xb[k][j] = 0.0f;
+                    if (j < nb) {                    // same for the whole workgroup
+                        load(br[j]);
+#pragma unroll
+                        for (int k = 0; k < VEC; ++k) xb[k][j] = x[k];
+                    }
                 }
 #pragma unroll
-                for (int j = 0; j < kBaseRegs; ++j) S += xb[j];
+                for (int j = 0; j < kBaseRegs; ++j)
+#pragma unroll
+                    for (int k = 0; k < VEC; ++k) S[k] += xb[k][j];
             }
             for (int s0 = kBaseRegs; s0 < nb; s0 += 8) {   // more base rows than registers were set aside for
-                float xb[8];
+                float xb[VEC][8];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    xb[j] = 0.0f;
-                    if (s0 + j < nb)
-                        xb[j] = __builtin_nontemporal_load(
-                            G + (int64_t)__builtin_amdgcn_readfirstlane(brows[s0 + j]) * ld + c);
+#pragma unroll
+                    for (int k = 0; k < VEC; ++k) xb[k][j] = 0.0f;
+                    if (s0 + j < nb) {
+                        load(__builtin_amdgcn_readfirstlane(brows[s0 + j]));
+#pragma unroll
+                        for (int k = 0; k < VEC; ++k) xb[k][j] = x[k];
+                    }
                 }
 #pragma unroll
-                for (int j = 0; j < 8; ++j) S += xb[j];
+                for (int j = 0; j < 8; ++j)
+#pragma unroll
+                    for (int k = 0; k < VEC; ++k) S[k] += xb[k][j];
             }
-            if constexpr (MODE == 2) {
-                float es[THETA];
+            float res[VEC];
 #pragma unroll
-                for (int t = 0; t < THETA; ++t) es[t] = e[t];
-                sort_registers<THETA>(es);
-                float med;
-                if constexpr (THETA & 1) med = es[THETA / 2];
-                else med = 0.5f * (es[THETA / 2 - 1] + es[THETA / 2]);
-                float best = 0.0f, bd = __builtin_huge_valf();
+            for (int k = 0; k < VEC; ++k) {
+                if constexpr (MODE == 2) {
+                    float es[THETA];
 #pragma unroll
-                for (int t = THETA - 1; t >= 0; --t) {
-                    S += e[t];
-                    const float at = S * im[t];
-                    const float dt = fabsf(at - med);
-                    const bool take = dt < bd || (dt == bd && at < best);
-                    best = take ? at : best;
-                    bd = take ? dt : bd;
+                    for (int t = 0; t < THETA; ++t) es[t] = e[k][t];
+                    sort_registers<THETA>(es);
+                    float med;
+                    if constexpr (THETA & 1) med = es[THETA / 2];
+                    else med = 0.5f * (es[THETA / 2 - 1] + es[THETA / 2]);
+                    float best = 0.0f, bd = __builtin_huge_valf();
+#pragma unroll
+                    for (int t = THETA - 1; t >= 0; --t) {
+                        S[k] += e[k][t];
+                        const float at = S[k] * im[t];
+                        const float dt = fabsf(at - med);
+                        const bool take = dt < bd || (dt == bd && at < best);
+                        best = take ? at : best;
+                        bd = take ? dt : bd;
+                    }
+                    res[k] = best;
+                } else {
+                    float a[THETA];
+#pragma unroll
+                    for (int t = THETA - 1; t >= 0; --t) {
+                        S[k] += e[k][t];
+                        a[t] = S[k] * im[t];
+                    }
+                    sort_registers<THETA>(e[k]);
+                    float med;
+                    if constexpr (THETA & 1) med = e[k][THETA / 2];
+                    else med = 0.5f * (e[k][THETA / 2 - 1] + e[k][THETA / 2]);
+                    res[k] = pick_closest<THETA>(a, med, beta);
                 }
-                out[c] = best;
+            }
+            if (vec) {
+                __builtin_nontemporal_store(floatx2{res[0], res[VEC - 1]}, reinterpret_cast<floatx2 *>(out + c));
             } else {
-                float a[THETA];
-#pragma unroll
-                for (int t = THETA - 1; t >= 0; --t) {
-                    S += e[t];
-                    a[t] = S * im[t];
-                }
-                sort_registers<THETA>(e);
-                float med;
-                if constexpr (THETA & 1) med = e[THETA / 2];
-                else med = 0.5f * (e[THETA / 2 - 1] + e[THETA / 2]);
-                out[c] = pick_closest<THETA>(a, med, beta);
+                out[c] = res[0];
+                if (two) out[c + 1] = res[VEC - 1];
             }
         }
     } else {
