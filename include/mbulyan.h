@@ -186,6 +186,9 @@ int multikrum_select(const double *dist, int n, int f, int theta,
  *   selected_idx device, theta int32 in [0, n), validated on the device: an
  *                out-of-range index makes the kernel write NaN to out
  *   out          device, d floats
+ * With agr_sets != NULL a 1 KB plan is kept in the library's own workspace
+ * (allocated on the first such call on a device; calls that use it must not
+ * overlap on one device).
  */
 int coordwise_trimmed_avg(const float *grads, int n, int64_t d, int64_t ld,
                           const int32_t *selected_idx, int theta, int beta,

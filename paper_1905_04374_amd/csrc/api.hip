@@ -34,7 +34,9 @@ constexpr size_t kOffReduced = kOffDist + 64 * 64 * 8;           // up to 2560 d
 constexpr size_t kOffSel = kOffReduced + 2560 * 8;               // 64 int32
 constexpr size_t kOffM = kOffSel + 256;                          // 64 int32
 constexpr size_t kOffSets = kOffM + 256;                         // 64*64 bytes
-constexpr size_t kOffPartials = kOffSets + 4096;
+constexpr size_t kOffPlan = kOffSets + 4096;                     // plan of the Algorithm-1 coordinate pass
+constexpr size_t kOffPartials = kOffPlan + 1024;
+static_assert(mb::kPlanWords * sizeof(int32_t) <= 1024, "plan segment");
 
 struct Workspace {
     char *base;
@@ -43,6 +45,7 @@ struct Workspace {
     int32_t *sel() const { return reinterpret_cast<int32_t *>(base + kOffSel); }
     int32_t *m() const { return reinterpret_cast<int32_t *>(base + kOffM); }
     uint8_t *sets() const { return reinterpret_cast<uint8_t *>(base + kOffSets); }
+    int32_t *plan() const { return reinterpret_cast<int32_t *>(base + kOffPlan); }
     double *partials() const { return reinterpret_cast<double *>(base + kOffPartials); }
 };
 
@@ -188,14 +191,15 @@ int run_dist(const float *grads, int n, int64_t d, int64_t ld, double *dist, int
 }
 
 int run_coord(const float *grads, int n, int64_t d, int64_t ld, int mode, int theta, int beta,
-              const int32_t *sel, const uint8_t *sets, float *out, hipStream_t s)
+              const int32_t *sel, const uint8_t *sets, int32_t *plan, float *out, hipStream_t s)
 {
     StageTimer t(MB_STAGE_COORD, s);
     if (mode == MB_MODE_SELECTED) {
         mb::CoordArgs a{grads, n, d, ld, sel, theta, beta, 0, out};
         MB_HIP(mb::launch_coord_selected(a, s));
     } else {
-        mb::CoordAlg1Args a{grads, n, d, ld, sel, sets, theta, beta, out};
+        mb::CoordAlg1Args a{grads, n, d, ld, sel, sets, theta, beta, out, plan};
+        MB_HIP(mb::launch_alg1_plan(n, theta, sel, sets, plan, s));
         MB_HIP(mb::launch_coord_alg1(a, s));
     }
     return MB_OK;
@@ -329,8 +333,13 @@ int coordwise_trimmed_avg(const float *grads, int n, int64_t d, int64_t ld, cons
     const int rc = check_matrix(grads, n, d, ld);
     if (rc != MB_OK) return rc;
     if (!selected_idx || !out || theta < 1 || theta > n || beta < 1 || beta > theta) return MB_EINVAL;
+    Workspace ws{nullptr};
+    if (agr_sets) {   // the Algorithm-1 pass keeps its plan in the library's own workspace
+        const int wrc = own_workspace(kOffPartials, &ws);
+        if (wrc != MB_OK) return wrc;
+    }
     return run_coord(grads, n, d, ld, agr_sets ? MB_MODE_ALG1 : MB_MODE_SELECTED, theta, beta,
-                     selected_idx, agr_sets, out, (hipStream_t)stream);
+                     selected_idx, agr_sets, agr_sets ? ws.plan() : nullptr, out, (hipStream_t)stream);
 }
 
 int mbulyan_aggregate_chunked(const float *const *chunks, int nchunks, const int64_t *chunk_d,
@@ -362,7 +371,7 @@ int mbulyan_aggregate_chunked(const float *const *chunks, int nchunks, const int
                                  mode == MB_MODE_ALG1 ? ws.sets() : nullptr, ws.m(), nullptr, s));
     }
     for (int c = 0; c < nchunks; ++c) {
-        rc = run_coord(chunks[c], n, chunk_d[c], chunk_ld[c], mode, theta, beta, ws.sel(), ws.sets(),
+        rc = run_coord(chunks[c], n, chunk_d[c], chunk_ld[c], mode, theta, beta, ws.sel(), ws.sets(), ws.plan(),
                        outs[c], s);
         if (rc != MB_OK) return rc;
     }
@@ -391,7 +400,7 @@ int mbulyan_aggregate_ex(const float *grads, int n, int f, int64_t d, int64_t ld
         MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, ws.sel(),
                                  mode == MB_MODE_ALG1 ? ws.sets() : nullptr, ws.m(), nullptr, s));
     }
-    rc = run_coord(grads, n, d, ld, mode, theta, beta, ws.sel(), ws.sets(), out, s);
+    rc = run_coord(grads, n, d, ld, mode, theta, beta, ws.sel(), ws.sets(), ws.plan(), out, s);
     if (rc != MB_OK) return rc;
     if (selected_idx)
         MB_HIP(hipMemcpyAsync(selected_idx, ws.sel(), sizeof(int32_t) * theta, hipMemcpyDeviceToDevice, s));

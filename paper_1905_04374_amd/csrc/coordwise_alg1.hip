@@ -65,15 +65,139 @@ __device__ __forceinline__ float pick_closest(float (&a)[THETA], float med, int 
     return sum / (float)beta;
 }
 
-// MODE 1 and 2 handle the regular case and do nothing otherwise; MODE 0 the reverse.  Two kernels
-// are launched (0 and one of 1, 2): which case holds is only known on the device.  MODE 2 is the
-// regular case with beta = 1: the one value closest to the median is picked while the running sums
-// are formed, which keeps the kernel at half the registers and twice the waves.
-template <int THETA, int MODE>
-__global__ __launch_bounds__(kThreads) void coord_alg1_kernel(
-    const float *__restrict__ G, int n, int64_t d, int64_t ld, const int32_t *__restrict__ sel,
-    const uint8_t *__restrict__ sets, int beta, float *__restrict__ out)
+// The regular case: from one round to the next the set only loses its winner, so
+// set_t = set_{theta-1} + {winner_t .. winner_{theta-2}}.  The averages are then running sums over
+// the winners' values, which the median needs anyway: theta + f coalesced row streams, everything
+// in registers, no LDS.  The plan (winners, base rows, weights) comes from launch_alg1_plan through
+// scalar loads; every workgroup takes one tile and ends (measured faster than workgroups that
+// loop over tiles, as in the other coordinate kernel).  B1: beta = 1, the one average closest to
+// the median is picked while the running sums are formed (half the registers); a lane then owns
+// two neighbouring coordinates.
+constexpr int kRegThreads = 256;
+constexpr int kBaseRegs = 16;   // base rows loaded in one batch (the default theta leaves f <= 15)
+
+template <int THETA, bool B1>
+__global__ __launch_bounds__(kRegThreads) void coord_alg1_regular_kernel(
+    const float *__restrict__ G, int64_t d, int64_t ld, int beta, const int32_t *__restrict__ plan,
+    float *__restrict__ out)
 {
+    if (!plan[kPlanRegular]) return;
+    constexpr int VEC = B1 ? 2 : 1;
+    const int64_t c = ((int64_t)blockIdx.x * kRegThreads + threadIdx.x) * VEC;
+    if (c >= d) return;
+    const int nb = plan[kPlanNBase];
+    const float *inv_m = reinterpret_cast<const float *>(plan + kPlanInvM);
+    const bool pairs_ok = VEC == 2 && ((uintptr_t)G % 8 == 0) && (ld % 2 == 0) && ((uintptr_t)out % 8 == 0);
+    const bool two = VEC == 2 && c + 1 < d;
+    const bool vec = pairs_ok && two;
+    float x[2];
+    auto load = [&](int row) {
+        const float *p = G + (int64_t)row * ld + c;
+        if (vec) {
+            const floatx2 v = __builtin_nontemporal_load(reinterpret_cast<const floatx2 *>(p));
+            x[0] = v[0];
+            x[1] = v[1];
+        } else {
+            x[0] = __builtin_nontemporal_load(p);
+            x[1] = two ? __builtin_nontemporal_load(p + 1) : x[0];
+        }
+    };
+    float e[VEC][THETA];
+#pragma unroll
+    for (int t = 0; t < THETA; ++t) {
+        load(plan[kPlanWinner + t]);
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) e[k][t] = x[k];
+    }
+    float S[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) S[k] = 0.0f;
+    {
+        float xb[VEC][kBaseRegs];
+#pragma unroll
+        for (int j = 0; j < kBaseRegs; ++j) {
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) xb[k][j] = 0.0f;
+            if (j < nb) {                    // same for every lane
+                load(plan[kPlanBase + j]);
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) xb[k][j] = x[k];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kBaseRegs; ++j)
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) S[k] += xb[k][j];
+    }
+    for (int s0 = kBaseRegs; s0 < nb; s0 += 8) {   // more base rows than one batch
+        float xb[VEC][8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) xb[k][j] = 0.0f;
+            if (s0 + j < nb) {
+                load(plan[kPlanBase + s0 + j]);
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) xb[k][j] = x[k];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) S[k] += xb[k][j];
+    }
+    float res[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+        if constexpr (B1) {
+            float es[THETA];
+#pragma unroll
+            for (int t = 0; t < THETA; ++t) es[t] = e[k][t];
+            sort_registers<THETA>(es);
+            float med;
+            if constexpr (THETA & 1) med = es[THETA / 2];
+            else med = 0.5f * (es[THETA / 2 - 1] + es[THETA / 2]);
+            float best = 0.0f, bd = __builtin_huge_valf();
+#pragma unroll
+            for (int t = THETA - 1; t >= 0; --t) {
+                S[k] += e[k][t];
+                const float at = S[k] * inv_m[t];
+                const float dt = fabsf(at - med);
+                const bool take = dt < bd || (dt == bd && at < best);
+                best = take ? at : best;
+                bd = take ? dt : bd;
+            }
+            res[k] = best;
+        } else {
+            float a[THETA];
+#pragma unroll
+            for (int t = THETA - 1; t >= 0; --t) {
+                S[k] += e[k][t];
+                a[t] = S[k] * inv_m[t];
+            }
+            sort_registers<THETA>(e[k]);
+            float med;
+            if constexpr (THETA & 1) med = e[k][THETA / 2];
+            else med = 0.5f * (e[k][THETA / 2 - 1] + e[k][THETA / 2]);
+            res[k] = pick_closest<THETA>(a, med, beta);
+        }
+    }
+    if (vec) {
+        __builtin_nontemporal_store(floatx2{res[0], res[VEC - 1]}, reinterpret_cast<floatx2 *>(out + c));
+    } else {
+        out[c] = res[0];
+        if (two) out[c + 1] = res[VEC - 1];
+    }
+}
+
+// The general case (some round's set is not "the previous set minus its winner"); returns at once
+// when the plan says the regular kernel handles the call.
+template <int THETA>
+__global__ __launch_bounds__(kThreads) void coord_alg1_general_kernel(
+    const float *__restrict__ G, int n, int64_t d, int64_t ld, const int32_t *__restrict__ sel,
+    const uint8_t *__restrict__ sets, int beta, const int32_t *__restrict__ plan, float *__restrict__ out)
+{
+    if (plan[kPlanRegular]) return;
     extern __shared__ float stage[];                 // [kWaves][slots][64]
     __shared__ unsigned char ops[kMaxN * kMaxN];     // slot | 0x80 if the row leaves the set
     __shared__ int off[kMaxN + 1];                   // ops of round t: [off[t], off[t+1])
@@ -84,17 +208,13 @@ __global__ __launch_bounds__(kThreads) void coord_alg1_kernel(
     __shared__ int wslot[kMaxN];                     // slot of the winner of round t
     __shared__ int nslots;
     __shared__ int bad_flag;
-    __shared__ int not_nested;                       // some round's set is not "previous set minus its winner"
-    __shared__ int brows[kMaxN];                     // rows of the last round's set, its winner left out
-    __shared__ int nbase;
-    __shared__ int wrow[kMaxN];                      // winner of round t
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
 
     // ---- plan: which rows are read, and the signed row updates of every round -------------
-    if (tid == 0) { bad_flag = 0; not_nested = 0; }
+    if (tid == 0) bad_flag = 0;
     if (tid < kMaxN) need[tid] = 0;
     __syncthreads();
     int my_count = 0, my_m = 0;
@@ -109,18 +229,8 @@ __global__ __launch_bounds__(kThreads) void coord_alg1_kernel(
         const int w = sel[tid];
         if ((unsigned)w >= (unsigned)n) bad_flag = 1;
         else need[w] = 1;
-        wrow[tid] = ((unsigned)w < (unsigned)n) ? w : 0;
         inv_m[tid] = my_m > 0 ? 1.0f / (float)my_m : 0.0f;
         off[tid + 1] = my_count;
-        // the regular case: from one round to the next the set only loses its winner
-        bool ok = (unsigned)w < (unsigned)n && sets[tid * n + ((unsigned)w < (unsigned)n ? w : 0)] != 0;
-        if (tid + 1 < THETA)
-            for (int r = 0; r < n; ++r) {
-                const int cur = sets[tid * n + r] ? 1 : 0;
-                const int nxt = sets[(tid + 1) * n + r] ? 1 : 0;
-                ok = ok && (nxt == ((r == w) ? 0 : cur));
-            }
-        if (!ok) not_nested = 1;
     }
     __syncthreads();
     if (tid == 0) {
@@ -130,10 +240,6 @@ __global__ __launch_bounds__(kThreads) void coord_alg1_kernel(
         for (int r = 0; r < n; ++r)
             if (need[r]) { slot_of[r] = (unsigned char)ns; rows[ns] = r; ++ns; }
         nslots = ns;
-        int nb = 0;
-        for (int r = 0; r < n; ++r)
-            if (sets[(THETA - 1) * n + r] && r != sel[THETA - 1]) brows[nb++] = r;
-        nbase = nb;
     }
     __syncthreads();
     if (tid < THETA) {
@@ -151,135 +257,6 @@ __global__ __launch_bounds__(kThreads) void coord_alg1_kernel(
     const int U = nslots;
 
     const int64_t ntiles = (d + kThreads - 1) / kThreads;
-    const bool regular = !not_nested && !bad;
-    constexpr bool FAST = MODE != 0;
-    if (regular != FAST) return;
-    if constexpr (FAST) {
-        // Regular case: set_t = set_{theta-1} + {winner_t .. winner_{theta-2}}.  The averages are
-        // then running sums over the winners' values, which the median needs anyway: theta + f
-        // coalesced row streams, everything in registers, no LDS.
-        const int nb = __builtin_amdgcn_readfirstlane(nbase);
-        // the plan is the same for every tile: winners and weights go to scalar registers once
-        // (with the default theta the last round's set has f + 1 members: f <= 15 base rows)
-        constexpr int kBaseRegs = 16;
-        int wr[THETA], br[kBaseRegs];
-        float im[THETA];
-#pragma unroll
-        for (int t = 0; t < THETA; ++t) {
-            wr[t] = __builtin_amdgcn_readfirstlane(wrow[t]);
-            im[t] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(inv_m[t])));
-        }
-#pragma unroll
-        for (int j = 0; j < kBaseRegs; ++j) br[j] = __builtin_amdgcn_readfirstlane(brows[j < nb ? j : 0]);
-        // With beta = 1 a lane owns two neighbouring coordinates (8-byte loads when the rows allow it).
-        constexpr int VEC = MODE == 2 ? 2 : 1;
-        const bool pairs_ok = VEC == 2 && ((uintptr_t)G % 8 == 0) && (ld % 2 == 0) && ((uintptr_t)out % 8 == 0);
-        const int64_t nvt = (d + VEC * kThreads - 1) / (VEC * kThreads);
-        for (int64_t tile = blockIdx.x; tile < nvt; tile += gridDim.x) {
-            const int64_t c = (tile * kThreads + tid) * VEC;
-            if (c >= d) continue;
-            const bool two = VEC == 2 && c + 1 < d;
-            const bool vec = pairs_ok && two;
-            float x[2];
-            auto load = [&](int row) {
-                const float *p = G + (int64_t)row * ld + c;
-                if (vec) {
-                    const floatx2 v = __builtin_nontemporal_load(reinterpret_cast<const floatx2 *>(p));
-                    x[0] = v[0];
-                    x[1] = v[1];
-                } else {
-                    x[0] = __builtin_nontemporal_load(p);
-                    x[1] = two ? __builtin_nontemporal_load(p + 1) : x[0];
-                }
-            };
-            float e[VEC][THETA];
-#pragma unroll
-            for (int t = 0; t < THETA; ++t) {
-                load(wr[t]);
-#pragma unroll
-                for (int k = 0; k < VEC; ++k) e[k][t] = x[k];
-            }
-            float S[VEC];
-#pragma unroll
-            for (int k = 0; k < VEC; ++k) S[k] = 0.0f;
-            {
-                float xb[VEC][kBaseRegs];
-#pragma unroll
-                for (int j = 0; j < kBaseRegs; ++j) {
-#pragma unroll
-                    for (int k = 0; k < VEC; ++k) xb[k][j] = 0.0f;
-                    if (j < nb) {                    // same for the whole workgroup
-                        load(br[j]);
-#pragma unroll
-                        for (int k = 0; k < VEC; ++k) xb[k][j] = x[k];
-                    }
-                }
-#pragma unroll
-                for (int j = 0; j < kBaseRegs; ++j)
-#pragma unroll
-                    for (int k = 0; k < VEC; ++k) S[k] += xb[k][j];
-            }
-            for (int s0 = kBaseRegs; s0 < nb; s0 += 8) {   // more base rows than registers were set aside for
-                float xb[VEC][8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-#pragma unroll
-                    for (int k = 0; k < VEC; ++k) xb[k][j] = 0.0f;
-                    if (s0 + j < nb) {
-                        load(__builtin_amdgcn_readfirstlane(brows[s0 + j]));
-#pragma unroll
-                        for (int k = 0; k < VEC; ++k) xb[k][j] = x[k];
-                    }
-                }
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-#pragma unroll
-                    for (int k = 0; k < VEC; ++k) S[k] += xb[k][j];
-            }
-            float res[VEC];
-#pragma unroll
-            for (int k = 0; k < VEC; ++k) {
-                if constexpr (MODE == 2) {
-                    float es[THETA];
-#pragma unroll
-                    for (int t = 0; t < THETA; ++t) es[t] = e[k][t];
-                    sort_registers<THETA>(es);
-                    float med;
-                    if constexpr (THETA & 1) med = es[THETA / 2];
-                    else med = 0.5f * (es[THETA / 2 - 1] + es[THETA / 2]);
-                    float best = 0.0f, bd = __builtin_huge_valf();
-#pragma unroll
-                    for (int t = THETA - 1; t >= 0; --t) {
-                        S[k] += e[k][t];
-                        const float at = S[k] * im[t];
-                        const float dt = fabsf(at - med);
-                        const bool take = dt < bd || (dt == bd && at < best);
-                        best = take ? at : best;
-                        bd = take ? dt : bd;
-                    }
-                    res[k] = best;
-                } else {
-                    float a[THETA];
-#pragma unroll
-                    for (int t = THETA - 1; t >= 0; --t) {
-                        S[k] += e[k][t];
-                        a[t] = S[k] * im[t];
-                    }
-                    sort_registers<THETA>(e[k]);
-                    float med;
-                    if constexpr (THETA & 1) med = e[k][THETA / 2];
-                    else med = 0.5f * (e[k][THETA / 2 - 1] + e[k][THETA / 2]);
-                    res[k] = pick_closest<THETA>(a, med, beta);
-                }
-            }
-            if (vec) {
-                __builtin_nontemporal_store(floatx2{res[0], res[VEC - 1]}, reinterpret_cast<floatx2 *>(out + c));
-            } else {
-                out[c] = res[0];
-                if (two) out[c + 1] = res[VEC - 1];
-            }
-        }
-    } else {
     float *my = stage + (size_t)wave * U * 64;
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const int64_t c = tile * kThreads + tid;
@@ -317,23 +294,26 @@ __global__ __launch_bounds__(kThreads) void coord_alg1_kernel(
         if (bad) res = __int_as_float(0x7fc00000);
         if (live) out[c] = res;
     }
-    }
 }
 
 template <int THETA>
 hipError_t launch_theta(const CoordAlg1Args &a, hipStream_t s)
 {
+    // which of the two kernels does the work is only known on the device (the plan): both are launched
+    if (a.beta == 1) {
+        const int64_t blocks = (a.d + 2 * kRegThreads - 1) / (2 * kRegThreads);
+        coord_alg1_regular_kernel<THETA, true><<<dim3((unsigned)blocks), dim3(kRegThreads), 0, s>>>(
+            a.G, a.d, a.ld, a.beta, a.plan, a.out);
+    } else {
+        const int64_t blocks = (a.d + kRegThreads - 1) / kRegThreads;
+        coord_alg1_regular_kernel<THETA, false><<<dim3((unsigned)blocks), dim3(kRegThreads), 0, s>>>(
+            a.G, a.d, a.ld, a.beta, a.plan, a.out);
+    }
     const size_t lds = (size_t)kWaves * a.n * 64 * sizeof(float);   // at most n rows are parked
     const int64_t ntiles = (a.d + kThreads - 1) / kThreads;
     const int grid = (int)(ntiles < 2048 ? ntiles : 2048);
-    if (a.beta == 1)
-        coord_alg1_kernel<THETA, 2><<<dim3(grid), dim3(kThreads), 0, s>>>(a.G, a.n, a.d, a.ld, a.sel, a.agr_sets,
-                                                                          a.beta, a.out);
-    else
-        coord_alg1_kernel<THETA, 1><<<dim3(grid), dim3(kThreads), 0, s>>>(a.G, a.n, a.d, a.ld, a.sel, a.agr_sets,
-                                                                          a.beta, a.out);
-    coord_alg1_kernel<THETA, 0><<<dim3(grid), dim3(kThreads), lds, s>>>(a.G, a.n, a.d, a.ld, a.sel, a.agr_sets,
-                                                                        a.beta, a.out);
+    coord_alg1_general_kernel<THETA><<<dim3(grid), dim3(kThreads), lds, s>>>(a.G, a.n, a.d, a.ld, a.sel, a.agr_sets,
+                                                                            a.beta, a.plan, a.out);
     return hipGetLastError();
 }
 

@@ -67,7 +67,19 @@ struct CoordAlg1Args {
     int theta;
     int beta;
     float *out;
+    int32_t *plan;           // kPlanWords words of scratch, written by launch_alg1_plan
 };
+// Plan of the Algorithm-1 coordinate pass (int32 words): is every round's averaged set the previous
+// one minus its winner, and if so the winners' rows, the rows of the last set without its winner,
+// and 1 / |set_t| (float bits).
+constexpr int kPlanRegular = 0;
+constexpr int kPlanNBase = 1;
+constexpr int kPlanWinner = 2;
+constexpr int kPlanBase = kPlanWinner + kMaxN;
+constexpr int kPlanInvM = kPlanBase + kMaxN;
+constexpr int kPlanWords = kPlanInvM + kMaxN;
+hipError_t launch_alg1_plan(int n, int theta, const int32_t *sel, const uint8_t *sets, int32_t *plan,
+                            hipStream_t s);
 hipError_t launch_coord_alg1(const CoordAlg1Args &a, hipStream_t s);
 // one per translation unit, covering theta in [8g+1, 8g+8]
 hipError_t launch_coord_alg1_group0(const CoordAlg1Args &a, hipStream_t s);

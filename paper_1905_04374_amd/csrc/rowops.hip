@@ -3,6 +3,7 @@
 // consecutive coordinates (one when the matrix is not 16-byte aligned) and
 // adds the selected rows in ascending row order; the membership mask is
 // uniform, so rows outside the set are skipped without being read.
+// Also here: the plan of the Algorithm-1 coordinate pass (one small kernel).
 #include <hip/hip_runtime.h>
 
 #include "mb_internal.hpp"
@@ -40,7 +41,49 @@ __global__ __launch_bounds__(256) void masked_mean_kernel(const float *__restric
         if (c0 + e < d) out[c0 + e] = acc[e] * inv;
 }
 
+// One wave, lane t = round t of multi-Krum (Algorithm 1): checks that set_{t+1} = set_t minus the
+// winner of round t for every t, and writes what the regular coordinate kernel needs.
+__global__ __launch_bounds__(64) void alg1_plan_kernel(int n, int theta, const int32_t *__restrict__ sel,
+                                                       const uint8_t *__restrict__ sets,
+                                                       int32_t *__restrict__ plan)
+{
+    const int t = threadIdx.x;
+    bool ok = true;
+    if (t < theta) {
+        const int w = sel[t];
+        const bool valid = (unsigned)w < (unsigned)n;
+        ok = valid && sets[t * n + (valid ? w : 0)] != 0;
+        int m = 0;
+        for (int r = 0; r < n; ++r) {
+            const int cur = sets[t * n + r] ? 1 : 0;
+            m += cur;
+            if (t + 1 < theta) {
+                const int nxt = sets[(t + 1) * n + r] ? 1 : 0;
+                ok = ok && (nxt == ((r == w) ? 0 : cur));
+            }
+        }
+        plan[kPlanWinner + t] = valid ? w : 0;
+        plan[kPlanInvM + t] = __float_as_int(m > 0 ? 1.0f / (float)m : 0.0f);
+    }
+    const bool regular = __ballot(!ok) == 0ull;
+    if (t == 0) {
+        int nb = 0;
+        const int last = sel[theta - 1];
+        for (int r = 0; r < n; ++r)
+            if (sets[(theta - 1) * n + r] && r != last) plan[kPlanBase + nb++] = r;
+        plan[kPlanNBase] = nb;
+        plan[kPlanRegular] = regular ? 1 : 0;
+    }
+}
+
 }  // namespace
+
+hipError_t launch_alg1_plan(int n, int theta, const int32_t *sel, const uint8_t *sets, int32_t *plan,
+                            hipStream_t s)
+{
+    alg1_plan_kernel<<<dim3(1), dim3(64), 0, s>>>(n, theta, sel, sets, plan);
+    return hipGetLastError();
+}
 
 hipError_t launch_masked_mean(const float *G, int n, int64_t d, int64_t ld, const uint8_t *mask,
                               float *out, hipStream_t s)
