@@ -6,8 +6,8 @@
 // counting, keys (distance, index)); then a single wave, lane i = gradient i,
 // plays the rounds with its ordered row held in registers and a bit mask of the
 // ranks still active: add the q nearest distances in ascending order in fp64,
-// find the smallest (score, index) by a wave reduction (or rank all scores through
-// LDS broadcasts when the averaged sets are wanted), extract it.
+// find the smallest (score, index) by a wave reduction (or rank all scores by
+// lane broadcasts when the averaged sets are wanted), extract it.
 #include <hip/hip_runtime.h>
 
 #include "mb_internal.hpp"
@@ -18,6 +18,119 @@ namespace {
 constexpr int kSelThreads = 256;   // 4 waves: one per SIMD, so the round-playing wave may use the whole register file
 constexpr int kPerThread = kMaxN * kMaxN / kSelThreads;
 
+struct Rounds {
+    const double *sD;            // LDS: row i in ascending order
+    const unsigned char *sJ;     // LDS: neighbour index by rank within row i
+    const unsigned char *sR;     // LDS: rank of neighbour j within row i
+    int n, f, rounds;
+    const uint8_t *active_in;
+    int32_t *sel;
+    uint8_t *agr_sets;
+    int32_t *m_out;
+    double *scores_out;
+};
+
+__device__ __forceinline__ double read_lane(double x, int lane)   // lane: the same for the whole wave
+{
+    const unsigned long long u = (unsigned long long)__double_as_longlong(x);
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)u, lane);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(u >> 32), lane);
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+
+// One wave, lane i = gradient i, ordered row in NV >= n - 1 registers.
+// `near`: bit r set while the r-th nearest neighbour of i is still active.
+// `take`: the q lowest set bits of `near`, the neighbours whose distances make up the score.
+// From one round to the next q drops by one and at most one neighbour leaves, so `take` loses
+// either the bit of the extracted gradient or its own top bit: no search after the first round.
+template <int NV>
+__device__ __forceinline__ void play_rounds(const Rounds &a, int i)
+{
+    const int n = a.n, f = a.f;
+    const double inf = __builtin_huge_val();
+    const int row = i < n ? i : 0;
+    double v[NV];
+#pragma unroll
+    for (int r = 0; r < NV; ++r) v[r] = (r < n - 1) ? a.sD[row * kMaxN + r] : 0.0;
+
+    unsigned long long act = 0;   // active gradients, same value in every lane
+    for (int j = 0; j < n; ++j)
+        if (!a.active_in || a.active_in[j]) act |= 1ull << j;
+    unsigned long long near = 0;
+    for (int r = 0; r < n - 1; ++r)
+        if ((act >> a.sJ[row * kMaxN + r]) & 1ull) near |= 1ull << r;
+    unsigned long long take = 0;
+    {
+        int q = __popcll(act) - f - 2;
+        q = q < 0 ? 0 : q;
+        int lo = 0, hi = 64;                       // smallest cut with popc(near & below(cut)) >= q
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            const unsigned long long below = mid >= 64 ? ~0ull : ((1ull << mid) - 1ull);
+            if (__popcll(near & below) >= q) hi = mid; else lo = mid + 1;
+        }
+        take = near & (lo >= 64 ? ~0ull : ((1ull << lo) - 1ull));
+    }
+
+    for (int t = 0; t < a.rounds; ++t) {
+        const int k = __popcll(act);
+        int q = k - f - 2;
+        q = q < 0 ? 0 : q;
+        const bool mine = i < n && ((act >> i) & 1ull);
+        const unsigned tlo = (unsigned)take, thi = (unsigned)(take >> 32);
+        double S = 0.0;   // added in ascending order of distance
+#pragma unroll
+        for (int r = 0; r < NV; ++r) {
+            const bool in = r < 32 ? (tlo & (1u << (r & 31))) != 0 : (thi & (1u << (r & 31))) != 0;
+            S += in ? v[r] : 0.0;
+        }
+        if (!mine) S = inf;
+        if (t == 0 && a.scores_out && i < n) a.scores_out[i] = S;
+
+        int w;            // the first of the active gradients in the order (score, index)
+        if (a.agr_sets) {
+            int pos = 0;  // position of i in that order
+#pragma unroll
+            for (int j = 0; j <= NV; ++j) {
+                if (j < n) {
+                    const double Sj = read_lane(S, j);
+                    const bool aj = (act >> j) & 1ull;
+                    pos += (aj && (Sj < S || (Sj == S && j < i))) ? 1 : 0;
+                }
+            }
+            const unsigned long long first = __ballot(mine && pos == 0);
+            w = first ? (int)__builtin_ctzll(first) : 0;
+            if (i < n) a.agr_sets[t * n + i] = (mine && pos < q) ? 1 : 0;
+        } else {
+            double bs = S;
+            int bi = mine ? i : kMaxN;
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                const double os = __shfl_xor(bs, off, 64);
+                const int oi = __shfl_xor(bi, off, 64);
+                const bool better = os < bs || (os == bs && oi < bi);
+                bs = better ? os : bs;
+                bi = better ? oi : bi;
+            }
+            w = bi < kMaxN ? bi : 0;
+        }
+        if (a.sel && i == 0) a.sel[t] = w;
+        if (a.m_out && i == 0) a.m_out[t] = q < k ? q : k;
+        if (k > 0) {
+            act &= ~(1ull << w);
+            const int rw = a.sR[row * kMaxN + w];        // rank of the extracted gradient in row i
+            const unsigned long long wbit = (w != row) ? (1ull << rw) : 0ull;
+            near &= ~wbit;
+            int qn = k - 1 - f - 2;
+            qn = qn < 0 ? 0 : qn;
+            if (qn < q && take) {
+                if (take & wbit) take &= ~wbit;
+                else take &= ~(1ull << (63 - __builtin_clzll(take)));
+            }
+        }
+    }
+}
+
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const double *__restrict__ dist, int n, int f, int rounds, const uint8_t *__restrict__ active_in,
     int32_t *__restrict__ sel, uint8_t *__restrict__ agr_sets, int32_t *__restrict__ m_out,
@@ -26,7 +139,6 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     __shared__ double sD[kMaxN * kMaxN];        // first dist[i][j], then row i in ascending order
     __shared__ unsigned char sJ[kMaxN * kMaxN]; // neighbour index by rank within row i
     __shared__ unsigned char sR[kMaxN * kMaxN]; // rank of neighbour j within row i
-    __shared__ double sS[kMaxN];
     const int tid = threadIdx.x;
     const double inf = __builtin_huge_val();
 
@@ -50,9 +162,17 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
             if (i != j) {
                 const double v = sD[i * kMaxN + j];
                 int rank = 0;
-                for (int jj = 0; jj < n; ++jj) {
-                    const double u = sD[i * kMaxN + jj];
-                    rank += (jj != i && (u < v || (u == v && jj < j))) ? 1 : 0;
+                // one wave per SIMD, nothing else hides the LDS latency: eight reads in flight
+                // (entries past n in the padded row are never counted)
+                for (int j0 = 0; j0 < n; j0 += 8) {
+                    double u[8];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) u[q] = sD[i * kMaxN + ((j0 + q) & (kMaxN - 1))];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) {
+                        const int jj = j0 + q;
+                        rank += (jj < n && jj != i && (u[q] < v || (u[q] == v && jj < j))) ? 1 : 0;
+                    }
                 }
                 myrank[k] = rank;
                 myv[k] = v;
@@ -72,87 +192,11 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     }
     __syncthreads();
     if (tid >= 64) return;   // one wave plays the rounds; no workgroup barrier below this line
-
-    // Lane i keeps its ordered row in registers and a bit mask over ranks: bit r is set while the
-    // r-th nearest neighbour of i is still active.  A round then needs no dependent LDS reads.
-    const int i = tid;
-    const int row = i < n ? i : 0;
-    double v[kMaxN - 1];
-#pragma unroll
-    for (int r = 0; r < kMaxN - 1; ++r) v[r] = (r < n - 1) ? sD[row * kMaxN + r] : 0.0;
-
-    unsigned long long act = 0;   // active gradients, same value in every lane
-    for (int j = 0; j < n; ++j)
-        if (!active_in || active_in[j]) act |= 1ull << j;
-    unsigned long long near = 0;  // active neighbours of i, by rank
-    for (int r = 0; r < n - 1; ++r)
-        if ((act >> sJ[row * kMaxN + r]) & 1ull) near |= 1ull << r;
-
-    for (int t = 0; t < rounds; ++t) {
-        const int k = __popcll(act);
-        int q = k - f - 2;
-        q = q < 0 ? 0 : q;
-        const bool mine = i < n && ((act >> i) & 1ull);
-        // ranks of the q nearest active neighbours: the q lowest set bits of `near`
-        unsigned long long take = near;
-        {
-            // drop set bits from the top until q are left (binary search on the cut position)
-            int lo = 0, hi = 64;                       // smallest cut with popc(near & below(cut)) >= q
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                const unsigned long long below = mid >= 64 ? ~0ull : ((1ull << mid) - 1ull);
-                if (__popcll(near & below) >= q) hi = mid; else lo = mid + 1;
-            }
-            take = near & (lo >= 64 ? ~0ull : ((1ull << lo) - 1ull));
-        }
-        const unsigned tlo = (unsigned)take, thi = (unsigned)(take >> 32);
-        double S = 0.0;   // added in ascending order of distance
-#pragma unroll
-        for (int r = 0; r < kMaxN - 1; ++r) {
-            if (r < n - 1) {
-                const bool in = r < 32 ? (tlo & (1u << (r & 31))) != 0 : (thi & (1u << (r & 31))) != 0;
-                S += in ? v[r] : 0.0;
-            }
-        }
-        if (!mine) S = inf;
-        if (t == 0 && scores_out && i < n) scores_out[i] = S;
-
-        int w;            // the first of the active gradients in the order (score, index)
-        int pos = 0;      // position of i in that order (only needed for the averaged sets)
-        if (agr_sets) {
-            sS[i] = S;
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-            __builtin_amdgcn_wave_barrier();
-            for (int j = 0; j < n; ++j) {
-                const double Sj = sS[j];
-                const bool aj = (act >> j) & 1ull;
-                pos += (aj && (Sj < S || (Sj == S && j < i))) ? 1 : 0;
-            }
-            __builtin_amdgcn_wave_barrier();
-            const unsigned long long first = __ballot(mine && pos == 0);
-            w = first ? (int)__builtin_ctzll(first) : 0;
-            if (i < n) agr_sets[t * n + i] = (mine && pos < q) ? 1 : 0;
-        } else {
-            double bs = S;
-            int bi = mine ? i : kMaxN;
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) {
-                const double os = __shfl_xor(bs, off, 64);
-                const int oi = __shfl_xor(bi, off, 64);
-                const bool better = os < bs || (os == bs && oi < bi);
-                bs = better ? os : bs;
-                bi = better ? oi : bi;
-            }
-            w = bi < kMaxN ? bi : 0;
-        }
-        if (sel && i == 0) sel[t] = w;
-        if (m_out && i == 0) m_out[t] = q < k ? q : k;
-        if (k > 0) {
-            act &= ~(1ull << w);
-            const int rw = sR[row * kMaxN + w];          // rank of the extracted gradient in row i
-            if (w != row) near &= ~(1ull << rw);
-        }
-    }
+    const Rounds rd{sD, sJ, sR, n, f, rounds, active_in, sel, agr_sets, m_out, scores_out};
+    if (n <= 16) play_rounds<15>(rd, tid);
+    else if (n <= 32) play_rounds<31>(rd, tid);
+    else if (n <= 48) play_rounds<47>(rd, tid);
+    else play_rounds<63>(rd, tid);
 }
 
 }  // namespace
