@@ -11,11 +11,16 @@
 namespace mb {
 namespace {
 
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
 template <int VEC>
 __global__ __launch_bounds__(256) void masked_mean_kernel(const float *__restrict__ G, int n, int64_t d,
                                                           int64_t ld, const uint8_t *__restrict__ mask,
                                                           float *__restrict__ out)
 {
+    // the membership mask as 64 bits in scalar registers (n <= 64): lane r looks at row r
+    const int lane = threadIdx.x & 63;
+    const unsigned long long members = __ballot(lane < n && mask[lane < n ? lane : 0] != 0);
     const int64_t c0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * VEC;
     if (c0 >= d) return;
     float acc[VEC];
@@ -23,17 +28,31 @@ __global__ __launch_bounds__(256) void masked_mean_kernel(const float *__restric
     for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
     int m = 0;
     const bool full = c0 + VEC <= d;
-    for (int r = 0; r < n; ++r) {
-        if (!mask[r]) continue;
-        ++m;
-        const float *p = G + (int64_t)r * ld + c0;
-        if (VEC == 4 && full) {
-            const float4 x = *reinterpret_cast<const float4 *>(p);
-            acc[0] += x.x; acc[1] += x.y; acc[2] += x.z; acc[3] += x.w;
-        } else {
+    // eight rows in flight at a time; the mask is the same for every lane, rows outside the set are
+    // not read; members are added in ascending row order
+    for (int r0 = 0; r0 < n; r0 += 8) {
+        float x[8][VEC];
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[e] += (c0 + e < d) ? p[e] : 0.0f;
+        for (int j = 0; j < 8; ++j) {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) x[j][e] = 0.0f;
+            const int r = r0 + j;
+            if (r < n && ((members >> r) & 1ull)) {
+                ++m;
+                const float *p = G + (int64_t)r * ld + c0;
+                if (VEC == 4 && full) {
+                    const floatx4 v = __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(p));
+                    x[j][0] = v[0]; x[j][1 % VEC] = v[1]; x[j][2 % VEC] = v[2]; x[j][3 % VEC] = v[3];
+                } else {
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) x[j][e] = (c0 + e < d) ? p[e] : 0.0f;
+                }
+            }
         }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] += x[j][e];
     }
     const float inv = m > 0 ? 1.0f / (float)m : 0.0f;
 #pragma unroll
