@@ -184,9 +184,10 @@ int multikrum_select(const double *dist, int n, int f, int theta,
  * Median of an even count: 0.5*(lo+hi) in fp32.  Closeness: |v-med| as one
  * fp32 subtraction; on equal closeness the smaller value is preferred.
  *   selected_idx device, theta int32 in [0, n), validated on the device: an
- *                out-of-range index makes the kernel write NaN to out
+ *                out-of-range index makes the kernel write NaN to out, and so
+ *                does, with agr_sets != NULL, an index that occurs twice
  *   out          device, d floats
- * With agr_sets != NULL a 1 KB plan is kept in the library's own workspace
+ * With agr_sets != NULL an 18 KB plan is kept in the library's own workspace
  * (allocated on the first such call on a device; calls that use it must not
  * overlap on one device).
  */

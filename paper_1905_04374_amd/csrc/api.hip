@@ -35,8 +35,9 @@ constexpr size_t kOffSel = kOffReduced + 2560 * 8;               // 64 int32
 constexpr size_t kOffM = kOffSel + 256;                          // 64 int32
 constexpr size_t kOffSets = kOffM + 256;                         // 64*64 bytes
 constexpr size_t kOffPlan = kOffSets + 4096;                     // plan of the Algorithm-1 coordinate pass
-constexpr size_t kOffPartials = kOffPlan + 1024;
-static_assert(mb::kPlanWords * sizeof(int32_t) <= 1024, "plan segment");
+constexpr size_t kPlanBytes = 18 * 1024;
+constexpr size_t kOffPartials = kOffPlan + kPlanBytes;
+static_assert(mb::kPlanWords * sizeof(int32_t) <= kPlanBytes, "plan segment");
 
 struct Workspace {
     char *base;

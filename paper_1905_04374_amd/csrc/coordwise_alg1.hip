@@ -7,13 +7,11 @@
 // previous one minus its winner; the averages are then running sums over the
 // winners' values (needed for the median anyway) on top of the last round's
 // set: theta + f row streams, all in registers.  Otherwise (the order of the
-// scores changed between rounds) each workgroup turns the theta x n membership
-// matrix into a list of signed row updates (rows entering or leaving the set
-// from one round to the next); the running sum S_t = S_{t-1} +- few rows then
-// costs a handful of adds per round.  A wave stages the values of the rows it
-// needs for its 64 coordinates in LDS (row-major, lane = coordinate), because
-// the update lists index rows at run time.  Rows that no round uses are not
-// read at all.
+// scores changed between rounds) the theta x n membership matrix becomes signed
+// row updates (rows entering or leaving the set from one round to the next) and
+// the running sum S_t = S_{t-1} +- few rows follows them; rows that no round
+// uses are not read at all.  A small plan kernel (rowops.hip) decides which case
+// holds and prepares both; the two kernels here read its plan with scalar loads.
 //
 // Compiled once per group of 8 values of theta (-DMB_GROUP=0..7).
 #include <hip/hip_runtime.h>
@@ -28,8 +26,6 @@
 namespace mb {
 namespace {
 
-constexpr int kThreads = 128;   // 2 waves: the staging area is n x 256 bytes per wave
-constexpr int kWaves = kThreads / 64;
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 
 // average of the beta values a[.] closest to med (closeness |a - med| in fp32, ties to the smaller value)
@@ -191,109 +187,53 @@ __global__ __launch_bounds__(kRegThreads) void coord_alg1_regular_kernel(
 }
 
 // The general case (some round's set is not "the previous set minus its winner"); returns at once
-// when the plan says the regular kernel handles the call.
+// when the plan says the regular kernel handles the call.  Every row that some round needs has a
+// slot (the winner of round t in slot t), a lane holds its coordinate of all of them in registers,
+// and the running sum over the current set follows the plan's signed membership changes:
+// S_t = S_{t-1} + sum_s delta[t][s] x[s].  Register arrays cannot be indexed at run time, so the
+// changes are applied as multiply-adds by -1, 0 or +1 from scalar registers, in groups of eight
+// slots that are skipped when nothing in them changes (after round 0 only a few rows move).
 template <int THETA>
-__global__ __launch_bounds__(kThreads) void coord_alg1_general_kernel(
-    const float *__restrict__ G, int n, int64_t d, int64_t ld, const int32_t *__restrict__ sel,
-    const uint8_t *__restrict__ sets, int beta, const int32_t *__restrict__ plan, float *__restrict__ out)
+__global__ __launch_bounds__(kRegThreads) void coord_alg1_general_kernel(
+    const float *__restrict__ G, int64_t d, int64_t ld, int beta, const int32_t *__restrict__ plan,
+    float *__restrict__ out)
 {
     if (plan[kPlanRegular]) return;
-    extern __shared__ float stage[];                 // [kWaves][slots][64]
-    __shared__ unsigned char ops[kMaxN * kMaxN];     // slot | 0x80 if the row leaves the set
-    __shared__ int off[kMaxN + 1];                   // ops of round t: [off[t], off[t+1])
-    __shared__ float inv_m[kMaxN];
-    __shared__ unsigned char need[kMaxN];            // row is read at all
-    __shared__ unsigned char slot_of[kMaxN];         // row -> slot among the rows that are read
-    __shared__ int rows[kMaxN];                      // slot -> row
-    __shared__ int wslot[kMaxN];                     // slot of the winner of round t
-    __shared__ int nslots;
-    __shared__ int bad_flag;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-
-    // ---- plan: which rows are read, and the signed row updates of every round -------------
-    if (tid == 0) bad_flag = 0;
-    if (tid < kMaxN) need[tid] = 0;
-    __syncthreads();
-    int my_count = 0, my_m = 0;
-    if (tid < THETA) {
-        for (int r = 0; r < n; ++r) {
-            const int cur = sets[tid * n + r] ? 1 : 0;
-            const int prev = (tid > 0 && sets[(tid - 1) * n + r]) ? 1 : 0;
-            my_count += (cur != prev);
-            my_m += cur;
-            if (cur) need[r] = 1;
-        }
-        const int w = sel[tid];
-        if ((unsigned)w >= (unsigned)n) bad_flag = 1;
-        else need[w] = 1;
-        inv_m[tid] = my_m > 0 ? 1.0f / (float)my_m : 0.0f;
-        off[tid + 1] = my_count;
+    const int64_t c = (int64_t)blockIdx.x * kRegThreads + threadIdx.x;
+    if (c >= d) return;
+    if (plan[kPlanBad]) {
+        out[c] = __int_as_float(0x7fc00000);
+        return;
     }
-    __syncthreads();
-    if (tid == 0) {
-        off[0] = 0;
-        for (int t = 0; t < THETA; ++t) off[t + 1] += off[t];
-        int ns = 0;
-        for (int r = 0; r < n; ++r)
-            if (need[r]) { slot_of[r] = (unsigned char)ns; rows[ns] = r; ++ns; }
-        nslots = ns;
+    const int U = plan[kPlanNSlots];
+    const float *inv_m = reinterpret_cast<const float *>(plan + kPlanInvM);
+    const float *delta = reinterpret_cast<const float *>(plan + kPlanDelta);
+    float x[kMaxN];
+#pragma unroll
+    for (int s = 0; s < kMaxN; ++s) {
+        x[s] = 0.0f;
+        if (s < U) x[s] = __builtin_nontemporal_load(G + (int64_t)plan[kPlanRows + s] * ld + c);
     }
-    __syncthreads();
-    if (tid < THETA) {
-        int k = off[tid];
-        for (int r = 0; r < n; ++r) {
-            const int cur = sets[tid * n + r] ? 1 : 0;
-            const int prev = (tid > 0 && sets[(tid - 1) * n + r]) ? 1 : 0;
-            if (cur != prev) ops[k++] = (unsigned char)(slot_of[r] | (cur ? 0 : 0x80));
-        }
-        const int w = sel[tid];
-        wslot[tid] = ((unsigned)w < (unsigned)n) ? slot_of[w] : 0;
-    }
-    __syncthreads();
-    const bool bad = bad_flag != 0;
-    const int U = nslots;
-
-    const int64_t ntiles = (d + kThreads - 1) / kThreads;
-    float *my = stage + (size_t)wave * U * 64;
-    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int64_t c = tile * kThreads + tid;
-        const bool live = c < d;
-        const int64_t cc = live ? c : d - 1;
-        // every needed row once, all loads in flight together, then parked in LDS where the
-        // update lists can index them (a lane only ever reads back what it wrote itself)
-        float x[kMaxN];
+    float e[THETA], a[THETA];
+    float S = 0.0f;
 #pragma unroll
-        for (int s = 0; s < kMaxN; ++s)
-            if (s < U) x[s] = __builtin_nontemporal_load(G + (int64_t)rows[s] * ld + cc);
+    for (int t = 0; t < THETA; ++t) {
+        e[t] = x[t];
+        const int groups = plan[kPlanGroups + t];
 #pragma unroll
-        for (int s = 0; s < kMaxN; ++s)
-            if (s < U) my[s * 64 + lane] = x[s];
-
-        float e[THETA], a[THETA];
-        float S = 0.0f;
+        for (int g = 0; g < kMaxN / 8; ++g) {
+            if (groups & (1 << g)) {           // same for every lane
 #pragma unroll
-        for (int t = 0; t < THETA; ++t) {
-            e[t] = my[wslot[t] * 64 + lane];
-            const int k1 = off[t + 1];
-            for (int k = off[t]; k < k1; ++k) {
-                const int op = ops[k];
-                const float xv = my[(op & 63) * 64 + lane];
-                S += (op & 0x80) ? -xv : xv;
+                for (int j = 0; j < 8; ++j) S = fmaf(delta[t * kMaxN + 8 * g + j], x[8 * g + j], S);
             }
-            a[t] = S * inv_m[t];
         }
-        sort_registers<THETA>(e);
-        float med;
-        if constexpr (THETA & 1) med = e[THETA / 2];
-        else med = 0.5f * (e[THETA / 2 - 1] + e[THETA / 2]);
-
-        float res = pick_closest<THETA>(a, med, beta);
-        if (bad) res = __int_as_float(0x7fc00000);
-        if (live) out[c] = res;
+        a[t] = S * inv_m[t];
     }
+    sort_registers<THETA>(e);
+    float med;
+    if constexpr (THETA & 1) med = e[THETA / 2];
+    else med = 0.5f * (e[THETA / 2 - 1] + e[THETA / 2]);
+    out[c] = pick_closest<THETA>(a, med, beta);
 }
 
 template <int THETA>
@@ -309,11 +249,9 @@ hipError_t launch_theta(const CoordAlg1Args &a, hipStream_t s)
         coord_alg1_regular_kernel<THETA, false><<<dim3((unsigned)blocks), dim3(kRegThreads), 0, s>>>(
             a.G, a.d, a.ld, a.beta, a.plan, a.out);
     }
-    const size_t lds = (size_t)kWaves * a.n * 64 * sizeof(float);   // at most n rows are parked
-    const int64_t ntiles = (a.d + kThreads - 1) / kThreads;
-    const int grid = (int)(ntiles < 2048 ? ntiles : 2048);
-    coord_alg1_general_kernel<THETA><<<dim3(grid), dim3(kThreads), lds, s>>>(a.G, a.n, a.d, a.ld, a.sel, a.agr_sets,
-                                                                            a.beta, a.plan, a.out);
+    const int64_t gblocks = (a.d + kRegThreads - 1) / kRegThreads;
+    coord_alg1_general_kernel<THETA><<<dim3((unsigned)gblocks), dim3(kRegThreads), 0, s>>>(a.G, a.d, a.ld, a.beta,
+                                                                                          a.plan, a.out);
     return hipGetLastError();
 }
 

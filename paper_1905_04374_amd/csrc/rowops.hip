@@ -60,17 +60,24 @@ __global__ __launch_bounds__(256) void masked_mean_kernel(const float *__restric
         if (c0 + e < d) out[c0 + e] = acc[e] * inv;
 }
 
-// One wave, lane t = round t of multi-Krum (Algorithm 1): checks that set_{t+1} = set_t minus the
-// winner of round t for every t, and writes what the regular coordinate kernel needs.
+// One wave, lane t = round t of multi-Krum (Algorithm 1).  Checks whether set_{t+1} = set_t minus
+// the winner of round t for every t and writes what the two coordinate kernels need.
 __global__ __launch_bounds__(64) void alg1_plan_kernel(int n, int theta, const int32_t *__restrict__ sel,
                                                        const uint8_t *__restrict__ sets,
                                                        int32_t *__restrict__ plan)
 {
+    __shared__ int slot_of[kMaxN];     // row -> slot, -1: no round needs the row
+    __shared__ int winner[kMaxN];
+    __shared__ int nslots_s;
     const int t = threadIdx.x;
-    bool ok = true;
+    bool ok = true, bad = false;
+    if (t < kMaxN) slot_of[t] = -1;
+    __syncthreads();
     if (t < theta) {
         const int w = sel[t];
         const bool valid = (unsigned)w < (unsigned)n;
+        bad = !valid;
+        winner[t] = valid ? w : 0;
         ok = valid && sets[t * n + (valid ? w : 0)] != 0;
         int m = 0;
         for (int r = 0; r < n; ++r) {
@@ -84,14 +91,60 @@ __global__ __launch_bounds__(64) void alg1_plan_kernel(int n, int theta, const i
         plan[kPlanWinner + t] = valid ? w : 0;
         plan[kPlanInvM + t] = __float_as_int(m > 0 ? 1.0f / (float)m : 0.0f);
     }
-    const bool regular = __ballot(!ok) == 0ull;
+    __syncthreads();
+    if (t < theta) {                   // a winner that an earlier round already extracted
+        for (int u = 0; u < t; ++u) bad = bad || (winner[u] == winner[t]);
+    }
+    const bool any_bad = __ballot(bad) != 0ull;
+    const bool regular = __ballot(!ok) == 0ull && !any_bad;
     if (t == 0) {
         int nb = 0;
-        const int last = sel[theta - 1];
+        const int last = winner[theta - 1];
         for (int r = 0; r < n; ++r)
             if (sets[(theta - 1) * n + r] && r != last) plan[kPlanBase + nb++] = r;
         plan[kPlanNBase] = nb;
         plan[kPlanRegular] = regular ? 1 : 0;
+        plan[kPlanBad] = any_bad ? 1 : 0;
+        // slots: winners first (slot t = round t), then the other rows some set contains
+        int ns = 0;
+        for (int u = 0; u < theta; ++u) {
+            if (slot_of[winner[u]] < 0) slot_of[winner[u]] = ns;
+            plan[kPlanRows + ns] = winner[u];
+            ++ns;
+        }
+        if (!any_bad) {                // (with repeated winners the slots could run past kMaxN)
+            for (int r = 0; r < n; ++r) {
+                if (slot_of[r] >= 0) continue;
+                bool used = false;
+                for (int u = 0; u < theta; ++u) used = used || sets[u * n + r] != 0;
+                if (used) {
+                    slot_of[r] = ns;
+                    plan[kPlanRows + ns] = r;
+                    ++ns;
+                }
+            }
+        }
+        nslots_s = ns;
+        plan[kPlanNSlots] = ns;
+    }
+    __syncthreads();
+    if (t < theta) {
+        const int ns = nslots_s;
+        unsigned groups = 0;
+        for (int s = 0; s < kMaxN; ++s) plan[kPlanDelta + t * kMaxN + s] = 0;   // 0.0f
+        if (!any_bad) {
+            for (int r = 0; r < n; ++r) {
+                const int s = slot_of[r];
+                if (s < 0 || s >= ns) continue;
+                const int cur = sets[t * n + r] ? 1 : 0;
+                const int prev = (t > 0 && sets[(t - 1) * n + r]) ? 1 : 0;
+                if (cur != prev) {
+                    plan[kPlanDelta + t * kMaxN + s] = __float_as_int(cur ? 1.0f : -1.0f);
+                    groups |= 1u << (s >> 3);
+                }
+            }
+        }
+        plan[kPlanGroups + t] = (int)groups;
     }
 }
 

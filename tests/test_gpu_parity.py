@@ -215,6 +215,13 @@ def test_coordwise_rejects_bad_indices_with_nan():
     G = gpu(np.ones((7, 100), np.float32))
     out = mb.coordwise_trimmed_avg(G, gpu(np.array([0, 1, 9], np.int32)), 1)
     assert torch.isnan(out).all()
+    # Algorithm-1 form: an index out of range, and an index extracted twice
+    sets = gpu(np.ones((3, 7), np.uint8))
+    for idx in ([0, 1, 9], [0, 1, -1], [2, 5, 2]):
+        out = mb.coordwise_trimmed_avg(G, gpu(np.array(idx, np.int32)), 1, agr_sets=sets)
+        assert torch.isnan(out).all(), idx
+    out = mb.coordwise_trimmed_avg(G, gpu(np.array([2, 5, 3], np.int32)), 1, agr_sets=sets)
+    assert torch.equal(out, torch.ones_like(out))
 
 
 def test_coordwise_median():
