@@ -183,8 +183,16 @@ __global__ __launch_bounds__(1024) void reduce_partials_kernel(const double *__r
     const int b0 = seg * per;
     const int b1 = (b0 + per < nblocks) ? b0 + per : nblocks;
     double s = 0.0;
-    if (e < slots)
-        for (int b = b0; b < b1; ++b) s += partials[(int64_t)b * stride + e];
+    if (e < slots) {
+        // eight loads in flight, added in workgroup order all the same
+        for (int b = b0; b < b1; b += 8) {
+            double x[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) x[k] = (b + k < b1) ? partials[(int64_t)(b + k) * stride + e] : 0.0;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) s += x[k];
+        }
+    }
     seg_sum[seg][el] = s;
     __syncthreads();
     if (seg == 0 && e < slots) {

@@ -521,9 +521,11 @@ hipError_t launch_dma_l(const float *G, int n, int64_t d, int64_t ld, double *pa
             return e;
         resident[n] = cus * (per_cu < 1 ? 1 : per_cu);
     }
+    // at least four tiles per workgroup: with fewer, writing and adding up the partial tiles costs
+    // more than the distance pass itself
     const int64_t ntiles = d / kTile;
     int64_t g = resident[n] < kGramMaxBlocks ? resident[n] : kGramMaxBlocks;
-    if (ntiles < g) g = ntiles < 1 ? 1 : ntiles;
+    if (ntiles < 4 * g) g = ntiles < 4 ? 1 : ntiles / 4;
     *nblocks = (int)g;
     gram_dma_kernel<NB, BF16, L><<<dim3((unsigned)g), dim3(kThreads), bytes, s>>>(G, n, d, ld, partials);
     return hipGetLastError();

@@ -15,7 +15,7 @@
 namespace mb {
 namespace {
 
-constexpr int kSelThreads = 256;   // 4 waves: one per SIMD, so the round-playing wave may use the whole register file
+constexpr int kSelThreads = 512;   // 8 waves rank the rows, two per SIMD: each may still use 256 registers
 constexpr int kPerThread = kMaxN * kMaxN / kSelThreads;
 
 struct Rounds {
@@ -56,9 +56,18 @@ __device__ __forceinline__ void play_rounds(const Rounds &a, int i)
     unsigned long long act = 0;   // active gradients, same value in every lane
     for (int j = 0; j < n; ++j)
         if (!a.active_in || a.active_in[j]) act |= 1ull << j;
-    unsigned long long near = 0;
-    for (int r = 0; r < n - 1; ++r)
-        if ((act >> a.sJ[row * kMaxN + r]) & 1ull) near |= 1ull << r;
+    unsigned long long near = n >= 2 ? (~0ull >> (65 - n)) : 0ull;   // all n - 1 neighbours
+    if (a.active_in) {
+        near = 0;
+        for (int r0 = 0; r0 < n - 1; r0 += 8) {
+            int jn[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) jn[q] = a.sJ[row * kMaxN + ((r0 + q) & (kMaxN - 1))];
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+                if (r0 + q < n - 1 && ((act >> jn[q]) & 1ull)) near |= 1ull << (r0 + q);
+        }
+    }
     unsigned long long take = 0;
     {
         int q = __popcll(act) - f - 2;
