@@ -79,6 +79,9 @@ def main():
     ap.add_argument("--d", type=int, default=None, help="override the number of coordinates")
     ap.add_argument("--mode", choices=["selected", "alg1"], default="selected")
     ap.add_argument("--dist-algo", choices=["auto", "direct", "gram", "gram_bf16"], default="auto")
+    ap.add_argument("--input-dtype", choices=["f32", "bf16"], default="f32",
+                    help="bf16: the workload rounded to bf16 once, aggregated by the bf16 entry point "
+                         "(half the bytes; a second workload, not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run one plain device copy of this many MiB before the timed region "
@@ -108,6 +111,11 @@ def main():
     nchunks = spec["chunks"] if a.d is None else 1
     mode = mb.MODE_SELECTED if a.mode == "selected" else mb.MODE_ALG1
     theta, beta = mb.mbulyan_params(n, f, mode)
+    in16 = a.input_dtype == "bf16"
+    if in16 and (nchunks != 1 or mode != mb.MODE_SELECTED):
+        print("bench.py: --input-dtype bf16 runs single-buffer workloads in the selected mode", file=sys.stderr)
+        sys.exit(2)
+    eb = 2.0 if in16 else 4.0
 
     # ---- inputs resident in HBM before the timed region ----------------------
     bounds = [d * k // nchunks for k in range(nchunks + 1)]
@@ -115,6 +123,11 @@ def main():
     for k in range(nchunks):
         g = torch.empty(n, bounds[k + 1] - bounds[k], device=dev, dtype=torch.float32)
         W.fill(a.config, g, bounds[k])
+        if in16:
+            g16 = torch.empty(g.shape, device=dev, dtype=torch.bfloat16)
+            for r in range(n):                     # row by row: no second fp32-sized temporary
+                g16[r].copy_(g[r])
+            g = g16
         chunks.append(g)
     outs = [torch.empty(c.shape[1], device=dev, dtype=torch.float32) for c in chunks]
     sel = torch.empty(theta, device=dev, dtype=torch.int32)
@@ -150,7 +163,7 @@ def main():
     mean5, std5 = paper_protocol(step, torch.cuda.synchronize)
 
     sec = (t1 - t0) / a.steps
-    in_bytes = 4.0 * n * d
+    in_bytes = eb * n * d
     rows2 = theta if mode == mb.MODE_SELECTED else None
     value = in_bytes / sec / 1e9
 
@@ -165,34 +178,39 @@ def main():
     gram = "gram_dma_kernel" if (d // nchunks) % 4 == 0 and d // nchunks >= 128 else "gram_kernel"
     kname = {"direct": "dist_direct_kernel", "gram": f"{gram}<{nb}, fp32>"}.get(
         a.dist_algo, f"{gram}<{nb}, bf16>")
+    if in16:
+        kname = f"gram_dma_kernel<{nb}, bf16 input>"
     roofline = {"kernel": kname, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get((a.config, "gram_bf16")) if (bf16 and a.d is None) else None,
+                "traffic": MEASURED_TRAFFIC_BYTES.get((a.config, "gram_bf16"))
+                if (bf16 and a.d is None and not in16) else None,
                 "algorithmic_bytes": dist_bytes,
                 "avg_launch_ms": round(dist_avg_s * 1e3, 4), "launches": dist_launches}
     if a.dist_algo != "direct":
         # matrix-core work of the same kernel: lower block triangle of 16x16 tiles, one (fp32) or six
         # (split bf16) products per tile and coordinate
         tiles = nb * (nb + 1) // 2
-        flops = tiles * 256 * 2 * (6 if bf16 else 1) * (d / nchunks)
-        peak = MFMA_BF16_PEAK_TFLOPS if bf16 else MFMA_FP32_PEAK_TFLOPS
-        roofline["matrix_cores"] = {"dtype": "bf16" if bf16 else "f32", "tflops": round(flops / dist_avg_s / 1e12, 1),
+        flops = tiles * 256 * 2 * (1 if in16 else 6 if bf16 else 1) * (d / nchunks)
+        peak = MFMA_BF16_PEAK_TFLOPS if (bf16 or in16) else MFMA_FP32_PEAK_TFLOPS
+        roofline["matrix_cores"] = {"dtype": "bf16" if (bf16 or in16) else "f32", "tflops": round(flops / dist_avg_s / 1e12, 1),
                                     "peak": peak, "frac": round(flops / dist_avg_s / 1e12 / peak, 4)}
 
     per_stage = {k: round(v[0] / a.steps, 4) for k, v in stages.items()}
     coord_ms, coord_launches = stages["coord"]
     if rows2 is not None and coord_launches:
-        coord_bytes = 4.0 * (rows2 + 1) * d / nchunks
+        coord_bytes = (eb * rows2 + 4.0) * d / nchunks
         per_stage["coord_GBps"] = round(coord_bytes / (coord_ms / 1e3 / coord_launches) / 1e9, 1)
-        alg_bytes = 4.0 * (n + rows2 + 1) * d
+        alg_bytes = (eb * (n + rows2) + 4.0) * d
         per_stage["hbm_frac_algorithmic_bytes"] = round(alg_bytes / sec / 1e9 / HBM_PEAK_GBS, 4)
 
     res = {
-        "metric": "multi-Bulyan aggregation GB/s of gradient input (n*d*4B/s), 1 GPU",
+        "metric": "multi-Bulyan aggregation GB/s of gradient input (n*d*4B/s), 1 GPU" if not in16 else
+                  "multi-Bulyan aggregation GB/s of gradient input (n*d*2B/s, bf16 gradients), 1 GPU",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": round(sec * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"configs[{a.config - 1}]: n={n} f={f} d={d} fp32, mode={a.mode}, "
+        "config": {"workload": f"configs[{a.config - 1}]: n={n} f={f} d={d} {'bf16 gradients' if in16 else 'fp32'}, "
+                               f"mode={a.mode}, "
                                f"theta={theta} beta={beta}, chunks={nchunks}"},
         "hbm_frac_input_bytes": round(value / HBM_PEAK_GBS, 4),
         "stage_ms_per_step": per_stage,
@@ -204,11 +222,11 @@ def main():
         import numpy as np
         import oracle as O
         ds = min(a.cpu_sample, chunks[0].shape[1])
-        host = chunks[0][:, :ds].contiguous().cpu().numpy()
+        host = chunks[0][:, :ds].float().contiguous().cpu().numpy()
         c0 = time.perf_counter()
         O.mbulyan(host, f, O.MODE_SELECTED if mode == mb.MODE_SELECTED else O.MODE_ALG1)
         c1 = time.perf_counter()
-        res["cpu_baseline"] = {"value": round(4.0 * n * ds / (c1 - c0) / 1e9, 3), "unit": "GB/s",
+        res["cpu_baseline"] = {"value": round(eb * n * ds / (c1 - c0) / 1e9, 3), "unit": "GB/s",
                                "cores": O.last_threads(), "kind": "oracle",
                                "sample": f"first {ds} of {d} coordinates, all {n} rows, whole rule, "
                                          f"{round(c1 - c0, 2)} s"}

@@ -196,6 +196,31 @@ int coordwise_trimmed_avg(const float *grads, int n, int64_t d, int64_t ld,
                           const uint8_t *agr_sets, float *out, void *stream);
 
 /*
+ * Gradients stored as bf16 (raw 16-bit words, the upper half of the fp32 bit
+ * pattern; ld in elements): the same operations of Algorithm 1 on half the
+ * bytes.  Every bf16 value is an fp32 value, so the results are those of the
+ * fp32 entry points on the widened matrix, to the same tolerances; distances
+ * and out stay fp64 / fp32.  The fast paths need rows that start on 16-byte
+ * boundaries (distance pass: grads % 16 == 0 and ld % 8 == 0) and 4-byte
+ * boundaries (coordinate pass: grads % 4 == 0, ld % 2 == 0, out % 8 == 0);
+ * anything else takes element loads.  MB_MODE_SELECTED only.
+ *   pairwise_sqdist_bf16        as pairwise_sqdist (Gram form; there is one
+ *                               exact product per pair and coordinate)
+ *   coordwise_trimmed_avg_bf16  as coordwise_trimmed_avg with agr_sets == NULL
+ *   mbulyan_aggregate_bf16      as mbulyan_aggregate_ex in MB_MODE_SELECTED
+ */
+int pairwise_sqdist_bf16(const uint16_t *grads, int n, int64_t d, int64_t ld,
+                         double *dist, int accumulate, void *workspace,
+                         size_t ws_bytes, void *stream);
+int coordwise_trimmed_avg_bf16(const uint16_t *grads, int n, int64_t d,
+                               int64_t ld, const int32_t *selected_idx,
+                               int theta, int beta, float *out, void *stream);
+int mbulyan_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d,
+                           int64_t ld, int theta, int beta, float *out,
+                           int32_t *selected_idx, void *workspace,
+                           size_t ws_bytes, void *stream);
+
+/*
  * Multi-Krum as a GAR (Algorithm 1, function multi-Krum, G^output): the
  * average of the m = n-f-2 gradients of smallest score.  Needs n >= 2f+3.
  *   selected_mask device, n bytes, may be NULL: 1 for the averaged gradients

@@ -26,6 +26,7 @@ EXPORTS = [
     "mbulyan_aggregate_chunked", "pairwise_sqdist", "krum_scores", "multikrum_select",
     "coordwise_trimmed_avg", "multikrum_aggregate", "coordwise_median", "mbulyan_timing_enable",
     "mbulyan_timing_reset", "mbulyan_timing_read", "mbulyan_release",
+    "pairwise_sqdist_bf16", "coordwise_trimmed_avg_bf16", "mbulyan_aggregate_bf16",
 ]
 
 
@@ -38,7 +39,7 @@ class MBulyanError(RuntimeError):
 def _load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(
-            f"{LIB_PATH} is missing: build it with `python -m paper_1905_04374_amd.build` "
+            f"{LIB_PATH} is missing: build it with `python paper_1905_04374_amd/build.py` "
             "(there is no fallback implementation)")
     lib = C.CDLL(LIB_PATH)
     vp, i64, sz = C.c_void_p, C.c_int64, C.c_size_t
@@ -59,6 +60,9 @@ def _load() -> C.CDLL:
     lib.coordwise_trimmed_avg.argtypes = [vp, ci, i64, i64, vp, ci, ci, vp, vp, vp]
     lib.multikrum_aggregate.argtypes = [vp, ci, ci, i64, i64, vp, vp, vp, sz, vp]
     lib.coordwise_median.argtypes = [vp, ci, i64, i64, vp, vp]
+    lib.pairwise_sqdist_bf16.argtypes = [vp, ci, i64, i64, vp, ci, vp, sz, vp]
+    lib.coordwise_trimmed_avg_bf16.argtypes = [vp, ci, i64, i64, vp, ci, ci, vp, vp]
+    lib.mbulyan_aggregate_bf16.argtypes = [vp, ci, ci, i64, i64, ci, ci, vp, vp, vp, sz, vp]
     lib.mbulyan_timing_enable.argtypes = [ci]
     lib.mbulyan_timing_read.argtypes = [C.POINTER(C.c_double), C.POINTER(i64)]
     return lib
@@ -89,10 +93,12 @@ def _dev(t: torch.Tensor | None, dtype, name: str) -> int | None:
     return t.data_ptr()
 
 
-def _matrix(grads: torch.Tensor):
-    """(pointer, n, d, ld) of an (n, d) float32 CUDA tensor with unit column stride."""
-    if not grads.is_cuda or grads.dtype != torch.float32 or grads.dim() != 2:
-        raise TypeError("grads must be a 2-D float32 CUDA tensor")
+def _matrix(grads: torch.Tensor, bf16_ok: bool = False):
+    """(pointer, n, d, ld) of an (n, d) float32 CUDA tensor with unit column stride (bfloat16 where
+    the entry point has a bf16 form; ld is in elements)."""
+    ok = (torch.float32, torch.bfloat16) if bf16_ok else (torch.float32,)
+    if not grads.is_cuda or grads.dtype not in ok or grads.dim() != 2:
+        raise TypeError("grads must be a 2-D CUDA tensor of " + " or ".join(str(t) for t in ok))
     n, d = grads.shape
     if d > 1 and grads.stride(1) != 1:
         raise ValueError("grads must have unit stride along the coordinates")
@@ -145,7 +151,8 @@ def mbulyan_aggregate(grads, f, out=None, selected_idx=None, stream=None):
 
 def mbulyan_aggregate_ex(grads, f, mode=MODE_SELECTED, theta=0, beta=0, out=None, selected_idx=None,
                          workspace=None, stream=None):
-    p, n, d, ld = _matrix(grads)
+    """grads may be bfloat16 (MODE_SELECTED only): the bf16 entry point runs, out stays float32."""
+    p, n, d, ld = _matrix(grads, bf16_ok=True)
     th_def, _ = mbulyan_params(n, f, mode)
     th = theta or th_def
     if out is None:
@@ -153,6 +160,13 @@ def mbulyan_aggregate_ex(grads, f, mode=MODE_SELECTED, theta=0, beta=0, out=None
     if selected_idx is None:
         selected_idx = torch.empty(th, device=grads.device, dtype=torch.int32)
     wp, wb = _ws(workspace)
+    if grads.dtype == torch.bfloat16:
+        if mode != MODE_SELECTED:
+            raise ValueError("bfloat16 gradients: MODE_SELECTED only")
+        _check(lib.mbulyan_aggregate_bf16(p, n, f, d, ld, theta, beta, _dev(out, torch.float32, "out"),
+                                          _dev(selected_idx, torch.int32, "selected_idx"), wp, wb,
+                                          _stream(stream)))
+        return out, selected_idx
     _check(lib.mbulyan_aggregate_ex(p, n, f, d, ld, mode, theta, beta, _dev(out, torch.float32, "out"),
                                     _dev(selected_idx, torch.int32, "selected_idx"), wp, wb, _stream(stream)))
     return out, selected_idx
@@ -183,12 +197,17 @@ def mbulyan_aggregate_chunked(chunks, f, mode=MODE_SELECTED, outs=None, selected
 
 
 def pairwise_sqdist(grads, dist=None, accumulate=False, algo=DIST_AUTO, workspace=None, stream=None):
-    p, n, d, ld = _matrix(grads)
+    """grads may be bfloat16: the bf16 entry point runs (Gram form, algo is not used)."""
+    p, n, d, ld = _matrix(grads, bf16_ok=True)
     if dist is None:
         if accumulate:
             raise ValueError("accumulate needs an existing dist")
         dist = torch.empty(n, n, device=grads.device, dtype=torch.float64)
     wp, wb = _ws(workspace)
+    if grads.dtype == torch.bfloat16:
+        _check(lib.pairwise_sqdist_bf16(p, n, d, ld, _dev(dist, torch.float64, "dist"), int(accumulate), wp, wb,
+                                        _stream(stream)))
+        return dist
     _check(lib.pairwise_sqdist(p, n, d, ld, _dev(dist, torch.float64, "dist"), int(accumulate), algo, wp, wb,
                                _stream(stream)))
     return dist
@@ -215,9 +234,17 @@ def multikrum_select(dist, f, theta, want_sets=True, stream=None):
 
 
 def coordwise_trimmed_avg(grads, selected_idx, beta, agr_sets=None, out=None, stream=None):
-    p, n, d, ld = _matrix(grads)
+    """grads may be bfloat16 when agr_sets is None."""
+    p, n, d, ld = _matrix(grads, bf16_ok=True)
     if out is None:
         out = torch.empty(d, device=grads.device, dtype=torch.float32)
+    if grads.dtype == torch.bfloat16:
+        if agr_sets is not None:
+            raise ValueError("bfloat16 gradients: agr_sets must be None")
+        _check(lib.coordwise_trimmed_avg_bf16(p, n, d, ld, _dev(selected_idx, torch.int32, "selected_idx"),
+                                              selected_idx.numel(), beta, _dev(out, torch.float32, "out"),
+                                              _stream(stream)))
+        return out
     _check(lib.coordwise_trimmed_avg(p, n, d, ld, _dev(selected_idx, torch.int32, "selected_idx"),
                                      selected_idx.numel(), beta, _dev(agr_sets, torch.uint8, "agr_sets"),
                                      _dev(out, torch.float32, "out"), _stream(stream)))

@@ -1,6 +1,8 @@
 """Build libmbulyan.so (gfx950) in-tree with hipcc.
 
-    python -m paper_1905_04374_amd.build [-j N] [--force]
+    python paper_1905_04374_amd/build.py [-j N] [--force]
+
+(run as a script: importing the package needs the library this makes)
 
 Objects go to paper_1905_04374_amd/_build/, the library next to this file.
 The coordinate-pass sources are compiled once per group of theta values
@@ -46,6 +48,7 @@ def units():
          ("rowops.o", "rowops.hip", [])]
     for g in range(8):
         u.append((f"coordwise_g{g}.o", "coordwise.hip", NO_NANS + [f"-DMB_GROUP={g}"]))
+        u.append((f"coordwise16_g{g}.o", "coordwise.hip", NO_NANS + [f"-DMB_GROUP={g}", "-DMB_IN16=1"]))
     for g in range(8):
         u.append((f"coordwise_alg1_g{g}.o", "coordwise_alg1.hip", NO_NANS + [f"-DMB_GROUP={g}"]))
     return u

@@ -162,6 +162,22 @@ int check_matrix(const void *grads, int n, int64_t d, int64_t ld)
 }
 
 // distances of one matrix into ws.dist()
+// gradients stored as bf16: Gram form only (one exact bf16 product per pair and coordinate)
+int run_dist_in16(const uint16_t *grads, int n, int64_t d, int64_t ld, double *dist, int accumulate,
+                  const Workspace &ws, hipStream_t s)
+{
+    const int slots = mb::gram_slots(n);
+    int nblocks = 0;
+    {
+        StageTimer t(MB_STAGE_DIST, s);
+        MB_HIP(mb::launch_dist_gram_in16(grads, n, d, ld, ws.partials(), &nblocks, s));
+    }
+    StageTimer t(MB_STAGE_REDUCE, s);
+    MB_HIP(mb::launch_reduce(ws.partials(), nblocks, slots, slots, ws.reduced(), s));
+    MB_HIP(mb::launch_finalize_gram(ws.reduced(), n, dist, accumulate, false, s));
+    return MB_OK;
+}
+
 int run_dist(const float *grads, int n, int64_t d, int64_t ld, double *dist, int accumulate, int algo,
              const Workspace &ws, hipStream_t s)
 {
@@ -191,15 +207,16 @@ int run_dist(const float *grads, int n, int64_t d, int64_t ld, double *dist, int
     return MB_OK;
 }
 
-int run_coord(const float *grads, int n, int64_t d, int64_t ld, int mode, int theta, int beta,
+int run_coord(const void *grads, int in16, int n, int64_t d, int64_t ld, int mode, int theta, int beta,
               const int32_t *sel, const uint8_t *sets, int32_t *plan, float *out, hipStream_t s)
 {
     StageTimer t(MB_STAGE_COORD, s);
     if (mode == MB_MODE_SELECTED) {
-        mb::CoordArgs a{grads, n, d, ld, sel, theta, beta, 0, out};
+        mb::CoordArgs a{grads, n, d, ld, sel, theta, beta, 0, out, in16};
         MB_HIP(mb::launch_coord_selected(a, s));
     } else {
-        mb::CoordAlg1Args a{grads, n, d, ld, sel, sets, theta, beta, out, plan};
+        if (in16) return MB_EUNSUPPORTED;
+        mb::CoordAlg1Args a{static_cast<const float *>(grads), n, d, ld, sel, sets, theta, beta, out, plan};
         MB_HIP(mb::launch_alg1_plan(n, theta, sel, sets, plan, s));
         MB_HIP(mb::launch_coord_alg1(a, s));
     }
@@ -223,6 +240,18 @@ namespace mb {
 hipError_t launch_coord_selected(const CoordArgs &a, hipStream_t s)
 {
     if (a.theta < 1 || a.theta > kMaxN) return hipErrorInvalidValue;
+    if (a.in16) {
+        switch ((a.theta - 1) / 8) {
+            case 0: return launch_coord16_group0(a, s);
+            case 1: return launch_coord16_group1(a, s);
+            case 2: return launch_coord16_group2(a, s);
+            case 3: return launch_coord16_group3(a, s);
+            case 4: return launch_coord16_group4(a, s);
+            case 5: return launch_coord16_group5(a, s);
+            case 6: return launch_coord16_group6(a, s);
+            default: return launch_coord16_group7(a, s);
+        }
+    }
     switch ((a.theta - 1) / 8) {
         case 0: return launch_coord_group0(a, s);
         case 1: return launch_coord_group1(a, s);
@@ -339,7 +368,7 @@ int coordwise_trimmed_avg(const float *grads, int n, int64_t d, int64_t ld, cons
         const int wrc = own_workspace(kOffPartials, &ws);
         if (wrc != MB_OK) return wrc;
     }
-    return run_coord(grads, n, d, ld, agr_sets ? MB_MODE_ALG1 : MB_MODE_SELECTED, theta, beta,
+    return run_coord(grads, 0, n, d, ld, agr_sets ? MB_MODE_ALG1 : MB_MODE_SELECTED, theta, beta,
                      selected_idx, agr_sets, agr_sets ? ws.plan() : nullptr, out, (hipStream_t)stream);
 }
 
@@ -372,7 +401,7 @@ int mbulyan_aggregate_chunked(const float *const *chunks, int nchunks, const int
                                  mode == MB_MODE_ALG1 ? ws.sets() : nullptr, ws.m(), nullptr, s));
     }
     for (int c = 0; c < nchunks; ++c) {
-        rc = run_coord(chunks[c], n, chunk_d[c], chunk_ld[c], mode, theta, beta, ws.sel(), ws.sets(), ws.plan(),
+        rc = run_coord(chunks[c], 0, n, chunk_d[c], chunk_ld[c], mode, theta, beta, ws.sel(), ws.sets(), ws.plan(),
                        outs[c], s);
         if (rc != MB_OK) return rc;
     }
@@ -401,7 +430,7 @@ int mbulyan_aggregate_ex(const float *grads, int n, int f, int64_t d, int64_t ld
         MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, ws.sel(),
                                  mode == MB_MODE_ALG1 ? ws.sets() : nullptr, ws.m(), nullptr, s));
     }
-    rc = run_coord(grads, n, d, ld, mode, theta, beta, ws.sel(), ws.sets(), ws.plan(), out, s);
+    rc = run_coord(grads, 0, n, d, ld, mode, theta, beta, ws.sel(), ws.sets(), ws.plan(), out, s);
     if (rc != MB_OK) return rc;
     if (selected_idx)
         MB_HIP(hipMemcpyAsync(selected_idx, ws.sel(), sizeof(int32_t) * theta, hipMemcpyDeviceToDevice, s));
@@ -446,8 +475,57 @@ int coordwise_median(const float *grads, int n, int64_t d, int64_t ld, float *ou
     if (rc != MB_OK) return rc;
     if (!out) return MB_EINVAL;
     StageTimer t(MB_STAGE_COORD, (hipStream_t)stream);
-    mb::CoordArgs a{grads, n, d, ld, nullptr, n, 1, 1, out};
+    mb::CoordArgs a{grads, n, d, ld, nullptr, n, 1, 1, out, 0};
     MB_HIP(mb::launch_coord_selected(a, (hipStream_t)stream));
+    return MB_OK;
+}
+
+// ---- gradients stored as bf16 ----------------------------------------------
+int pairwise_sqdist_bf16(const uint16_t *grads, int n, int64_t d, int64_t ld, double *dist, int accumulate,
+                         void *workspace, size_t ws_bytes, void *stream)
+{
+    int rc = check_matrix(grads, n, d, ld);
+    if (rc != MB_OK) return rc;
+    if (!dist) return MB_EINVAL;
+    Workspace ws;
+    rc = get_workspace(workspace, ws_bytes, n, d, &ws);
+    if (rc != MB_OK) return rc;
+    return run_dist_in16(grads, n, d, ld, dist, accumulate ? 1 : 0, ws, (hipStream_t)stream);
+}
+
+int coordwise_trimmed_avg_bf16(const uint16_t *grads, int n, int64_t d, int64_t ld, const int32_t *selected_idx,
+                               int theta, int beta, float *out, void *stream)
+{
+    const int rc = check_matrix(grads, n, d, ld);
+    if (rc != MB_OK) return rc;
+    if (!selected_idx || !out || theta < 1 || theta > n || beta < 1 || beta > theta) return MB_EINVAL;
+    return run_coord(grads, 1, n, d, ld, MB_MODE_SELECTED, theta, beta, selected_idx, nullptr, nullptr, out,
+                     (hipStream_t)stream);
+}
+
+int mbulyan_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d, int64_t ld, int theta, int beta,
+                           float *out, int32_t *selected_idx, void *workspace, size_t ws_bytes, void *stream)
+{
+    int rc = check_matrix(grads, n, d, ld);
+    if (rc != MB_OK) return rc;
+    if (!out || f < 0 || theta < 0 || beta < 0) return MB_EINVAL;
+    if (n < 4 * f + 3) return MB_EPRECOND;
+    rc = resolve_params(n, f, MB_MODE_SELECTED, &theta, &beta);
+    if (rc != MB_OK) return rc;
+    Workspace ws;
+    rc = get_workspace(workspace, ws_bytes, n, d, &ws);
+    if (rc != MB_OK) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    rc = run_dist_in16(grads, n, d, ld, ws.dist(), 0, ws, s);
+    if (rc != MB_OK) return rc;
+    {
+        StageTimer t(MB_STAGE_SELECT, s);
+        MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, ws.sel(), nullptr, ws.m(), nullptr, s));
+    }
+    rc = run_coord(grads, 1, n, d, ld, MB_MODE_SELECTED, theta, beta, ws.sel(), nullptr, nullptr, out, s);
+    if (rc != MB_OK) return rc;
+    if (selected_idx)
+        MB_HIP(hipMemcpyAsync(selected_idx, ws.sel(), sizeof(int32_t) * theta, hipMemcpyDeviceToDevice, s));
     return MB_OK;
 }
 

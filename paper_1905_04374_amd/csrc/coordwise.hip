@@ -93,15 +93,22 @@ __device__ __forceinline__ float closest_sum(const float (&v)[THETA], int K, boo
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 
+#ifndef MB_IN16
+#define MB_IN16 0   // 1: this unit holds the kernels for gradients stored as bf16
+#endif
 #ifndef MB_COORD_MINBLOCKS
 #define MB_COORD_MINBLOCKS 1
 #endif
 
-template <int THETA, int VEC, int WIN>
+// IN16: the gradients are bf16 (raw 16-bit words); they widen exactly to fp32 in registers and the
+// arithmetic and the output stay fp32.
+template <int THETA, int VEC, int WIN, bool IN16>
 __global__ __launch_bounds__(256, MB_COORD_MINBLOCKS) void coord_selected_kernel(
-    const float *__restrict__ G, int n, int64_t d, int64_t ld, const int32_t *__restrict__ sel,
+    const void *__restrict__ Gv, int n, int64_t d, int64_t ld, const int32_t *__restrict__ sel,
     int K, int median_only, float scale, float *__restrict__ out)
 {
+    const float *G = static_cast<const float *>(Gv);
+    const unsigned short *G16 = static_cast<const unsigned short *>(Gv);
     const int64_t c0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * VEC;
     if (c0 >= d) return;
     // row offsets of the theta extracted gradients (uniform: scalar loads), validated
@@ -115,7 +122,23 @@ __global__ __launch_bounds__(256, MB_COORD_MINBLOCKS) void coord_selected_kernel
     }
     float v[VEC][THETA];
     const bool full = (c0 + VEC <= d);
-    if (VEC == 4 && full) {
+    if constexpr (IN16) {
+        static_assert(VEC <= 2, "bf16 input: one or two coordinates per lane");
+        if (VEC == 2 && full) {
+#pragma unroll
+            for (int t = 0; t < THETA; ++t) {
+                const unsigned x = __builtin_nontemporal_load(reinterpret_cast<const unsigned *>(G16 + roff[t] + c0));
+                v[0][t] = __uint_as_float(x << 16);
+                v[1 % VEC][t] = __uint_as_float(x & 0xffff0000u);
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < THETA; ++t)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e)
+                    v[e][t] = (c0 + e < d) ? __uint_as_float((unsigned)G16[roff[t] + c0 + e] << 16) : 0.0f;
+        }
+    } else if (VEC == 4 && full) {
         // the input is read once and never again: non-temporal loads keep it from displacing
         // anything useful in the caches
 #pragma unroll
@@ -167,21 +190,22 @@ hipError_t launch_theta(const CoordArgs &a, hipStream_t s)
     constexpr int H = THETA / 2;
     const int K = a.median_only ? 0 : a.beta - (ODD ? 1 : 0);
     const float scale = a.median_only ? 1.0f : 1.0f / (float)a.beta;
-    // two coordinates per lane (8-byte loads) measured faster than four at every theta tried
-    // (11, 15, 21, 27): fewer live registers, more waves in flight
-    const bool aligned = ((uintptr_t)a.G % 8 == 0) && ((uintptr_t)a.out % 8 == 0) && (a.ld % 2 == 0);
+    // two coordinates per lane (8-byte loads; 4-byte loads of bf16 pairs) measured faster than four
+    // at every theta tried (11, 15, 21, 27): fewer live registers, more waves in flight
+    constexpr bool IN16 = MB_IN16 != 0;
+    const bool aligned = ((uintptr_t)a.G % (IN16 ? 4 : 8) == 0) && ((uintptr_t)a.out % 8 == 0) && (a.ld % 2 == 0);
     const dim3 block(256);
     if (aligned) {
         const dim3 grid((unsigned)((a.d + 511) / 512));
         if (K <= 2 && H > 2)
-            coord_selected_kernel<THETA, 2, 2><<<grid, block, 0, s>>>(a.G, a.n, a.d, a.ld, a.sel, K,
-                                                                      a.median_only, scale, a.out);
+            coord_selected_kernel<THETA, 2, 2, IN16><<<grid, block, 0, s>>>(a.G, a.n, a.d, a.ld, a.sel, K,
+                                                                            a.median_only, scale, a.out);
         else
-            coord_selected_kernel<THETA, 2, (H > 0 ? H : 1)><<<grid, block, 0, s>>>(
+            coord_selected_kernel<THETA, 2, (H > 0 ? H : 1), IN16><<<grid, block, 0, s>>>(
                 a.G, a.n, a.d, a.ld, a.sel, K, a.median_only, scale, a.out);
     } else {
         const dim3 grid((unsigned)((a.d + 255) / 256));
-        coord_selected_kernel<THETA, 1, (H > 0 ? H : 1)><<<grid, block, 0, s>>>(
+        coord_selected_kernel<THETA, 1, (H > 0 ? H : 1), IN16><<<grid, block, 0, s>>>(
             a.G, a.n, a.d, a.ld, a.sel, K, a.median_only, scale, a.out);
     }
     return hipGetLastError();
@@ -192,7 +216,11 @@ hipError_t launch_theta(const CoordArgs &a, hipStream_t s)
 #define MB_CAT2(a, b) a##b
 #define MB_CAT(a, b) MB_CAT2(a, b)
 
+#if MB_IN16
+hipError_t MB_CAT(launch_coord16_group, MB_GROUP)(const CoordArgs &a, hipStream_t s)
+#else
 hipError_t MB_CAT(launch_coord_group, MB_GROUP)(const CoordArgs &a, hipStream_t s)
+#endif
 {
     switch (a.theta - 8 * MB_GROUP) {
         case 1: return launch_theta<8 * MB_GROUP + 1>(a, s);

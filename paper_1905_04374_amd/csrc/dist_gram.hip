@@ -103,6 +103,22 @@ struct Tiles {
 #undef MB_SLICE
     }
 
+    // bf16 input: u and w hold the raw bf16 values of two 32-column steps
+    __device__ __forceinline__ void mac_in16(const Raw (&x)[NB])
+    {
+#define MB_STEP(FIELD)                                                                          \
+    {                                                                                           \
+        int t = 0;                                                                              \
+        _Pragma("unroll") for (int I = 0; I < NB; ++I)                                          \
+            _Pragma("unroll") for (int J = 0; J <= I; ++J, ++t)                                 \
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                               \
+                    __builtin_bit_cast(bf16x8, x[I].FIELD), __builtin_bit_cast(bf16x8, x[J].FIELD), \
+                    acc[t], 0, 0, 0);                                                           \
+    }
+        MB_STEP(u) MB_STEP(w)
+#undef MB_STEP
+    }
+
     // bf16 variant: six piece products, the small ones first
     __device__ __forceinline__ void mac_bf16(const Pieces (&x)[NB])
     {
@@ -347,14 +363,29 @@ inline int dma_pairs(int n) { return (n + 1) / 2; }   // load instructions per t
 // LDS bytes of one workgroup: the tile buffers and the spare slot
 inline size_t dma_lds_bytes(int n) { return (size_t)kStages * dma_pairs(n) * 1024 + 1024; }
 
-template <int NB, bool BF16, int L>
+// What the kernel reads and how it multiplies:
+//   kFp32    fp32 input, fp32 MFMA
+//   kSplit   fp32 input, every value split into three bf16 pieces (see the top of this file)
+//   kIn16    bf16 input (raw 16-bit words): products of two bf16 values are exact in fp32, one
+//            v_mfma_f32_16x16x32_bf16 per tile and 32 columns, nothing to split
+// A tile is 512 bytes of every row either way: 128 fp32 or 256 bf16 columns.
+enum Kind { kFp32 = 0, kSplit = 1, kIn16 = 2 };
+template <int KIND> constexpr int elem_bytes() { return KIND == kIn16 ? 2 : 4; }
+template <int KIND> constexpr int tile_cols() { return 512 / elem_bytes<KIND>(); }
+
+template <int NB, int KIND, int L>
 __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_kernel(
-    const float *__restrict__ G, int n, int64_t d, int64_t ld, double *__restrict__ partials)
+    const void *__restrict__ Gv, int n, int64_t d, int64_t ld, int64_t ntiles, double *__restrict__ partials)
 {
     constexpr int NT = NB * (NB + 1) / 2;
     constexpr int S = kStages;
+    constexpr int EB = elem_bytes<KIND>();
+    constexpr int TC = tile_cols<KIND>();
+    constexpr int WC = TC / 4;                    // columns of a tile that one wave multiplies
+    constexpr int kEvery = kFlush * 32 / WC;      // tiles between hand-overs: 256 columns of a wave
     static_assert(S >= 2 && L * (S - 2) < 64, "stage count");
     extern __shared__ __attribute__((aligned(16))) float lds[];
+    const char *G = static_cast<const char *>(Gv);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -364,7 +395,7 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
 
     // ---- loads: instruction j of this wave moves row pair wave + 4j ---------------------------
     const int half = lane >> 5, slot = lane & 31;
-    const float *src[L];
+    const char *src[L];
     int dst[L], dstep[L];   // float offset of the target in buffer 0, its step per buffer (same for the wave)
     bool on[L];
 #pragma unroll
@@ -373,7 +404,7 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
         const int row = 2 * p + half;
         if (2 * p < n) {
             on[j] = row < n;
-            src[j] = G + (int64_t)(on[j] ? row : 0) * ld + 4 * (slot ^ (row & 15));
+            src[j] = G + (int64_t)(on[j] ? row : 0) * ld * EB + 16 * (slot ^ (row & 15));
             dst[j] = p * 256;
             dstep[j] = tile_floats;
         } else {   // no such rows: one lane fetches 16 bytes into the spare slot, nothing reads them
@@ -387,21 +418,23 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
 #pragma unroll
         for (int j = 0; j < L; ++j) {
             if (on[j])
-                __builtin_amdgcn_global_load_lds((global_void_ptr)(src[j] + tile * kTile),
+                __builtin_amdgcn_global_load_lds((global_void_ptr)(src[j] + tile * 512),
                                                  (lds_void_ptr)(lds + dst[j] + buf * dstep[j]), 16, 0,
                                                  2 /* non-temporal */);
         }
     };
 
     // ---- reads: byte offsets of this lane's two chunks per row block (padded rows re-read row n-1)
+    // fp32: the 8 values of one 32-column step are chunks 8w+2q and 8w+2q+1;
+    // bf16: a chunk is the 8 values of one step, the wave's two steps are chunks 8w+q and 8w+4+q.
     unsigned off[2 * NB];
 #pragma unroll
     for (int I = 0; I < NB; ++I) {
         int row = 16 * I + r;
         row = row < n ? row : n - 1;
-        const int c0 = (8 * wave + 2 * q) ^ (row & 15);
+        const int c0 = (KIND == kIn16 ? 8 * wave + q : 8 * wave + 2 * q) ^ (row & 15);
         off[2 * I] = (unsigned)(row * 512 + c0 * 16);
-        off[2 * I + 1] = (unsigned)(row * 512 + (c0 ^ 1) * 16);
+        off[2 * I + 1] = (unsigned)(row * 512 + (c0 ^ (KIND == kIn16 ? 4 : 1)) * 16);
     }
     const unsigned lds0 = lds_byte_address(lds);
 
@@ -421,18 +454,19 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
         }
     };
     auto multiply = [&](const Raw (&x)[NB]) {
-        if constexpr (BF16) {
+        if constexpr (KIND == kSplit) {
             Pieces p[NB];
 #pragma unroll
             for (int I = 0; I < NB; ++I) p[I] = split8(x[I].u, x[I].w);
             tiles.mac_bf16(p);
+        } else if constexpr (KIND == kIn16) {
+            tiles.mac_in16(x);
         } else {
             tiles.mac_fp32(x);
         }
     };
 
     // ---- whole tiles b, b + g, b + 2g, ... of this workgroup ----------------------------------
-    const int64_t ntiles = d / kTile;
     const int64_t g = gridDim.x, b = blockIdx.x;
     const int64_t mine = b < ntiles ? (ntiles - b + g - 1) / g : 0;
 #pragma unroll
@@ -450,27 +484,48 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
         Raw x[NB];
         read_tile<NB>(lds0 + (unsigned)((int)(i % S) * tile_floats * 4), off, x);
         multiply(x);
-        if ((i & (kFlush - 1)) == kFlush - 1) flush();
+        if ((i & (kEvery - 1)) == kEvery - 1) flush();
     }
 
-    // ---- columns past the last whole tile (fewer than 128): element loads, one workgroup ------
-    if (b == ntiles % g) {
-        const int64_t c0 = ntiles * kTile + 32 * wave;
-        if (c0 < d) {
-            const int64_t c = c0 + 8 * q;
+    // ---- the columns after the whole tiles: element loads, a wave takes WC columns at a time,
+    //      all waves of the grid in turn (everything, when the rows are not 16-byte aligned and
+    //      ntiles = 0) --------------------------------------------------------------------------
+    {
+        const int64_t c_begin = ntiles * TC;
+        const int64_t units = (d - c_begin + WC - 1) / WC;
+        const int64_t nwaves = g * 4, gw = b * 4 + wave;
+        int64_t done = 0;
+        for (int64_t u = gw; u < units; u += nwaves, ++done) {
+            const int64_t c = c_begin + u * WC + 8 * q;      // this lane's 8 columns of the first step
             Raw x[NB];
 #pragma unroll
             for (int I = 0; I < NB; ++I) {
                 int row = 16 * I + r;
                 row = row < n ? row : n - 1;
-                const float *p = G + (int64_t)row * ld;
-                float v[8];
+                if constexpr (KIND == kIn16) {
+                    const unsigned short *p = reinterpret_cast<const unsigned short *>(G) + (int64_t)row * ld;
+                    unsigned w0[4], w1[4];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] = (c + e < d) ? p[c + e] : 0.0f;
-                x[I].u = make_float4(v[0], v[1], v[2], v[3]);
-                x[I].w = make_float4(v[4], v[5], v[6], v[7]);
+                    for (int e = 0; e < 4; ++e) {
+                        const int64_t ca = c + 2 * e, cb = c + 32 + 2 * e;
+                        w0[e] = (ca < d ? (unsigned)p[ca] : 0u) | (ca + 1 < d ? (unsigned)p[ca + 1] << 16 : 0u);
+                        w1[e] = (cb < d ? (unsigned)p[cb] : 0u) | (cb + 1 < d ? (unsigned)p[cb + 1] << 16 : 0u);
+                    }
+                    x[I].u = make_float4(__uint_as_float(w0[0]), __uint_as_float(w0[1]), __uint_as_float(w0[2]),
+                                         __uint_as_float(w0[3]));
+                    x[I].w = make_float4(__uint_as_float(w1[0]), __uint_as_float(w1[1]), __uint_as_float(w1[2]),
+                                         __uint_as_float(w1[3]));
+                } else {
+                    const float *p = reinterpret_cast<const float *>(G) + (int64_t)row * ld;
+                    float v[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v[e] = (c + e < d) ? p[c + e] : 0.0f;
+                    x[I].u = make_float4(v[0], v[1], v[2], v[3]);
+                    x[I].w = make_float4(v[4], v[5], v[6], v[7]);
+                }
             }
             multiply(x);
+            if ((done & (kEvery - 1)) == kEvery - 1) flush();
         }
     }
     flush();
@@ -497,15 +552,15 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
     for (int t = 0; t < NT; ++t) out[t * 256 + tid] = total[t];
 }
 
-template <int NB, bool BF16, int L>
-hipError_t launch_dma_l(const float *G, int n, int64_t d, int64_t ld, double *partials, int *nblocks,
+template <int NB, int KIND, int L>
+hipError_t launch_dma_l(const void *G, int n, int64_t d, int64_t ld, bool aligned, double *partials, int *nblocks,
                         hipStream_t s)
 {
     static bool prepared = false;
     static int resident[65] = {0};   // workgroups the device holds at once, by n (LDS use grows with n)
     hipError_t e;
     if (!prepared) {
-        if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gram_dma_kernel<NB, BF16, L>),
+        if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gram_dma_kernel<NB, KIND, L>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)dma_lds_bytes(16 * NB))) !=
             hipSuccess)
             return e;
@@ -516,28 +571,31 @@ hipError_t launch_dma_l(const float *G, int n, int64_t d, int64_t ld, double *pa
         int dev = 0, cus = 0, per_cu = 0;
         if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
         if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
-        if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gram_dma_kernel<NB, BF16, L>, kThreads,
+        if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gram_dma_kernel<NB, KIND, L>, kThreads,
                                                               bytes)) != hipSuccess)
             return e;
         resident[n] = cus * (per_cu < 1 ? 1 : per_cu);
     }
     // at least four tiles per workgroup: with fewer, writing and adding up the partial tiles costs
     // more than the distance pass itself
-    const int64_t ntiles = d / kTile;
+    constexpr int TC = tile_cols<KIND>();
+    const int64_t tiles = aligned ? d / TC : 0;
+    const int64_t work = aligned ? tiles : (d + TC - 1) / TC;   // element loads: a workgroup per TC columns
     int64_t g = resident[n] < kGramMaxBlocks ? resident[n] : kGramMaxBlocks;
-    if (ntiles < 4 * g) g = ntiles < 4 ? 1 : ntiles / 4;
+    if (work < 4 * g) g = work < 4 ? 1 : work / 4;
     *nblocks = (int)g;
-    gram_dma_kernel<NB, BF16, L><<<dim3((unsigned)g), dim3(kThreads), bytes, s>>>(G, n, d, ld, partials);
+    gram_dma_kernel<NB, KIND, L><<<dim3((unsigned)g), dim3(kThreads), bytes, s>>>(G, n, d, ld, tiles, partials);
     return hipGetLastError();
 }
 
-template <int NB, bool BF16>
-hipError_t launch_dma(const float *G, int n, int64_t d, int64_t ld, double *partials, int *nblocks,
+template <int NB, int KIND>
+hipError_t launch_dma(const void *G, int n, int64_t d, int64_t ld, bool aligned, double *partials, int *nblocks,
                       hipStream_t s)
 {
     // load instructions per wave and tile: ceil(pairs / 4), one of two values for each NB
-    if ((dma_pairs(n) + 3) / 4 == 2 * NB) return launch_dma_l<NB, BF16, 2 * NB>(G, n, d, ld, partials, nblocks, s);
-    return launch_dma_l<NB, BF16, 2 * NB - 1>(G, n, d, ld, partials, nblocks, s);
+    if ((dma_pairs(n) + 3) / 4 == 2 * NB)
+        return launch_dma_l<NB, KIND, 2 * NB>(G, n, d, ld, aligned, partials, nblocks, s);
+    return launch_dma_l<NB, KIND, 2 * NB - 1>(G, n, d, ld, aligned, partials, nblocks, s);
 }
 
 template <int NB, bool BF16, int DEPTH>
@@ -590,13 +648,26 @@ hipError_t launch_nb(const float *G, int n, int64_t d, int64_t ld, double *parti
                      hipStream_t s)
 {
     if (((uintptr_t)G % 16 == 0) && (ld % 4 == 0) && d >= kTile)
-        return launch_dma<NB, BF16>(G, n, d, ld, partials, nblocks, s);
+        return launch_dma<NB, BF16 ? kSplit : kFp32>(G, n, d, ld, true, partials, nblocks, s);
     constexpr int D = Depth<NB, BF16>::value;
     *nblocks = grid_for<NB, BF16, D>(d);
     return launch_one<NB, BF16, D>(G, n, d, ld, partials, *nblocks, s);
 }
 
 }  // namespace
+
+hipError_t launch_dist_gram_in16(const uint16_t *G, int n, int64_t d, int64_t ld, double *partials, int *nblocks,
+                                 hipStream_t s)
+{
+    const bool aligned = ((uintptr_t)G % 16 == 0) && (ld % 8 == 0) && d >= tile_cols<kIn16>();
+    switch (gram_blocks(n)) {
+        case 1: return launch_dma<1, kIn16>(G, n, d, ld, aligned, partials, nblocks, s);
+        case 2: return launch_dma<2, kIn16>(G, n, d, ld, aligned, partials, nblocks, s);
+        case 3: return launch_dma<3, kIn16>(G, n, d, ld, aligned, partials, nblocks, s);
+        case 4: return launch_dma<4, kIn16>(G, n, d, ld, aligned, partials, nblocks, s);
+    }
+    return hipErrorInvalidValue;
+}
 
 hipError_t launch_dist_gram(const float *G, int n, int64_t d, int64_t ld, double *partials, bool bf16,
                             int *nblocks, hipStream_t s)

@@ -24,6 +24,9 @@ hipError_t launch_dist_direct(const float *G, int n, int64_t d, int64_t ld, doub
 // launches with as many workgroups as stay resident (at most dist_grid_blocks) and reports the count
 hipError_t launch_dist_gram(const float *G, int n, int64_t d, int64_t ld, double *partials, bool bf16,
                             int *nblocks, hipStream_t s);
+// the same for gradients stored as bf16 (raw 16-bit words, ld in elements)
+hipError_t launch_dist_gram_in16(const uint16_t *G, int n, int64_t d, int64_t ld, double *partials, int *nblocks,
+                                 hipStream_t s);
 // partials[nblocks][stride] -> reduced[0..slots) (fixed summation order), then -> dist[n*n]
 hipError_t launch_reduce(const double *partials, int nblocks, int stride, int slots, double *reduced,
                          hipStream_t s);
@@ -39,7 +42,7 @@ hipError_t launch_select(const double *dist, int n, int f, int rounds, const uin
 
 // ---- coordinate pass -----------------------------------------------------
 struct CoordArgs {
-    const float *G;
+    const void *G;       // fp32, or bf16 as raw 16-bit words when in16 is set
     int n;
     int64_t d;
     int64_t ld;
@@ -48,10 +51,13 @@ struct CoordArgs {
     int beta;            // number of averaged values; ignored when median_only
     int median_only;     // output the median itself
     float *out;
+    int in16;
 };
 hipError_t launch_coord_selected(const CoordArgs &a, hipStream_t s);
 // one per translation unit, covering theta in [8g+1, 8g+8]
-#define MB_DECL_GROUP(g) hipError_t launch_coord_group##g(const CoordArgs &a, hipStream_t s);
+#define MB_DECL_GROUP(g)                                                \
+    hipError_t launch_coord_group##g(const CoordArgs &a, hipStream_t s); \
+    hipError_t launch_coord16_group##g(const CoordArgs &a, hipStream_t s);
 MB_DECL_GROUP(0) MB_DECL_GROUP(1) MB_DECL_GROUP(2) MB_DECL_GROUP(3)
 MB_DECL_GROUP(4) MB_DECL_GROUP(5) MB_DECL_GROUP(6) MB_DECL_GROUP(7)
 #undef MB_DECL_GROUP
