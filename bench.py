@@ -18,7 +18,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch of the distance kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
 # scaled by what the same counter reads for a 4 GiB device copy (FETCH_SIZE reads half the bytes
 # of the copy, WRITE_SIZE all of them); see profiles/gram_dma_kernel_cfg4_n39_d250M_hbm_traffic.md
-MEASURED_TRAFFIC_BYTES = {(4, "gram_bf16"): 2 * 19043035 * 1024 + 9216 * 1024}
+MEASURED_TRAFFIC_BYTES = {(4, "gram_bf16"): 2 * 19043035 * 1024 + 9216 * 1024,
+                          (4, "in16"): 2 * 9521537 * 1024 + 9216 * 1024}
 MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix, published
 
@@ -182,8 +183,8 @@ def main():
         kname = f"gram_dma_kernel<{nb}, bf16 input>"
     roofline = {"kernel": kname, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get((a.config, "gram_bf16"))
-                if (bf16 and a.d is None and not in16) else None,
+                "traffic": MEASURED_TRAFFIC_BYTES.get((a.config, "in16" if in16 else "gram_bf16"))
+                if (bf16 and a.d is None) else None,
                 "algorithmic_bytes": dist_bytes,
                 "avg_launch_ms": round(dist_avg_s * 1e3, 4), "launches": dist_launches}
     if a.dist_algo != "direct":

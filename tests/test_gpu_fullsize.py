@@ -48,13 +48,20 @@ def check_separation(D, f, theta, ext):
     return worst
 
 
-@pytest.mark.parametrize("cfg", [3, 4])
-def test_full_size_single_buffer(cfg):
+@pytest.mark.parametrize("cfg,dtype", [(3, "f32"), (4, "f32"), (4, "bf16")])
+def test_full_size_single_buffer(cfg, dtype):
+    """dtype bf16: the workload rounded to bf16 once, through the bf16 entry points; the oracle gets
+    the widened values."""
     s = W.spec(cfg)
     n, f, d = s["n"], s["f"], s["d"]
-    say("full size", cfg, n, f, d)
+    say("full size", cfg, dtype, n, f, d)
     theta, beta = O.params(n, f)
     Gt = W.make(cfg, DEV)
+    if dtype == "bf16":
+        G16 = torch.empty(n, d, device=DEV, dtype=torch.bfloat16)
+        for r in range(n):
+            G16[r].copy_(Gt[r])
+        Gt = G16
     ws = torch.empty(mb.mbulyan_workspace_bytes(n, d), dtype=torch.uint8, device=DEV)
     out, sel = mb.mbulyan_aggregate_ex(Gt, f, workspace=ws)
     Dg = mb.pairwise_sqdist(Gt, workspace=ws).cpu().numpy()
@@ -62,7 +69,7 @@ def test_full_size_single_buffer(cfg):
     say("gpu done; copying", round(4e-9 * n * d, 1), "GB to the host")
     G = np.empty((n, d), np.float32)
     for r in range(n):
-        G[r] = Gt[r].cpu().numpy()
+        G[r] = Gt[r].float().cpu().numpy()
     got = out.cpu().numpy()
     sel = sel.cpu().numpy()
     del Gt, out
@@ -83,7 +90,7 @@ def test_full_size_single_buffer(cfg):
         hi = min(d, lo + step)
         ref, scale = O.coordwise_selected(G[:, lo:hi], ext, beta, want_scale=True)
         worst = max(worst, check_chunk(got[lo:hi], ref, scale))
-    say(f"cfg {cfg}: selected {ext.tolist()}, score gap {gap:.2e}, dist rel err max {rel.max():.2e}, "
+    say(f"cfg {cfg} {dtype}: selected {ext.tolist()}, score gap {gap:.2e}, dist rel err max {rel.max():.2e}, "
         f"out worst err/tol {worst:.3g}, oracle coordinate phase {time.time() - t0:.1f} s")
 
 
