@@ -208,6 +208,8 @@ int coordwise_trimmed_avg(const float *grads, int n, int64_t d, int64_t ld,
  *                               exact product per pair and coordinate)
  *   coordwise_trimmed_avg_bf16  as coordwise_trimmed_avg with agr_sets == NULL
  *   mbulyan_aggregate_bf16      as mbulyan_aggregate_ex in MB_MODE_SELECTED
+ *   mbulyan_aggregate_chunked_bf16  as mbulyan_aggregate_chunked in
+ *                               MB_MODE_SELECTED
  */
 int pairwise_sqdist_bf16(const uint16_t *grads, int n, int64_t d, int64_t ld,
                          double *dist, int accumulate, void *workspace,
@@ -219,6 +221,12 @@ int mbulyan_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d,
                            int64_t ld, int theta, int beta, float *out,
                            int32_t *selected_idx, void *workspace,
                            size_t ws_bytes, void *stream);
+int mbulyan_aggregate_chunked_bf16(const uint16_t *const *chunks, int nchunks,
+                                   const int64_t *chunk_d,
+                                   const int64_t *chunk_ld, int n, int f,
+                                   float *const *outs, int32_t *selected_idx,
+                                   void *workspace, size_t ws_bytes,
+                                   void *stream);
 
 /*
  * Multi-Krum as a GAR (Algorithm 1, function multi-Krum, G^output): the

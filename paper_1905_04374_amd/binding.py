@@ -27,6 +27,7 @@ EXPORTS = [
     "coordwise_trimmed_avg", "multikrum_aggregate", "coordwise_median", "mbulyan_timing_enable",
     "mbulyan_timing_reset", "mbulyan_timing_read", "mbulyan_release",
     "pairwise_sqdist_bf16", "coordwise_trimmed_avg_bf16", "mbulyan_aggregate_bf16",
+    "mbulyan_aggregate_chunked_bf16",
 ]
 
 
@@ -63,6 +64,8 @@ def _load() -> C.CDLL:
     lib.pairwise_sqdist_bf16.argtypes = [vp, ci, i64, i64, vp, ci, vp, sz, vp]
     lib.coordwise_trimmed_avg_bf16.argtypes = [vp, ci, i64, i64, vp, ci, ci, vp, vp]
     lib.mbulyan_aggregate_bf16.argtypes = [vp, ci, ci, i64, i64, ci, ci, vp, vp, vp, sz, vp]
+    lib.mbulyan_aggregate_chunked_bf16.argtypes = [C.POINTER(vp), ci, C.POINTER(i64), C.POINTER(i64), ci, ci,
+                                                   C.POINTER(vp), vp, vp, sz, vp]
     lib.mbulyan_timing_enable.argtypes = [ci]
     lib.mbulyan_timing_read.argtypes = [C.POINTER(C.c_double), C.POINTER(i64)]
     return lib
@@ -174,9 +177,15 @@ def mbulyan_aggregate_ex(grads, f, mode=MODE_SELECTED, theta=0, beta=0, out=None
 
 def mbulyan_aggregate_chunked(chunks, f, mode=MODE_SELECTED, outs=None, selected_idx=None, workspace=None,
                               stream=None):
-    """chunks: list of (n, d_c) float32 CUDA tensors, the column chunks of one matrix."""
+    """chunks: list of (n, d_c) float32 CUDA tensors, the column chunks of one matrix (all bfloat16
+    instead: the bf16 entry point, MODE_SELECTED only)."""
     k = len(chunks)
-    mats = [_matrix(c) for c in chunks]
+    mats = [_matrix(c, bf16_ok=True) for c in chunks]
+    in16 = chunks[0].dtype == torch.bfloat16
+    if any(c.dtype != chunks[0].dtype for c in chunks):
+        raise TypeError("all chunks must have the same dtype")
+    if in16 and mode != MODE_SELECTED:
+        raise ValueError("bfloat16 gradients: MODE_SELECTED only")
     n = mats[0][1]
     if any(m[1] != n for m in mats):
         raise ValueError("all chunks must have the same number of rows")
@@ -190,6 +199,11 @@ def mbulyan_aggregate_chunked(chunks, f, mode=MODE_SELECTED, outs=None, selected
     cl = (C.c_int64 * k)(*[m[3] for m in mats])
     op = (C.c_void_p * k)(*[_dev(o, torch.float32, "out") for o in outs])
     wp, wb = _ws(workspace)
+    if in16:
+        _check(lib.mbulyan_aggregate_chunked_bf16(cp, k, cd, cl, n, f, op,
+                                                  _dev(selected_idx, torch.int32, "selected_idx"), wp, wb,
+                                                  _stream(stream)))
+        return outs, selected_idx
     _check(lib.mbulyan_aggregate_chunked(cp, k, cd, cl, n, f, mode, op,
                                          _dev(selected_idx, torch.int32, "selected_idx"), wp, wb,
                                          _stream(stream)))

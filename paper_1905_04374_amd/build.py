@@ -55,11 +55,13 @@ def units():
 
 
 def _deps_newer(obj: str, src: str) -> bool:
-    """An object depends on its own source, every header beside it, the public headers and this file."""
+    """An object depends on its own source, every header beside it and this file; the C-ABI layer
+    also on the public headers (no other source includes them)."""
     t = os.path.getmtime(obj)
     deps = [os.path.join(CSRC, src), __file__]
     deps += [os.path.join(CSRC, name) for name in os.listdir(CSRC) if name.endswith(".hpp")]
-    deps += [os.path.join(INCLUDE, name) for name in os.listdir(INCLUDE)]
+    if src == "api.hip":
+        deps += [os.path.join(INCLUDE, name) for name in os.listdir(INCLUDE)]
     return any(os.path.getmtime(dep) > t for dep in deps)
 
 

@@ -372,10 +372,11 @@ int coordwise_trimmed_avg(const float *grads, int n, int64_t d, int64_t ld, cons
                      selected_idx, agr_sets, agr_sets ? ws.plan() : nullptr, out, (hipStream_t)stream);
 }
 
-int mbulyan_aggregate_chunked(const float *const *chunks, int nchunks, const int64_t *chunk_d,
-                              const int64_t *chunk_ld, int n, int f, int mode, float *const *outs,
-                              int32_t *selected_idx, void *workspace, size_t ws_bytes, void *stream)
+static int aggregate_chunked(const void *const *chunks, int in16, int nchunks, const int64_t *chunk_d,
+                             const int64_t *chunk_ld, int n, int f, int mode, float *const *outs,
+                             int32_t *selected_idx, void *workspace, size_t ws_bytes, void *stream)
 {
+    if (in16 && mode != MB_MODE_SELECTED) return MB_EUNSUPPORTED;
     if (!chunks || !chunk_d || !chunk_ld || !outs || nchunks < 1) return MB_EINVAL;
     int theta = 0, beta = 0;
     int rc = resolve_params(n, f, mode, &theta, &beta);
@@ -392,7 +393,10 @@ int mbulyan_aggregate_chunked(const float *const *chunks, int nchunks, const int
     if (rc != MB_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
     for (int c = 0; c < nchunks; ++c) {
-        rc = run_dist(chunks[c], n, chunk_d[c], chunk_ld[c], ws.dist(), c > 0, MB_DIST_AUTO, ws, s);
+        rc = in16 ? run_dist_in16(static_cast<const uint16_t *>(chunks[c]), n, chunk_d[c], chunk_ld[c], ws.dist(), c > 0,
+                                  ws, s)
+                  : run_dist(static_cast<const float *>(chunks[c]), n, chunk_d[c], chunk_ld[c], ws.dist(), c > 0,
+                             MB_DIST_AUTO, ws, s);
         if (rc != MB_OK) return rc;
     }
     {
@@ -401,13 +405,29 @@ int mbulyan_aggregate_chunked(const float *const *chunks, int nchunks, const int
                                  mode == MB_MODE_ALG1 ? ws.sets() : nullptr, ws.m(), nullptr, s));
     }
     for (int c = 0; c < nchunks; ++c) {
-        rc = run_coord(chunks[c], 0, n, chunk_d[c], chunk_ld[c], mode, theta, beta, ws.sel(), ws.sets(), ws.plan(),
+        rc = run_coord(chunks[c], in16, n, chunk_d[c], chunk_ld[c], mode, theta, beta, ws.sel(), ws.sets(), ws.plan(),
                        outs[c], s);
         if (rc != MB_OK) return rc;
     }
     if (selected_idx)
         MB_HIP(hipMemcpyAsync(selected_idx, ws.sel(), sizeof(int32_t) * theta, hipMemcpyDeviceToDevice, s));
     return MB_OK;
+}
+
+int mbulyan_aggregate_chunked(const float *const *chunks, int nchunks, const int64_t *chunk_d,
+                              const int64_t *chunk_ld, int n, int f, int mode, float *const *outs,
+                              int32_t *selected_idx, void *workspace, size_t ws_bytes, void *stream)
+{
+    return aggregate_chunked(reinterpret_cast<const void *const *>(chunks), 0, nchunks, chunk_d, chunk_ld, n, f, mode,
+                             outs, selected_idx, workspace, ws_bytes, stream);
+}
+
+int mbulyan_aggregate_chunked_bf16(const uint16_t *const *chunks, int nchunks, const int64_t *chunk_d,
+                                   const int64_t *chunk_ld, int n, int f, float *const *outs,
+                                   int32_t *selected_idx, void *workspace, size_t ws_bytes, void *stream)
+{
+    return aggregate_chunked(reinterpret_cast<const void *const *>(chunks), 1, nchunks, chunk_d, chunk_ld, n, f,
+                             MB_MODE_SELECTED, outs, selected_idx, workspace, ws_bytes, stream);
 }
 
 int mbulyan_aggregate_ex(const float *grads, int n, int f, int64_t d, int64_t ld, int mode, int theta,

@@ -148,6 +148,22 @@ def test_aggregate_bf16_matches_oracle(cfg, d, placement):
     assert torch.equal(out, out2) and torch.equal(sel, sel2)
 
 
+def test_aggregate_chunked_bf16_equals_whole():
+    say("chunked bf16")
+    s = W.spec(5)
+    d = 300_000
+    Gt = W.make(5, DEV, d=d).to(torch.bfloat16)
+    whole, sel = mb.mbulyan_aggregate_ex(Gt, s["f"])
+    cuts = [0, 70_001, 70_002, 200_000, d]
+    chunks = [Gt[:, a:b].contiguous() for a, b in zip(cuts[:-1], cuts[1:])]
+    outs, sel2 = mb.mbulyan_aggregate_chunked(chunks, s["f"])
+    assert torch.equal(sel, sel2)
+    assert torch.equal(whole, torch.cat(outs))
+    G = Gt.float().cpu().numpy()
+    ref, ext = O.mbulyan(G, s["f"])
+    assert sel.cpu().numpy().tolist() == ext.tolist()
+
+
 def test_bf16_rejects_alg1_mode():
     Gt = torch.zeros(11, 64, device=DEV, dtype=torch.bfloat16)
     with pytest.raises(ValueError):
