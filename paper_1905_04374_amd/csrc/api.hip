@@ -163,8 +163,11 @@ int check_matrix(const void *grads, int n, int64_t d, int64_t ld)
 
 // distances of one matrix into ws.dist()
 // gradients stored as bf16: Gram form only (one exact bf16 product per pair and coordinate)
+// `defer` (may be null): leave the last step, Gram tiles -> distance matrix, to the selection kernel
+// (it forms the matrix itself from ws.reduced()); set to 1 when that was possible, *canon as for
+// launch_finalize_gram.
 int run_dist_in16(const uint16_t *grads, int n, int64_t d, int64_t ld, double *dist, int accumulate,
-                  const Workspace &ws, hipStream_t s)
+                  const Workspace &ws, hipStream_t s, int *defer = nullptr, bool *canon = nullptr)
 {
     const int slots = mb::gram_slots(n);
     int nblocks = 0;
@@ -174,12 +177,17 @@ int run_dist_in16(const uint16_t *grads, int n, int64_t d, int64_t ld, double *d
     }
     StageTimer t(MB_STAGE_REDUCE, s);
     MB_HIP(mb::launch_reduce(ws.partials(), nblocks, slots, slots, ws.reduced(), s));
+    if (defer && !accumulate) {
+        *defer = 1;
+        *canon = false;
+        return MB_OK;
+    }
     MB_HIP(mb::launch_finalize_gram(ws.reduced(), n, dist, accumulate, false, s));
     return MB_OK;
 }
 
 int run_dist(const float *grads, int n, int64_t d, int64_t ld, double *dist, int accumulate, int algo,
-             const Workspace &ws, hipStream_t s)
+             const Workspace &ws, hipStream_t s, int *defer = nullptr, bool *canon = nullptr)
 {
     algo = resolve_algo(algo);
     int nblocks = mb::dist_grid_blocks(d, algo);
@@ -200,6 +208,11 @@ int run_dist(const float *grads, int n, int64_t d, int64_t ld, double *dist, int
         }
         StageTimer t(MB_STAGE_REDUCE, s);
         MB_HIP(mb::launch_reduce(ws.partials(), nblocks, slots, slots, ws.reduced(), s));
+        if (defer && !accumulate) {
+            *defer = 1;
+            *canon = algo == MB_DIST_GRAM_BF16;
+            return MB_OK;
+        }
         MB_HIP(mb::launch_finalize_gram(ws.reduced(), n, dist, accumulate, algo == MB_DIST_GRAM_BF16, s));
     } else {
         return MB_EINVAL;
@@ -443,12 +456,17 @@ int mbulyan_aggregate_ex(const float *grads, int n, int f, int64_t d, int64_t ld
     rc = get_workspace(workspace, ws_bytes, n, d, &ws);
     if (rc != MB_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
-    rc = run_dist(grads, n, d, ld, ws.dist(), 0, MB_DIST_AUTO, ws, s);
+    int deferred = 0;
+    bool canon = false;
+    rc = run_dist(grads, n, d, ld, ws.dist(), 0, MB_DIST_AUTO, ws, s, &deferred, &canon);
     if (rc != MB_OK) return rc;
     {
         StageTimer t(MB_STAGE_SELECT, s);
-        MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, ws.sel(),
-                                 mode == MB_MODE_ALG1 ? ws.sets() : nullptr, ws.m(), nullptr, s));
+        uint8_t *sets = mode == MB_MODE_ALG1 ? ws.sets() : nullptr;
+        if (deferred)
+            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, theta, ws.sel(), sets, ws.m(), s));
+        else
+            MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, ws.sel(), sets, ws.m(), nullptr, s));
     }
     rc = run_coord(grads, 0, n, d, ld, mode, theta, beta, ws.sel(), ws.sets(), ws.plan(), out, s);
     if (rc != MB_OK) return rc;
@@ -475,11 +493,16 @@ int multikrum_aggregate(const float *grads, int n, int f, int64_t d, int64_t ld,
     rc = get_workspace(workspace, ws_bytes, n, d, &ws);
     if (rc != MB_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
-    rc = run_dist(grads, n, d, ld, ws.dist(), 0, MB_DIST_AUTO, ws, s);
+    int deferred = 0;
+    bool canon = false;
+    rc = run_dist(grads, n, d, ld, ws.dist(), 0, MB_DIST_AUTO, ws, s, &deferred, &canon);
     if (rc != MB_OK) return rc;
     {
         StageTimer t(MB_STAGE_SELECT, s);
-        MB_HIP(mb::launch_select(ws.dist(), n, f, 1, nullptr, ws.sel(), ws.sets(), ws.m(), nullptr, s));
+        if (deferred)
+            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, 1, ws.sel(), ws.sets(), ws.m(), s));
+        else
+            MB_HIP(mb::launch_select(ws.dist(), n, f, 1, nullptr, ws.sel(), ws.sets(), ws.m(), nullptr, s));
     }
     {
         StageTimer t(MB_STAGE_COORD, s);
@@ -536,11 +559,16 @@ int mbulyan_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d, int64
     rc = get_workspace(workspace, ws_bytes, n, d, &ws);
     if (rc != MB_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
-    rc = run_dist_in16(grads, n, d, ld, ws.dist(), 0, ws, s);
+    int deferred = 0;
+    bool canon = false;
+    rc = run_dist_in16(grads, n, d, ld, ws.dist(), 0, ws, s, &deferred, &canon);
     if (rc != MB_OK) return rc;
     {
         StageTimer t(MB_STAGE_SELECT, s);
-        MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, ws.sel(), nullptr, ws.m(), nullptr, s));
+        if (deferred)
+            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, theta, ws.sel(), nullptr, ws.m(), s));
+        else
+            MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, ws.sel(), nullptr, ws.m(), nullptr, s));
     }
     rc = run_coord(grads, 1, n, d, ld, MB_MODE_SELECTED, theta, beta, ws.sel(), nullptr, nullptr, out, s);
     if (rc != MB_OK) return rc;

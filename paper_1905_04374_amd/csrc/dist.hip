@@ -122,16 +122,6 @@ __global__ void finalize_direct_kernel(const double *__restrict__ reduced, int n
 }
 
 // ------------------------------------------------- gram: matrix -> distances
-// Element (i, j), i >= j, of the Gram matrix inside the reduced tile array.  Tile (I, J) holds
-// rows 16I.. as the A operand and rows 16J.. as the B operand; the instruction leaves entry
-// (a, b) of its 16x16 result in register a%4 of lane 16*(a/4) + b.
-__device__ __forceinline__ double gram_at(const double *__restrict__ reduced, int i, int j)
-{
-    const int I = i >> 4, J = j >> 4, a = i & 15, b = j & 15;
-    const int t = I * (I + 1) / 2 + J;
-    return reduced[t * 256 + (a & 3) * 64 + 16 * (a >> 2) + b];
-}
-
 // canon != 0: rows at distance exactly 0 from an earlier row are copies of it and take over its
 // distance row.  The split-bf16 products are not symmetric in their operands (hi*lo and lo*hi are
 // added at different moments), so without this two bit-identical rows could get distance rows that

@@ -16,6 +16,16 @@ constexpr int kGramMaxBlocks = 2048;
 inline int gram_blocks(int n) { return (n + 15) / 16; }
 inline int gram_slots(int n) { int nb = gram_blocks(n); return nb * (nb + 1) / 2 * 256; }
 
+// Element (i, j), i >= j, of the Gram matrix inside the reduced tile array.  Tile (I, J) holds
+// rows 16I.. as the A operand and rows 16J.. as the B operand; the instruction leaves entry
+// (a, b) of its 16x16 result in register a%4 of lane 16*(a/4) + b.
+__device__ __forceinline__ double gram_at(const double *__restrict__ reduced, int i, int j)
+{
+    const int I = i >> 4, J = j >> 4, a = i & 15, b = j & 15;
+    const int t = I * (I + 1) / 2 + J;
+    return reduced[t * 256 + (a & 3) * 64 + 16 * (a >> 2) + b];
+}
+
 // Upper bound on the number of workgroups the distance kernels are launched with (sizes the partials).
 int dist_grid_blocks(int64_t d, int algo);
 
@@ -39,6 +49,10 @@ hipError_t launch_finalize_gram(const double *reduced, int n, double *dist, int 
 hipError_t launch_select(const double *dist, int n, int f, int rounds, const uint8_t *active_in,
                          int32_t *sel, uint8_t *agr_sets, int32_t *m_out, double *scores_out,
                          hipStream_t s);
+// The same starting from the reduced Gram tiles of the distance pass: the kernel forms the distance
+// matrix itself (what launch_finalize_gram would write, canon as there) and saves that launch.
+hipError_t launch_select_gram(const double *reduced, bool canon, int n, int f, int rounds, int32_t *sel,
+                              uint8_t *agr_sets, int32_t *m_out, hipStream_t s);
 
 // ---- coordinate pass -----------------------------------------------------
 struct CoordArgs {

@@ -140,23 +140,66 @@ __device__ __forceinline__ void play_rounds(const Rounds &a, int i)
     }
 }
 
+// dist != null: the distance matrix.  Otherwise gram = the reduced Gram tiles of the distance pass,
+// and the matrix is formed here exactly as finalize_gram_kernel forms it (canon as there).
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
-    const double *__restrict__ dist, int n, int f, int rounds, const uint8_t *__restrict__ active_in,
-    int32_t *__restrict__ sel, uint8_t *__restrict__ agr_sets, int32_t *__restrict__ m_out,
-    double *__restrict__ scores_out)
+    const double *__restrict__ dist, const double *__restrict__ gram, int canon, int n, int f, int rounds,
+    const uint8_t *__restrict__ active_in, int32_t *__restrict__ sel, uint8_t *__restrict__ agr_sets,
+    int32_t *__restrict__ m_out, double *__restrict__ scores_out)
 {
     __shared__ double sD[kMaxN * kMaxN];        // first dist[i][j], then row i in ascending order
     __shared__ unsigned char sJ[kMaxN * kMaxN]; // neighbour index by rank within row i
     __shared__ unsigned char sR[kMaxN * kMaxN]; // rank of neighbour j within row i
+    __shared__ int rep[kMaxN];
     const int tid = threadIdx.x;
     const double inf = __builtin_huge_val();
 
-    for (int e = tid; e < n * n; e += kSelThreads) {
-        double x = dist[e];
-        if (!(x == x)) x = inf;                 // a NaN distance never makes a neighbour
-        sD[(e / n) * kMaxN + (e % n)] = x;
+    if (dist) {
+        for (int e = tid; e < n * n; e += kSelThreads) {
+            double x = dist[e];
+            if (!(x == x)) x = inf;                 // a NaN distance never makes a neighbour
+            sD[(e / n) * kMaxN + (e % n)] = x;
+        }
+        __syncthreads();
+    } else {
+        for (int e = tid; e < n * n; e += kSelThreads) {
+            const int i = e / n, j = e % n;
+            const int hi = i > j ? i : j, lo = i > j ? j : i;
+            double v = 0.0;
+            if (hi != lo) {
+                v = (gram_at(gram, hi, hi) + gram_at(gram, lo, lo)) - 2.0 * gram_at(gram, hi, lo);
+                v = v < 0.0 ? 0.0 : v;
+            }
+            sD[i * kMaxN + j] = v;
+        }
+        __syncthreads();
+        if (tid < n) {
+            int r = tid;
+            if (canon)
+                for (int i = 0; i < tid; ++i)
+                    if (sD[i * kMaxN + tid] == 0.0) { r = i; break; }
+            rep[tid] = r;
+        }
+        __syncthreads();
+        double mine[kPerThread];
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) {
+            const int e = tid + k * kSelThreads;
+            mine[k] = 0.0;
+            if (e < n * n) mine[k] = sD[rep[e / n] * kMaxN + rep[e % n]];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) {
+            const int e = tid + k * kSelThreads;
+            if (e < n * n) {
+                double x = mine[k];
+                if (!(x == x)) x = inf;
+                sD[(e / n) * kMaxN + (e % n)] = x;
+            }
+        }
+        __syncthreads();
     }
-    __syncthreads();
 
     // rank of j among the neighbours of i (everything but i itself), keys (distance, index)
     double myv[kPerThread];
@@ -214,8 +257,16 @@ hipError_t launch_select(const double *dist, int n, int f, int rounds, const uin
                          int32_t *sel, uint8_t *agr_sets, int32_t *m_out, double *scores_out,
                          hipStream_t s)
 {
-    select_kernel<<<dim3(1), dim3(kSelThreads), 0, s>>>(dist, n, f, rounds, active_in, sel, agr_sets,
+    select_kernel<<<dim3(1), dim3(kSelThreads), 0, s>>>(dist, nullptr, 0, n, f, rounds, active_in, sel, agr_sets,
                                                         m_out, scores_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_select_gram(const double *reduced, bool canon, int n, int f, int rounds, int32_t *sel,
+                              uint8_t *agr_sets, int32_t *m_out, hipStream_t s)
+{
+    select_kernel<<<dim3(1), dim3(kSelThreads), 0, s>>>(nullptr, reduced, canon ? 1 : 0, n, f, rounds, nullptr, sel,
+                                                        agr_sets, m_out, nullptr);
     return hipGetLastError();
 }
 
