@@ -38,6 +38,15 @@ __device__ __forceinline__ double read_lane(double x, int lane)   // lane: the s
     return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
 }
 
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double x)   // x of the lane the DPP control selects
+{
+    const unsigned long long u = (unsigned long long)__double_as_longlong(x);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(unsigned)u, CTRL, 0xf, 0xf, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(unsigned)(u >> 32), CTRL, 0xf, 0xf, true);
+    return __longlong_as_double((long long)(((unsigned long long)(unsigned)hi << 32) | (unsigned)lo));
+}
+
 // One wave, lane i = gradient i, ordered row in NV >= n - 1 registers.
 // `near`: bit r set while the r-th nearest neighbour of i is still active.
 // `take`: the q lowest set bits of `near`, the neighbours whose distances make up the score.
@@ -111,17 +120,18 @@ __device__ __forceinline__ void play_rounds(const Rounds &a, int i)
             w = first ? (int)__builtin_ctzll(first) : 0;
             if (i < n) a.agr_sets[t * n + i] = (mine && pos < q) ? 1 : 0;
         } else {
-            double bs = S;
-            int bi = mine ? i : kMaxN;
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) {
-                const double os = __shfl_xor(bs, off, 64);
-                const int oi = __shfl_xor(bi, off, 64);
-                const bool better = os < bs || (os == bs && oi < bi);
-                bs = better ? os : bs;
-                bi = better ? oi : bi;
-            }
-            w = bi < kMaxN ? bi : 0;
+            // smallest score of the wave, then the first active lane that has it: the same as
+            // the smallest (score, index).  Data-parallel moves inside rows of 16 lanes (min is
+            // idempotent, so swaps and mirrors do), lane reads across the four rows.
+            double mn = S;
+            mn = fmin(mn, dpp_move<0xB1>(mn));     // quad_perm [1,0,3,2]
+            mn = fmin(mn, dpp_move<0x4E>(mn));     // quad_perm [2,3,0,1]
+            mn = fmin(mn, dpp_move<0x141>(mn));    // row_half_mirror
+            mn = fmin(mn, dpp_move<0x140>(mn));    // row_mirror
+            const double best = fmin(fmin(read_lane(mn, 0), read_lane(mn, 16)),
+                                     fmin(read_lane(mn, 32), read_lane(mn, 48)));
+            const unsigned long long first = __ballot(mine && S == best);
+            w = first ? (int)__builtin_ctzll(first) : 0;
         }
         if (a.sel && i == 0) a.sel[t] = w;
         if (a.m_out && i == 0) a.m_out[t] = q < k ? q : k;
