@@ -210,6 +210,8 @@ int coordwise_trimmed_avg(const float *grads, int n, int64_t d, int64_t ld,
  *   mbulyan_aggregate_bf16      as mbulyan_aggregate_ex in MB_MODE_SELECTED
  *   mbulyan_aggregate_chunked_bf16  as mbulyan_aggregate_chunked in
  *                               MB_MODE_SELECTED
+ *   multikrum_aggregate_bf16    as multikrum_aggregate
+ *   coordwise_median_bf16       as coordwise_median
  */
 int pairwise_sqdist_bf16(const uint16_t *grads, int n, int64_t d, int64_t ld,
                          double *dist, int accumulate, void *workspace,
@@ -221,6 +223,11 @@ int mbulyan_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d,
                            int64_t ld, int theta, int beta, float *out,
                            int32_t *selected_idx, void *workspace,
                            size_t ws_bytes, void *stream);
+int multikrum_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d,
+                             int64_t ld, float *out, uint8_t *selected_mask,
+                             void *workspace, size_t ws_bytes, void *stream);
+int coordwise_median_bf16(const uint16_t *grads, int n, int64_t d, int64_t ld,
+                          float *out, void *stream);
 int mbulyan_aggregate_chunked_bf16(const uint16_t *const *chunks, int nchunks,
                                    const int64_t *chunk_d,
                                    const int64_t *chunk_ld, int n, int f,

@@ -27,7 +27,7 @@ EXPORTS = [
     "coordwise_trimmed_avg", "multikrum_aggregate", "coordwise_median", "mbulyan_timing_enable",
     "mbulyan_timing_reset", "mbulyan_timing_read", "mbulyan_release",
     "pairwise_sqdist_bf16", "coordwise_trimmed_avg_bf16", "mbulyan_aggregate_bf16",
-    "mbulyan_aggregate_chunked_bf16",
+    "mbulyan_aggregate_chunked_bf16", "multikrum_aggregate_bf16", "coordwise_median_bf16",
 ]
 
 
@@ -66,6 +66,8 @@ def _load() -> C.CDLL:
     lib.mbulyan_aggregate_bf16.argtypes = [vp, ci, ci, i64, i64, ci, ci, vp, vp, vp, sz, vp]
     lib.mbulyan_aggregate_chunked_bf16.argtypes = [C.POINTER(vp), ci, C.POINTER(i64), C.POINTER(i64), ci, ci,
                                                    C.POINTER(vp), vp, vp, sz, vp]
+    lib.multikrum_aggregate_bf16.argtypes = [vp, ci, ci, i64, i64, vp, vp, vp, sz, vp]
+    lib.coordwise_median_bf16.argtypes = [vp, ci, i64, i64, vp, vp]
     lib.mbulyan_timing_enable.argtypes = [ci]
     lib.mbulyan_timing_read.argtypes = [C.POINTER(C.c_double), C.POINTER(i64)]
     return lib
@@ -266,22 +268,26 @@ def coordwise_trimmed_avg(grads, selected_idx, beta, agr_sets=None, out=None, st
 
 
 def multikrum_aggregate(grads, f, out=None, selected_mask=None, workspace=None, stream=None):
-    p, n, d, ld = _matrix(grads)
+    """grads may be bfloat16."""
+    p, n, d, ld = _matrix(grads, bf16_ok=True)
     if out is None:
         out = torch.empty(d, device=grads.device, dtype=torch.float32)
     if selected_mask is None:
         selected_mask = torch.empty(n, device=grads.device, dtype=torch.uint8)
     wp, wb = _ws(workspace)
-    _check(lib.multikrum_aggregate(p, n, f, d, ld, _dev(out, torch.float32, "out"),
+    fn = lib.multikrum_aggregate_bf16 if grads.dtype == torch.bfloat16 else lib.multikrum_aggregate
+    _check(fn(p, n, f, d, ld, _dev(out, torch.float32, "out"),
                                    _dev(selected_mask, torch.uint8, "selected_mask"), wp, wb, _stream(stream)))
     return out, selected_mask
 
 
 def coordwise_median(grads, out=None, stream=None):
-    p, n, d, ld = _matrix(grads)
+    """grads may be bfloat16."""
+    p, n, d, ld = _matrix(grads, bf16_ok=True)
     if out is None:
         out = torch.empty(d, device=grads.device, dtype=torch.float32)
-    _check(lib.coordwise_median(p, n, d, ld, _dev(out, torch.float32, "out"), _stream(stream)))
+    fn = lib.coordwise_median_bf16 if grads.dtype == torch.bfloat16 else lib.coordwise_median
+    _check(fn(p, n, d, ld, _dev(out, torch.float32, "out"), _stream(stream)))
     return out
 
 

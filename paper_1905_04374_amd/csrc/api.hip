@@ -546,6 +546,47 @@ int coordwise_trimmed_avg_bf16(const uint16_t *grads, int n, int64_t d, int64_t 
                      (hipStream_t)stream);
 }
 
+int multikrum_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d, int64_t ld, float *out,
+                             uint8_t *selected_mask, void *workspace, size_t ws_bytes, void *stream)
+{
+    int rc = check_matrix(grads, n, d, ld);
+    if (rc != MB_OK) return rc;
+    if (!out || f < 0) return MB_EINVAL;
+    if (n < 2 * f + 3) return MB_EPRECOND;
+    Workspace ws;
+    rc = get_workspace(workspace, ws_bytes, n, d, &ws);
+    if (rc != MB_OK) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    int deferred = 0;
+    bool canon = false;
+    rc = run_dist_in16(grads, n, d, ld, ws.dist(), 0, ws, s, &deferred, &canon);
+    if (rc != MB_OK) return rc;
+    {
+        StageTimer t(MB_STAGE_SELECT, s);
+        if (deferred)
+            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, 1, ws.sel(), ws.sets(), ws.m(), s));
+        else
+            MB_HIP(mb::launch_select(ws.dist(), n, f, 1, nullptr, ws.sel(), ws.sets(), ws.m(), nullptr, s));
+    }
+    {
+        StageTimer t(MB_STAGE_COORD, s);
+        MB_HIP(mb::launch_masked_mean_in16(grads, n, d, ld, ws.sets(), out, s));
+    }
+    if (selected_mask) MB_HIP(hipMemcpyAsync(selected_mask, ws.sets(), (size_t)n, hipMemcpyDeviceToDevice, s));
+    return MB_OK;
+}
+
+int coordwise_median_bf16(const uint16_t *grads, int n, int64_t d, int64_t ld, float *out, void *stream)
+{
+    const int rc = check_matrix(grads, n, d, ld);
+    if (rc != MB_OK) return rc;
+    if (!out) return MB_EINVAL;
+    StageTimer t(MB_STAGE_COORD, (hipStream_t)stream);
+    mb::CoordArgs a{grads, n, d, ld, nullptr, n, 1, 1, out, 1};
+    MB_HIP(mb::launch_coord_selected(a, (hipStream_t)stream));
+    return MB_OK;
+}
+
 int mbulyan_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d, int64_t ld, int theta, int beta,
                            float *out, int32_t *selected_idx, void *workspace, size_t ws_bytes, void *stream)
 {

@@ -123,5 +123,7 @@ hipError_t launch_coord_alg1_group7(const CoordAlg1Args &a, hipStream_t s);
 // out[c] = mean over rows r with mask[r] of G[r][c]
 hipError_t launch_masked_mean(const float *G, int n, int64_t d, int64_t ld, const uint8_t *mask,
                               float *out, hipStream_t s);
+hipError_t launch_masked_mean_in16(const uint16_t *G, int n, int64_t d, int64_t ld, const uint8_t *mask,
+                                   float *out, hipStream_t s);
 
 }  // namespace mb

@@ -13,11 +13,14 @@ namespace {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-template <int VEC>
-__global__ __launch_bounds__(256) void masked_mean_kernel(const float *__restrict__ G, int n, int64_t d,
+// IN16: gradients stored as bf16 (raw 16-bit words), widened exactly in registers; VEC is then 1 or 2.
+template <int VEC, bool IN16>
+__global__ __launch_bounds__(256) void masked_mean_kernel(const void *__restrict__ Gv, int n, int64_t d,
                                                           int64_t ld, const uint8_t *__restrict__ mask,
                                                           float *__restrict__ out)
 {
+    const float *G = static_cast<const float *>(Gv);
+    const unsigned short *G16 = static_cast<const unsigned short *>(Gv);
     // the membership mask as 64 bits in scalar registers (n <= 64): lane r looks at row r
     const int lane = threadIdx.x & 63;
     const unsigned long long members = __ballot(lane < n && mask[lane < n ? lane : 0] != 0);
@@ -39,6 +42,19 @@ __global__ __launch_bounds__(256) void masked_mean_kernel(const float *__restric
             const int r = r0 + j;
             if (r < n && ((members >> r) & 1ull)) {
                 ++m;
+                if constexpr (IN16) {
+                    const unsigned short *p16 = G16 + (int64_t)r * ld + c0;
+                    if (VEC == 2 && full) {
+                        const unsigned w = __builtin_nontemporal_load(reinterpret_cast<const unsigned *>(p16));
+                        x[j][0] = __uint_as_float(w << 16);
+                        x[j][1 % VEC] = __uint_as_float(w & 0xffff0000u);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e)
+                            x[j][e] = (c0 + e < d) ? __uint_as_float((unsigned)p16[e] << 16) : 0.0f;
+                    }
+                    continue;
+                }
                 const float *p = G + (int64_t)r * ld + c0;
                 if (VEC == 4 && full) {
                     const floatx4 v = __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(p));
@@ -162,9 +178,20 @@ hipError_t launch_masked_mean(const float *G, int n, int64_t d, int64_t ld, cons
 {
     const bool aligned = ((uintptr_t)G % 16 == 0) && (ld % 4 == 0);
     if (aligned)
-        masked_mean_kernel<4><<<dim3((unsigned)((d + 1023) / 1024)), dim3(256), 0, s>>>(G, n, d, ld, mask, out);
+        masked_mean_kernel<4, false><<<dim3((unsigned)((d + 1023) / 1024)), dim3(256), 0, s>>>(G, n, d, ld, mask, out);
     else
-        masked_mean_kernel<1><<<dim3((unsigned)((d + 255) / 256)), dim3(256), 0, s>>>(G, n, d, ld, mask, out);
+        masked_mean_kernel<1, false><<<dim3((unsigned)((d + 255) / 256)), dim3(256), 0, s>>>(G, n, d, ld, mask, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_masked_mean_in16(const uint16_t *G, int n, int64_t d, int64_t ld, const uint8_t *mask,
+                                   float *out, hipStream_t s)
+{
+    const bool aligned = ((uintptr_t)G % 4 == 0) && (ld % 2 == 0);
+    if (aligned)
+        masked_mean_kernel<2, true><<<dim3((unsigned)((d + 511) / 512)), dim3(256), 0, s>>>(G, n, d, ld, mask, out);
+    else
+        masked_mean_kernel<1, true><<<dim3((unsigned)((d + 255) / 256)), dim3(256), 0, s>>>(G, n, d, ld, mask, out);
     return hipGetLastError();
 }
 

@@ -164,6 +164,30 @@ def test_aggregate_chunked_bf16_equals_whole():
     assert sel.cpu().numpy().tolist() == ext.tolist()
 
 
+def test_multikrum_aggregate_bf16():
+    say("multikrum_aggregate bf16")
+    for cfg, d in [(1, 50_001), (2, 20_000), (4, 30_004)]:
+        s = W.spec(cfg)
+        Gt = W.make(cfg, DEV, d=d).to(torch.bfloat16)
+        G = Gt.float().cpu().numpy()
+        ref, mask = O.multikrum_aggregate(G, s["f"])
+        out, mask_g = mb.multikrum_aggregate(Gt, s["f"])
+        assert np.array_equal(mask_g.cpu().numpy(), mask)
+        assert_out_close(out, ref, np.abs(G[mask.astype(bool)]).mean(0))
+
+
+def test_coordwise_median_bf16():
+    say("median bf16")
+    rng = np.random.default_rng(95)
+    for n in (1, 2, 7, 11, 20, 39, 64):
+        Gt, G = to_bf16(rng.standard_normal((n, 3001)).astype(np.float32))
+        ref = O.coordwise_median(G)
+        got = mb.coordwise_median(Gt)
+        assert_out_close(got, ref, np.abs(ref), rtol=1e-6)
+        if n % 2:
+            assert np.array_equal(got.cpu().numpy(), ref)
+
+
 def test_bf16_rejects_alg1_mode():
     Gt = torch.zeros(11, 64, device=DEV, dtype=torch.bfloat16)
     with pytest.raises(ValueError):
