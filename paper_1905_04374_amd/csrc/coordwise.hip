@@ -8,7 +8,8 @@
 // around the median.  Nothing is staged in LDS: the working set is theta
 // floats per coordinate and fits the register file for theta <= 64.
 //
-// This file is compiled once per group of 8 values of theta (-DMB_GROUP=g).
+// This file is compiled once per group of 8 values of theta (-DMB_GROUP=g), and a second time
+// with -DMB_IN16=1 for gradients stored as bf16.
 #include <hip/hip_runtime.h>
 
 #include "mb_internal.hpp"
@@ -96,14 +97,11 @@ typedef float floatx2 __attribute__((ext_vector_type(2)));
 #ifndef MB_IN16
 #define MB_IN16 0   // 1: this unit holds the kernels for gradients stored as bf16
 #endif
-#ifndef MB_COORD_MINBLOCKS
-#define MB_COORD_MINBLOCKS 1
-#endif
 
 // IN16: the gradients are bf16 (raw 16-bit words); they widen exactly to fp32 in registers and the
 // arithmetic and the output stay fp32.
 template <int THETA, int VEC, int WIN, bool IN16>
-__global__ __launch_bounds__(256, MB_COORD_MINBLOCKS) void coord_selected_kernel(
+__global__ __launch_bounds__(256) void coord_selected_kernel(
     const void *__restrict__ Gv, int n, int64_t d, int64_t ld, const int32_t *__restrict__ sel,
     int K, int median_only, float scale, float *__restrict__ out)
 {

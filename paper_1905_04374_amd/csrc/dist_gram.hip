@@ -2,13 +2,18 @@
 // G = X X^T accumulated over all coordinates, D_ij = G_ii + G_jj - 2 G_ij afterwards in fp64.
 //
 // Rows are padded to NB = ceil(n/16) blocks of 16 and only the lower block triangle of G is
-// computed: NT = NB(NB+1)/2 tiles of 16x16.  A wave owns steps of 32 columns, walked
-// grid-strided so that neighbouring waves read neighbouring 128-byte lines of every row.  In a
-// step lane (r = lane%16, q = lane/16) loads the 8 floats of row 16I+r at columns 8q..8q+7 for
-// every row block I: exactly the operand layout of the MFMA instructions (row = lane%16, k
-// group = lane/16), and the A and B operands of a Gram product share it, so tile (I,J) is
-// mfma(x[I], x[J]).  Nothing is staged in LDS and the main loop has no data-dependent barrier.
-// Loads run DEPTH steps ahead in a register ring.
+// computed: NT = NB(NB+1)/2 tiles of 16x16.  In a step of 32 columns lane (r = lane%16,
+// q = lane/16) holds the 8 values of row 16I+r at columns 8q..8q+7 for every row block I:
+// exactly the operand layout of the MFMA instructions (row = lane%16, k group = lane/16), and
+// the A and B operands of a Gram product share it, so tile (I,J) is mfma(x[I], x[J]).
+//
+// Two kernels, which differ in how the operands arrive:
+//  gram_dma_kernel  rows that start on 16-byte boundaries: tiles of 512 bytes per row go from HBM
+//                   straight into LDS (described at the kernel); also takes bf16 input.
+//  gram_kernel      any alignment and stride: a wave owns steps of 32 columns, walked grid-strided
+//                   so that neighbouring waves read neighbouring 128-byte lines of every row; the
+//                   lane loads its 32 bytes itself, DEPTH steps ahead in a register ring; nothing
+//                   is staged in LDS and the main loop has no data-dependent barrier.
 //
 // Two arithmetic variants:
 //  fp32:  v_mfma_f32_16x16x4_f32, eight k-slices per step.  At n = 39 its 1536 MACs per
@@ -21,9 +26,10 @@
 //         per instruction: six of them at 16 cycles replace eight at 32, so the matrix cores
 //         stop being the limit and the kernel is bound by the HBM stream.
 //
-// Precision: the MFMA accumulators are fp32; every 8 steps (256 columns) the four waves of a
-// workgroup hand them over through LDS and each thread adds its share into fp64 sums in wave
-// order.  Workgroup sums are written as fp64 partial tiles and added over workgroups in index
+// Precision: the MFMA accumulators are fp32; every 256 columns of a wave they are handed over to
+// fp64 sums (gram_kernel: the four waves of a workgroup through LDS, each thread adding its share
+// in wave order; gram_dma_kernel: each wave its own, the waves adding up in order at the end).
+// Workgroup sums are written as fp64 partial tiles and added over workgroups in index
 // order by reduce_partials_kernel.  No atomics: the result is a function of the data only.
 #include <hip/hip_runtime.h>
 
@@ -636,11 +642,7 @@ int grid_for(int64_t d)
 // prefetch depth per variant and row-block count (register budget: 24 VGPRs per step at NB = 3)
 template <int NB, bool BF16>
 struct Depth {
-#ifdef MB_GRAM_DEPTH
-    static constexpr int value = MB_GRAM_DEPTH;
-#else
     static constexpr int value = 4;   // measured: 1..4 within 2 % of each other at n = 39, 4 best at n = 51
-#endif
 };
 
 template <int NB, bool BF16>
