@@ -2,7 +2,7 @@
 // gradients (Algorithm 1, function multi-Krum and the loop of multi-Bulyan).
 //
 // O(theta n^2) scalar work on an n x n matrix, n <= 64: one workgroup.
-// All 4 waves first order every row of the distance matrix once (rank by
+// Eight waves first order every row of the distance matrix once (rank by
 // counting, keys (distance, index)); then a single wave, lane i = gradient i,
 // plays the rounds with its ordered row held in registers and a bit mask of the
 // ranks still active: add the q nearest distances in ascending order in fp64,
@@ -110,10 +110,9 @@ __device__ __forceinline__ void play_rounds(const Rounds &a, int i)
             int pos = 0;  // position of i in that order
 #pragma unroll
             for (int j = 0; j <= NV; ++j) {
-                if (j < n) {
+                if ((act >> j) & 1ull) {       // active gradients only (same test in every lane)
                     const double Sj = read_lane(S, j);
-                    const bool aj = (act >> j) & 1ull;
-                    pos += (aj && (Sj < S || (Sj == S && j < i))) ? 1 : 0;
+                    pos += (Sj < S || (Sj == S && j < i)) ? 1 : 0;
                 }
             }
             const unsigned long long first = __ballot(mine && pos == 0);
