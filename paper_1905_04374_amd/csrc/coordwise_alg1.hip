@@ -3,21 +3,21 @@
 // that round t of multi-Krum averaged; out[c] = average of the beta values
 // G^agr[.][c] closest to M[c].
 //
-// G^agr is never materialised.  In the regular case a round's set is the
-// previous one minus its winner; the averages are then running sums over the
-// winners' values (needed for the median anyway) on top of the last round's
-// set: theta + f row streams, all in registers.  Otherwise (the order of the
-// scores changed between rounds) the theta x n membership matrix becomes signed
+// G^agr is never materialised.  The theta x n membership matrix becomes signed
 // row updates (rows entering or leaving the set from one round to the next) and
-// the running sum S_t = S_{t-1} +- few rows follows them; rows that no round
-// uses are not read at all.  A small plan kernel (rowops.hip) decides which case
-// holds and prepares both; the two kernels here read its plan with scalar loads.
+// the running sum over the current set follows them: usually a round's set is
+// the previous one minus its winner, one row per round, but any membership
+// matrix works.  Rows that no round uses are not read at all.  A small plan
+// kernel (rowops.hip) prepares the row list and the updates; the kernel here
+// reads its plan with scalar loads and keeps everything else in registers.
 //
 // Compiled once per group of 8 values of theta (-DMB_GROUP=0..7).
 #include <hip/hip_runtime.h>
 
 #include "mb_internal.hpp"
 #include "sortnet.hpp"
+
+#include <type_traits>
 
 #ifndef MB_GROUP
 #error "compile with -DMB_GROUP=0..7"
@@ -61,27 +61,196 @@ __device__ __forceinline__ float pick_closest(float (&a)[THETA], float med, int 
     return sum / (float)beta;
 }
 
-// The regular case: from one round to the next the set only loses its winner, so
-// set_t = set_{theta-1} + {winner_t .. winner_{theta-2}}.  The averages are then running sums over
-// the winners' values, which the median needs anyway: theta + f coalesced row streams, everything
-// in registers, no LDS.  The plan (winners, base rows, weights) comes from launch_alg1_plan through
-// scalar loads; every workgroup takes one tile and ends (measured faster than workgroups that
-// loop over tiles, as in the other coordinate kernel).  B1: beta = 1, the one average closest to
-// the median is picked while the running sums are formed (half the registers); a lane then owns
-// two neighbouring coordinates.
-constexpr int kRegThreads = 256;
-constexpr int kBaseRegs = 16;   // base rows loaded in one batch (the default theta leaves f <= 15)
+// One workgroup takes one tile and ends (measured faster than workgroups that loop over tiles,
+// as in the other coordinate kernel).  The winners (slots 0 .. theta-1, kept for the median) and
+// the next 16 rows are loaded in one go, further rows 16 at a time; P[t]
+// accumulates the change of the running sum in round t, sum_s delta[t][s] x[s], eight slots at a
+// time where the plan says something changes there.  Register arrays cannot be indexed at run
+// time, so the changes are multiply-adds by -1, 0 or +1 held in scalar registers.  In the usual
+// case (each round's set = the previous one minus its winner) round 0 touches every slot and every
+// later round one.  The running sums S_t = P_0 + .. + P_t times 1 / |set_t| are the averages.
+// B1: beta = 1, the one average closest to the median is picked while the running sums are formed
+// and a lane owns two neighbouring coordinates (8-byte loads when the rows allow it).
+constexpr int kThreads = 256;
+constexpr int kBatch = 16;
+
+// the slots from B0 on, kBatch at a time (compile-time recursion over the batches)
+template <int B0, class Y, class Load, class X, class Apply>
+__device__ __forceinline__ void more_slots(int U, Y &y, Load &load, X &x, Apply &apply)
+{
+    if constexpr (B0 < kMaxN) {
+        constexpr int END = B0 + kBatch < kMaxN ? B0 + kBatch : kMaxN;
+        if (B0 < U) {                                // same for every lane
+            constexpr int VEC = sizeof(y) / sizeof(y[0]);
+#pragma unroll
+            for (int j = 0; j < END - B0; ++j) {
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) y[k][j] = 0.0f;
+                if (B0 + j < U) {
+                    load(B0 + j);
+#pragma unroll
+                    for (int k = 0; k < VEC; ++k) y[k][j] = x[k];
+                }
+            }
+            apply(std::integral_constant<int, B0>{}, std::integral_constant<int, END>{},
+                  std::integral_constant<int, B0>{}, y);
+            more_slots<END>(U, y, load, x, apply);
+        }
+    }
+}
 
 template <int THETA, bool B1>
-__global__ __launch_bounds__(kRegThreads) void coord_alg1_regular_kernel(
+__global__ __launch_bounds__(kThreads) void coord_alg1_kernel(const float *__restrict__ G, int64_t d, int64_t ld,
+                                                              int beta, const int32_t *__restrict__ plan,
+                                                              int unless_nested, float *__restrict__ out)
+{
+    if (unless_nested && plan[kPlanNested]) return;   // coord_alg1_nested_kernel takes the call
+    constexpr int VEC = B1 ? 2 : 1;
+    const int64_t c = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * VEC;
+    if (c >= d) return;
+    const bool two = VEC == 2 && c + 1 < d;
+    if (plan[kPlanBad]) {
+        out[c] = __int_as_float(0x7fc00000);
+        if (two) out[c + 1] = __int_as_float(0x7fc00000);
+        return;
+    }
+    const int U = plan[kPlanNSlots];
+    const float *inv_m = reinterpret_cast<const float *>(plan + kPlanInvM);
+    const float *delta = reinterpret_cast<const float *>(plan + kPlanDelta);
+    const bool pairs_ok = VEC == 2 && ((uintptr_t)G % 8 == 0) && (ld % 2 == 0) && ((uintptr_t)out % 8 == 0);
+    const bool vec = pairs_ok && two;
+
+    float e[VEC][THETA], P[VEC][THETA];
+#pragma unroll
+    for (int t = 0; t < THETA; ++t)
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) P[k][t] = 0.0f;
+    float x[2];
+    auto load = [&](int slot) {
+        const float *p = G + (int64_t)plan[kPlanRows + slot] * ld + c;
+        if (vec) {
+            const floatx2 v = __builtin_nontemporal_load(reinterpret_cast<const floatx2 *>(p));
+            x[0] = v[0];
+            x[1] = v[1];
+        } else {
+            x[0] = __builtin_nontemporal_load(p);
+            x[1] = (VEC == 2 && two) ? __builtin_nontemporal_load(p + 1) : x[0];
+        }
+    };
+    // P[t] += sum over the slots [lo, hi) of delta[t][s] * v[s - base], group by group
+    auto apply = [&](auto lo_c, auto hi_c, auto base_c, const auto &v) {
+        constexpr int LO = decltype(lo_c)::value, HI = decltype(hi_c)::value, BASE = decltype(base_c)::value;
+#pragma unroll
+        for (int t = 0; t < THETA; ++t) {
+            const int groups = plan[kPlanGroups + t];
+#pragma unroll
+            for (int g = LO / 8; g <= (HI - 1) / 8; ++g) {
+                if (groups & (1 << g)) {             // same for every lane
+#pragma unroll
+                    for (int s2 = 8 * g; s2 < 8 * g + 8; ++s2) {
+                        if (s2 >= LO && s2 < HI) {
+                            const float dl = delta[t * kMaxN + s2];
+#pragma unroll
+                            for (int k = 0; k < VEC; ++k) P[k][t] = fmaf(dl, v[k][s2 - BASE], P[k][t]);
+                        }
+                    }
+                }
+            }
+        }
+    };
+
+    // the winners (slots 0 .. theta-1, always there) and the next kBatch rows: all loads in flight at once
+    float y[VEC][kBatch];
+#pragma unroll
+    for (int t = 0; t < THETA; ++t) {
+        load(t);
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) e[k][t] = x[k];
+    }
+    constexpr int kFirstEnd = THETA + kBatch < kMaxN ? THETA + kBatch : kMaxN;
+#pragma unroll
+    for (int j = 0; j < kFirstEnd - THETA; ++j) {
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) y[k][j] = 0.0f;
+        if (THETA + j < U) {                         // same for every lane
+            load(THETA + j);
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) y[k][j] = x[k];
+        }
+    }
+    apply(std::integral_constant<int, 0>{}, std::integral_constant<int, THETA>{}, std::integral_constant<int, 0>{}, e);
+    if constexpr (kFirstEnd > THETA) {
+        if (THETA < U)
+            apply(std::integral_constant<int, THETA>{}, std::integral_constant<int, kFirstEnd>{},
+                  std::integral_constant<int, THETA>{}, y);
+    }
+    // more rows than that (only with a theta below the default or a membership matrix of one's own)
+    more_slots<THETA + kBatch>(U, y, load, x, apply);
+
+    float res[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+        float S = 0.0f;
+        if constexpr (B1) {
+            float es[THETA];
+#pragma unroll
+            for (int t = 0; t < THETA; ++t) es[t] = e[k][t];
+            sort_registers<THETA>(es);
+            float med;
+            if constexpr (THETA & 1) med = es[THETA / 2];
+            else med = 0.5f * (es[THETA / 2 - 1] + es[THETA / 2]);
+            float best = 0.0f, bd = __builtin_huge_valf();
+#pragma unroll
+            for (int t = 0; t < THETA; ++t) {
+                S += P[k][t];
+                const float at = S * inv_m[t];
+                const float dt = fabsf(at - med);
+                const bool take = dt < bd || (dt == bd && at < best);
+                best = take ? at : best;
+                bd = take ? dt : bd;
+            }
+            res[k] = best;
+        } else {
+            float a[THETA];
+#pragma unroll
+            for (int t = 0; t < THETA; ++t) {
+                S += P[k][t];
+                a[t] = S * inv_m[t];
+            }
+            sort_registers<THETA>(e[k]);
+            float med;
+            if constexpr (THETA & 1) med = e[k][THETA / 2];
+            else med = 0.5f * (e[k][THETA / 2 - 1] + e[k][THETA / 2]);
+            res[k] = pick_closest<THETA>(a, med, beta);
+        }
+    }
+    if (vec) {
+        __builtin_nontemporal_store(floatx2{res[0], res[VEC - 1]}, reinterpret_cast<floatx2 *>(out + c));
+    } else {
+        out[c] = res[0];
+        if (two) out[c + 1] = res[VEC - 1];
+    }
+}
+
+// The usual case for itself, beta = 1 (the default theta with n = 4f + 3), worth a kernel of its own
+// at large d: every round's set is the previous one minus its winner, so
+// set_t = set_{theta-1} + {winner_t .. winner_{theta-2}} and the averages are running sums over the
+// winners' values, walked from the last round back, on top of the rows of the last set (the
+// slots after the winners).  No per-round accumulators: fewer registers, more waves, about 10 %
+// (theta = 19) to 25 % (theta = 25) faster than the kernel above on the same input.  Does nothing
+// unless the plan says the sets are nested.
+constexpr int kBaseRegs = 16;   // rows of the last set loaded in one batch (the default theta leaves f <= 15)
+
+template <int THETA>
+__global__ __launch_bounds__(kThreads) void coord_alg1_nested_kernel(
     const float *__restrict__ G, int64_t d, int64_t ld, int beta, const int32_t *__restrict__ plan,
     float *__restrict__ out)
 {
-    if (!plan[kPlanRegular]) return;
-    constexpr int VEC = B1 ? 2 : 1;
-    const int64_t c = ((int64_t)blockIdx.x * kRegThreads + threadIdx.x) * VEC;
+    if (!plan[kPlanNested]) return;
+    constexpr int VEC = 2;
+    const int64_t c = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * VEC;
     if (c >= d) return;
-    const int nb = plan[kPlanNBase];
+    const int nb = plan[kPlanNSlots] - THETA;     // rows of the last set without its winner
     const float *inv_m = reinterpret_cast<const float *>(plan + kPlanInvM);
     const bool pairs_ok = VEC == 2 && ((uintptr_t)G % 8 == 0) && (ld % 2 == 0) && ((uintptr_t)out % 8 == 0);
     const bool two = VEC == 2 && c + 1 < d;
@@ -101,7 +270,7 @@ __global__ __launch_bounds__(kRegThreads) void coord_alg1_regular_kernel(
     float e[VEC][THETA];
 #pragma unroll
     for (int t = 0; t < THETA; ++t) {
-        load(plan[kPlanWinner + t]);
+        load(plan[kPlanRows + t]);
 #pragma unroll
         for (int k = 0; k < VEC; ++k) e[k][t] = x[k];
     }
@@ -115,7 +284,7 @@ __global__ __launch_bounds__(kRegThreads) void coord_alg1_regular_kernel(
 #pragma unroll
             for (int k = 0; k < VEC; ++k) xb[k][j] = 0.0f;
             if (j < nb) {                    // same for every lane
-                load(plan[kPlanBase + j]);
+                load(plan[kPlanRows + THETA + j]);
 #pragma unroll
                 for (int k = 0; k < VEC; ++k) xb[k][j] = x[k];
             }
@@ -132,7 +301,7 @@ __global__ __launch_bounds__(kRegThreads) void coord_alg1_regular_kernel(
 #pragma unroll
             for (int k = 0; k < VEC; ++k) xb[k][j] = 0.0f;
             if (s0 + j < nb) {
-                load(plan[kPlanBase + s0 + j]);
+                load(plan[kPlanRows + THETA + s0 + j]);
 #pragma unroll
                 for (int k = 0; k < VEC; ++k) xb[k][j] = x[k];
             }
@@ -145,38 +314,24 @@ __global__ __launch_bounds__(kRegThreads) void coord_alg1_regular_kernel(
     float res[VEC];
 #pragma unroll
     for (int k = 0; k < VEC; ++k) {
-        if constexpr (B1) {
-            float es[THETA];
+        float es[THETA];
 #pragma unroll
-            for (int t = 0; t < THETA; ++t) es[t] = e[k][t];
-            sort_registers<THETA>(es);
-            float med;
-            if constexpr (THETA & 1) med = es[THETA / 2];
-            else med = 0.5f * (es[THETA / 2 - 1] + es[THETA / 2]);
-            float best = 0.0f, bd = __builtin_huge_valf();
+        for (int t = 0; t < THETA; ++t) es[t] = e[k][t];
+        sort_registers<THETA>(es);
+        float med;
+        if constexpr (THETA & 1) med = es[THETA / 2];
+        else med = 0.5f * (es[THETA / 2 - 1] + es[THETA / 2]);
+        float best = 0.0f, bd = __builtin_huge_valf();
 #pragma unroll
-            for (int t = THETA - 1; t >= 0; --t) {
-                S[k] += e[k][t];
-                const float at = S[k] * inv_m[t];
-                const float dt = fabsf(at - med);
-                const bool take = dt < bd || (dt == bd && at < best);
-                best = take ? at : best;
-                bd = take ? dt : bd;
-            }
-            res[k] = best;
-        } else {
-            float a[THETA];
-#pragma unroll
-            for (int t = THETA - 1; t >= 0; --t) {
-                S[k] += e[k][t];
-                a[t] = S[k] * inv_m[t];
-            }
-            sort_registers<THETA>(e[k]);
-            float med;
-            if constexpr (THETA & 1) med = e[k][THETA / 2];
-            else med = 0.5f * (e[k][THETA / 2 - 1] + e[k][THETA / 2]);
-            res[k] = pick_closest<THETA>(a, med, beta);
+        for (int t = THETA - 1; t >= 0; --t) {
+            S[k] += e[k][t];
+            const float at = S[k] * inv_m[t];
+            const float dt = fabsf(at - med);
+            const bool take = dt < bd || (dt == bd && at < best);
+            best = take ? at : best;
+            bd = take ? dt : bd;
         }
+        res[k] = best;
     }
     if (vec) {
         __builtin_nontemporal_store(floatx2{res[0], res[VEC - 1]}, reinterpret_cast<floatx2 *>(out + c));
@@ -186,72 +341,25 @@ __global__ __launch_bounds__(kRegThreads) void coord_alg1_regular_kernel(
     }
 }
 
-// The general case (some round's set is not "the previous set minus its winner"); returns at once
-// when the plan says the regular kernel handles the call.  Every row that some round needs has a
-// slot (the winner of round t in slot t), a lane holds its coordinate of all of them in registers,
-// and the running sum over the current set follows the plan's signed membership changes:
-// S_t = S_{t-1} + sum_s delta[t][s] x[s].  Register arrays cannot be indexed at run time, so the
-// changes are applied as multiply-adds by -1, 0 or +1 from scalar registers, in groups of eight
-// slots that are skipped when nothing in them changes (after round 0 only a few rows move).
-template <int THETA>
-__global__ __launch_bounds__(kRegThreads) void coord_alg1_general_kernel(
-    const float *__restrict__ G, int64_t d, int64_t ld, int beta, const int32_t *__restrict__ plan,
-    float *__restrict__ out)
-{
-    if (plan[kPlanRegular]) return;
-    const int64_t c = (int64_t)blockIdx.x * kRegThreads + threadIdx.x;
-    if (c >= d) return;
-    if (plan[kPlanBad]) {
-        out[c] = __int_as_float(0x7fc00000);
-        return;
-    }
-    const int U = plan[kPlanNSlots];
-    const float *inv_m = reinterpret_cast<const float *>(plan + kPlanInvM);
-    const float *delta = reinterpret_cast<const float *>(plan + kPlanDelta);
-    float x[kMaxN];
-#pragma unroll
-    for (int s = 0; s < kMaxN; ++s) {
-        x[s] = 0.0f;
-        if (s < U) x[s] = __builtin_nontemporal_load(G + (int64_t)plan[kPlanRows + s] * ld + c);
-    }
-    float e[THETA], a[THETA];
-    float S = 0.0f;
-#pragma unroll
-    for (int t = 0; t < THETA; ++t) {
-        e[t] = x[t];
-        const int groups = plan[kPlanGroups + t];
-#pragma unroll
-        for (int g = 0; g < kMaxN / 8; ++g) {
-            if (groups & (1 << g)) {           // same for every lane
-#pragma unroll
-                for (int j = 0; j < 8; ++j) S = fmaf(delta[t * kMaxN + 8 * g + j], x[8 * g + j], S);
-            }
-        }
-        a[t] = S * inv_m[t];
-    }
-    sort_registers<THETA>(e);
-    float med;
-    if constexpr (THETA & 1) med = e[THETA / 2];
-    else med = 0.5f * (e[THETA / 2 - 1] + e[THETA / 2]);
-    out[c] = pick_closest<THETA>(a, med, beta);
-}
-
 template <int THETA>
 hipError_t launch_theta(const CoordAlg1Args &a, hipStream_t s)
 {
-    // which of the two kernels does the work is only known on the device (the plan): both are launched
     if (a.beta == 1) {
-        const int64_t blocks = (a.d + 2 * kRegThreads - 1) / (2 * kRegThreads);
-        coord_alg1_regular_kernel<THETA, true><<<dim3((unsigned)blocks), dim3(kRegThreads), 0, s>>>(
-            a.G, a.d, a.ld, a.beta, a.plan, a.out);
+        const int64_t blocks = (a.d + 2 * kThreads - 1) / (2 * kThreads);
+        // Large d: the nested-sets kernel as well; which of the two does the work is only known on
+        // the device (the plan), the other returns at once.  Below, the second launch would cost
+        // more than it saves.
+        const int both = a.d >= (int64_t)1 << 22;
+        if (both)
+            coord_alg1_nested_kernel<THETA><<<dim3((unsigned)blocks), dim3(kThreads), 0, s>>>(a.G, a.d, a.ld, a.beta,
+                                                                                             a.plan, a.out);
+        coord_alg1_kernel<THETA, true><<<dim3((unsigned)blocks), dim3(kThreads), 0, s>>>(a.G, a.d, a.ld, a.beta,
+                                                                                       a.plan, both, a.out);
     } else {
-        const int64_t blocks = (a.d + kRegThreads - 1) / kRegThreads;
-        coord_alg1_regular_kernel<THETA, false><<<dim3((unsigned)blocks), dim3(kRegThreads), 0, s>>>(
-            a.G, a.d, a.ld, a.beta, a.plan, a.out);
+        const int64_t blocks = (a.d + kThreads - 1) / kThreads;
+        coord_alg1_kernel<THETA, false><<<dim3((unsigned)blocks), dim3(kThreads), 0, s>>>(a.G, a.d, a.ld, a.beta,
+                                                                                        a.plan, 0, a.out);
     }
-    const int64_t gblocks = (a.d + kRegThreads - 1) / kRegThreads;
-    coord_alg1_general_kernel<THETA><<<dim3((unsigned)gblocks), dim3(kRegThreads), 0, s>>>(a.G, a.d, a.ld, a.beta,
-                                                                                          a.plan, a.out);
     return hipGetLastError();
 }
 

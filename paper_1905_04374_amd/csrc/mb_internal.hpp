@@ -90,19 +90,16 @@ struct CoordAlg1Args {
     int32_t *plan;           // kPlanWords words of scratch, written by launch_alg1_plan
 };
 // Plan of the Algorithm-1 coordinate pass (int32 words), written by launch_alg1_plan.
-//   regular: every round's averaged set is the previous one minus its winner.  Then: the winners'
-//     rows, the rows of the last set without its winner (nbase of them), 1 / |set_t| (float bits).
-//   otherwise: the rows any round needs get slots, the winner of round t in slot t, the others
-//     after them in ascending order (nslots in all); delta[t][s] in {-1, 0, +1} (float bits) is
-//     the change of slot s's membership from round t-1 to round t, groups[t] has bit g set when
-//     delta[t][8g .. 8g+7] is not all zero.  bad: an index out of range or repeated.
-constexpr int kPlanRegular = 0;
-constexpr int kPlanNBase = 1;
-constexpr int kPlanNSlots = 2;
-constexpr int kPlanBad = 3;
-constexpr int kPlanWinner = 4;
-constexpr int kPlanBase = kPlanWinner + kMaxN;
-constexpr int kPlanInvM = kPlanBase + kMaxN;
+// Every row that some round needs gets a slot: the winner of round t in slot t, the other rows
+// after them in ascending order (nslots in all).  delta[t][s] in {-1, 0, +1} (float bits) is the
+// change of slot s's membership from round t-1 to round t (round -1: the empty set), groups[t] has
+// bit g set when delta[t][8g .. 8g+7] is not all zero, inv_m[t] = 1 / |set_t| (float bits).
+// bad: an index out of range or repeated.  nested: every round's set is the previous one minus
+// its winner (then the slots after the winners are the last set without its winner).
+constexpr int kPlanNSlots = 0;
+constexpr int kPlanBad = 1;
+constexpr int kPlanNested = 2;
+constexpr int kPlanInvM = 3;
 constexpr int kPlanRows = kPlanInvM + kMaxN;
 constexpr int kPlanGroups = kPlanRows + kMaxN;
 constexpr int kPlanDelta = kPlanGroups + kMaxN;

@@ -76,92 +76,85 @@ __global__ __launch_bounds__(256) void masked_mean_kernel(const void *__restrict
         if (c0 + e < d) out[c0 + e] = acc[e] * inv;
 }
 
-// One wave, lane t = round t of multi-Krum (Algorithm 1).  Checks whether set_{t+1} = set_t minus
-// the winner of round t for every t and writes what the two coordinate kernels need.
-__global__ __launch_bounds__(64) void alg1_plan_kernel(int n, int theta, const int32_t *__restrict__ sel,
-                                                       const uint8_t *__restrict__ sets,
-                                                       int32_t *__restrict__ plan)
+// Plan of the Algorithm-1 coordinate pass (layout in mb_internal.hpp).  One workgroup; the
+// membership matrix and the winners are brought into LDS first, everything else works from there.
+constexpr int kPlanThreads = 256;
+
+__global__ __launch_bounds__(kPlanThreads) void alg1_plan_kernel(int n, int theta, const int32_t *__restrict__ sel,
+                                                                 const uint8_t *__restrict__ sets,
+                                                                 int32_t *__restrict__ plan)
 {
-    __shared__ int slot_of[kMaxN];     // row -> slot, -1: no round needs the row
+    __shared__ unsigned char member[kMaxN * kMaxN];   // member[t * kMaxN + r]
     __shared__ int winner[kMaxN];
-    __shared__ int nslots_s;
-    const int t = threadIdx.x;
-    bool ok = true, bad = false;
-    if (t < kMaxN) slot_of[t] = -1;
+    __shared__ int slot_of[kMaxN];                    // row -> slot, -1: no round needs the row
+    __shared__ int rows[kMaxN];                       // slot -> row
+    __shared__ int nslots;
+    __shared__ int bad;
+    __shared__ int not_nested;
+    __shared__ unsigned groups[kMaxN];
+    const int tid = threadIdx.x;
+    if (tid == 0) { bad = 0; not_nested = 0; }
+    if (tid < kMaxN) { slot_of[tid] = -1; groups[tid] = 0; }
+    for (int e = tid; e < theta * n; e += kPlanThreads) member[(e / n) * kMaxN + (e % n)] = sets[e] ? 1 : 0;
     __syncthreads();
-    if (t < theta) {
-        const int w = sel[t];
+    if (tid < theta) {
+        const int w = sel[tid];
         const bool valid = (unsigned)w < (unsigned)n;
-        bad = !valid;
-        winner[t] = valid ? w : 0;
-        ok = valid && sets[t * n + (valid ? w : 0)] != 0;
+        winner[tid] = valid ? w : 0;
+        if (!valid) bad = 1;
         int m = 0;
+        bool ok = valid && member[tid * kMaxN + (valid ? w : 0)] != 0;
         for (int r = 0; r < n; ++r) {
-            const int cur = sets[t * n + r] ? 1 : 0;
+            const int cur = member[tid * kMaxN + r];
             m += cur;
-            if (t + 1 < theta) {
-                const int nxt = sets[(t + 1) * n + r] ? 1 : 0;
-                ok = ok && (nxt == ((r == w) ? 0 : cur));
-            }
+            if (tid + 1 < theta) ok = ok && (member[(tid + 1) * kMaxN + r] == ((r == w) ? 0 : cur));
         }
-        plan[kPlanWinner + t] = valid ? w : 0;
-        plan[kPlanInvM + t] = __float_as_int(m > 0 ? 1.0f / (float)m : 0.0f);
+        if (!ok) not_nested = 1;
+        plan[kPlanInvM + tid] = __float_as_int(m > 0 ? 1.0f / (float)m : 0.0f);
     }
     __syncthreads();
-    if (t < theta) {                   // a winner that an earlier round already extracted
-        for (int u = 0; u < t; ++u) bad = bad || (winner[u] == winner[t]);
-    }
-    const bool any_bad = __ballot(bad) != 0ull;
-    const bool regular = __ballot(!ok) == 0ull && !any_bad;
-    if (t == 0) {
-        int nb = 0;
-        const int last = winner[theta - 1];
-        for (int r = 0; r < n; ++r)
-            if (sets[(theta - 1) * n + r] && r != last) plan[kPlanBase + nb++] = r;
-        plan[kPlanNBase] = nb;
-        plan[kPlanRegular] = regular ? 1 : 0;
-        plan[kPlanBad] = any_bad ? 1 : 0;
-        // slots: winners first (slot t = round t), then the other rows some set contains
+    if (tid < theta)                   // a winner that an earlier round already extracted
+        for (int u = 0; u < tid; ++u)
+            if (winner[u] == winner[tid]) bad = 1;
+    __syncthreads();
+    if (tid == 0) {
         int ns = 0;
-        for (int u = 0; u < theta; ++u) {
+        for (int u = 0; u < theta; ++u) {          // winners first: slot t = round t
             if (slot_of[winner[u]] < 0) slot_of[winner[u]] = ns;
-            plan[kPlanRows + ns] = winner[u];
-            ++ns;
+            rows[ns++] = winner[u];
         }
-        if (!any_bad) {                // (with repeated winners the slots could run past kMaxN)
+        if (!bad) {                                // (with repeated winners the slots could run past kMaxN)
             for (int r = 0; r < n; ++r) {
                 if (slot_of[r] >= 0) continue;
                 bool used = false;
-                for (int u = 0; u < theta; ++u) used = used || sets[u * n + r] != 0;
+                for (int u = 0; u < theta; ++u) used = used || member[u * kMaxN + r] != 0;
                 if (used) {
                     slot_of[r] = ns;
-                    plan[kPlanRows + ns] = r;
-                    ++ns;
+                    rows[ns++] = r;
                 }
             }
         }
-        nslots_s = ns;
+        nslots = ns;
         plan[kPlanNSlots] = ns;
+        plan[kPlanBad] = bad;
+        plan[kPlanNested] = (!bad && !not_nested) ? 1 : 0;
     }
     __syncthreads();
-    if (t < theta) {
-        const int ns = nslots_s;
-        unsigned groups = 0;
-        for (int s = 0; s < kMaxN; ++s) plan[kPlanDelta + t * kMaxN + s] = 0;   // 0.0f
-        if (!any_bad) {
-            for (int r = 0; r < n; ++r) {
-                const int s = slot_of[r];
-                if (s < 0 || s >= ns) continue;
-                const int cur = sets[t * n + r] ? 1 : 0;
-                const int prev = (t > 0 && sets[(t - 1) * n + r]) ? 1 : 0;
-                if (cur != prev) {
-                    plan[kPlanDelta + t * kMaxN + s] = __float_as_int(cur ? 1.0f : -1.0f);
-                    groups |= 1u << (s >> 3);
-                }
-            }
+    const int ns = nslots;
+    if (tid < kMaxN) plan[kPlanRows + tid] = tid < ns ? rows[tid] : 0;
+    for (int e = tid; e < kMaxN * kMaxN; e += kPlanThreads) {
+        const int t = e / kMaxN, s = e % kMaxN;
+        float dl = 0.0f;
+        if (!bad && t < theta && s < ns && slot_of[rows[s]] == s) {   // a row counts in its first slot only
+            const int cur = member[t * kMaxN + rows[s]];
+            const int prev = t > 0 ? member[(t - 1) * kMaxN + rows[s]] : 0;
+            dl = (float)(cur - prev);
         }
-        plan[kPlanGroups + t] = (int)groups;
+        plan[kPlanDelta + e] = __float_as_int(dl);
+        if (dl != 0.0f) atomicOr(&groups[t], 1u << (s >> 3));
     }
+    __syncthreads();
+    if (tid < kMaxN) plan[kPlanGroups + tid] = (int)groups[tid];
 }
 
 }  // namespace
@@ -169,7 +162,7 @@ __global__ __launch_bounds__(64) void alg1_plan_kernel(int n, int theta, const i
 hipError_t launch_alg1_plan(int n, int theta, const int32_t *sel, const uint8_t *sets, int32_t *plan,
                             hipStream_t s)
 {
-    alg1_plan_kernel<<<dim3(1), dim3(64), 0, s>>>(n, theta, sel, sets, plan);
+    alg1_plan_kernel<<<dim3(1), dim3(kPlanThreads), 0, s>>>(n, theta, sel, sets, plan);
     return hipGetLastError();
 }
 
