@@ -92,6 +92,7 @@ __global__ __launch_bounds__(kPlanThreads) void alg1_plan_kernel(int n, int thet
     __shared__ int bad;
     __shared__ int not_nested;
     __shared__ unsigned groups[kMaxN];
+    __shared__ unsigned char used[kMaxN];             // some round's set holds the row
     const int tid = threadIdx.x;
     if (tid == 0) { bad = 0; not_nested = 0; }
     if (tid < kMaxN) { slot_of[tid] = -1; groups[tid] = 0; }
@@ -116,6 +117,12 @@ __global__ __launch_bounds__(kPlanThreads) void alg1_plan_kernel(int n, int thet
     if (tid < theta)                   // a winner that an earlier round already extracted
         for (int u = 0; u < tid; ++u)
             if (winner[u] == winner[tid]) bad = 1;
+    if (tid >= 64 && tid < 64 + n) {   // (another wave than the one above)
+        const int r = tid - 64;
+        int any = 0;
+        for (int u = 0; u < theta; ++u) any |= member[u * kMaxN + r];
+        used[r] = (unsigned char)any;
+    }
     __syncthreads();
     if (tid == 0) {
         int ns = 0;
@@ -125,10 +132,7 @@ __global__ __launch_bounds__(kPlanThreads) void alg1_plan_kernel(int n, int thet
         }
         if (!bad) {                                // (with repeated winners the slots could run past kMaxN)
             for (int r = 0; r < n; ++r) {
-                if (slot_of[r] >= 0) continue;
-                bool used = false;
-                for (int u = 0; u < theta; ++u) used = used || member[u * kMaxN + r] != 0;
-                if (used) {
+                if (slot_of[r] < 0 && used[r]) {
                     slot_of[r] = ns;
                     rows[ns++] = r;
                 }
