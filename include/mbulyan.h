@@ -203,25 +203,26 @@ int coordwise_trimmed_avg(const float *grads, int n, int64_t d, int64_t ld,
  * and out stay fp64 / fp32.  The fast paths need rows that start on 16-byte
  * boundaries (distance pass: grads % 16 == 0 and ld % 8 == 0) and 4-byte
  * boundaries (coordinate pass: grads % 4 == 0, ld % 2 == 0, out % 8 == 0);
- * anything else takes element loads.  MB_MODE_SELECTED only.
- *   pairwise_sqdist_bf16        as pairwise_sqdist (Gram form; there is one
- *                               exact product per pair and coordinate)
- *   coordwise_trimmed_avg_bf16  as coordwise_trimmed_avg with agr_sets == NULL
- *   mbulyan_aggregate_bf16      as mbulyan_aggregate_ex in MB_MODE_SELECTED
- *   mbulyan_aggregate_chunked_bf16  as mbulyan_aggregate_chunked in
- *                               MB_MODE_SELECTED
- *   multikrum_aggregate_bf16    as multikrum_aggregate
- *   coordwise_median_bf16       as coordwise_median
+ * anything else takes element loads.  Arguments as for the fp32 entry point
+ * of the same name:
+ *   pairwise_sqdist_bf16            pairwise_sqdist (Gram form; there is one
+ *                                   exact product per pair and coordinate)
+ *   coordwise_trimmed_avg_bf16      coordwise_trimmed_avg
+ *   mbulyan_aggregate_bf16          mbulyan_aggregate_ex
+ *   mbulyan_aggregate_chunked_bf16  mbulyan_aggregate_chunked
+ *   multikrum_aggregate_bf16        multikrum_aggregate
+ *   coordwise_median_bf16           coordwise_median
  */
 int pairwise_sqdist_bf16(const uint16_t *grads, int n, int64_t d, int64_t ld,
                          double *dist, int accumulate, void *workspace,
                          size_t ws_bytes, void *stream);
 int coordwise_trimmed_avg_bf16(const uint16_t *grads, int n, int64_t d,
                                int64_t ld, const int32_t *selected_idx,
-                               int theta, int beta, float *out, void *stream);
+                               int theta, int beta, const uint8_t *agr_sets,
+                               float *out, void *stream);
 int mbulyan_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d,
-                           int64_t ld, int theta, int beta, float *out,
-                           int32_t *selected_idx, void *workspace,
+                           int64_t ld, int mode, int theta, int beta,
+                           float *out, int32_t *selected_idx, void *workspace,
                            size_t ws_bytes, void *stream);
 int multikrum_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d,
                              int64_t ld, float *out, uint8_t *selected_mask,
@@ -231,7 +232,8 @@ int coordwise_median_bf16(const uint16_t *grads, int n, int64_t d, int64_t ld,
 int mbulyan_aggregate_chunked_bf16(const uint16_t *const *chunks, int nchunks,
                                    const int64_t *chunk_d,
                                    const int64_t *chunk_ld, int n, int f,
-                                   float *const *outs, int32_t *selected_idx,
+                                   int mode, float *const *outs,
+                                   int32_t *selected_idx,
                                    void *workspace, size_t ws_bytes,
                                    void *stream);
 

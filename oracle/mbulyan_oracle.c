@@ -296,10 +296,11 @@ void orc_coordwise_selected(const float *G, int64_t d, int64_t ld,
  * scale (may be NULL): the largest, over the rounds, of the mean absolute value
  * of the gradients averaged into G^agr[t][c]: the conditioning scale of an
  * fp32 evaluation of those averages.
- * margin (may be NULL): gap, in fp32, between the beta-th and the (beta+1)-th
- * smallest |G^agr - M|; alt (may be NULL): the output if the (beta+1)-th
- * replaced the beta-th.  A comparison may accept alt where margin is below
- * the rounding noise of an fp32 evaluation of G^agr.
+ * margin (may be NULL): gap, in fp32, between the beta-th smallest |G^agr - M|
+ * and the smallest one among the values not chosen that differ from the
+ * beta-th value; alt (may be NULL): the output if that value replaced the
+ * beta-th.  A comparison may accept alt where margin is below the rounding
+ * noise of an fp32 evaluation of G^agr.
  */
 void orc_coordwise_alg1(const float *G, int n, int64_t d, int64_t ld,
                         const int32_t *ext, const uint8_t *agr_sets,
@@ -333,16 +334,18 @@ void orc_coordwise_alg1(const float *G, int n, int64_t d, int64_t ld,
         out[c] = (float)(s / (double)beta);
         if (scale) scale[c] = (float)cond;
         if (margin || alt) {
-            /* worst picked and best not-picked, by (delta, position) */
+            /* worst picked, by (delta, position), and the best not-picked value that differs
+             * from it: swapping in an equal value would be no alternative at all (averages of
+             * few-bit inputs repeat, and three-way ties do occur) */
             int worst = -1, next = -1;
             for (int p = 0; p < theta; ++p) {
                 volatile float df = a[p] - med;
                 delta[p] = fabsf(df);
             }
-            for (int p = 0; p < theta; ++p) {
-                if (picked[p]) { if (worst < 0 || delta[p] >= delta[worst]) worst = p; }
-                else           { if (next < 0 || delta[p] < delta[next]) next = p; }
-            }
+            for (int p = 0; p < theta; ++p)
+                if (picked[p] && (worst < 0 || delta[p] >= delta[worst])) worst = p;
+            for (int p = 0; p < theta; ++p)
+                if (!picked[p] && a[p] != a[worst] && (next < 0 || delta[p] < delta[next])) next = p;
             if (next < 0) {
                 if (margin) margin[c] = INFINITY;
                 if (alt) alt[c] = out[c];

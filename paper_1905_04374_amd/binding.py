@@ -62,9 +62,9 @@ def _load() -> C.CDLL:
     lib.multikrum_aggregate.argtypes = [vp, ci, ci, i64, i64, vp, vp, vp, sz, vp]
     lib.coordwise_median.argtypes = [vp, ci, i64, i64, vp, vp]
     lib.pairwise_sqdist_bf16.argtypes = [vp, ci, i64, i64, vp, ci, vp, sz, vp]
-    lib.coordwise_trimmed_avg_bf16.argtypes = [vp, ci, i64, i64, vp, ci, ci, vp, vp]
-    lib.mbulyan_aggregate_bf16.argtypes = [vp, ci, ci, i64, i64, ci, ci, vp, vp, vp, sz, vp]
-    lib.mbulyan_aggregate_chunked_bf16.argtypes = [C.POINTER(vp), ci, C.POINTER(i64), C.POINTER(i64), ci, ci,
+    lib.coordwise_trimmed_avg_bf16.argtypes = [vp, ci, i64, i64, vp, ci, ci, vp, vp, vp]
+    lib.mbulyan_aggregate_bf16.argtypes = [vp, ci, ci, i64, i64, ci, ci, ci, vp, vp, vp, sz, vp]
+    lib.mbulyan_aggregate_chunked_bf16.argtypes = [C.POINTER(vp), ci, C.POINTER(i64), C.POINTER(i64), ci, ci, ci,
                                                    C.POINTER(vp), vp, vp, sz, vp]
     lib.multikrum_aggregate_bf16.argtypes = [vp, ci, ci, i64, i64, vp, vp, vp, sz, vp]
     lib.coordwise_median_bf16.argtypes = [vp, ci, i64, i64, vp, vp]
@@ -156,7 +156,7 @@ def mbulyan_aggregate(grads, f, out=None, selected_idx=None, stream=None):
 
 def mbulyan_aggregate_ex(grads, f, mode=MODE_SELECTED, theta=0, beta=0, out=None, selected_idx=None,
                          workspace=None, stream=None):
-    """grads may be bfloat16 (MODE_SELECTED only): the bf16 entry point runs, out stays float32."""
+    """grads may be bfloat16: the bf16 entry point runs, out stays float32."""
     p, n, d, ld = _matrix(grads, bf16_ok=True)
     th_def, _ = mbulyan_params(n, f, mode)
     th = theta or th_def
@@ -166,9 +166,7 @@ def mbulyan_aggregate_ex(grads, f, mode=MODE_SELECTED, theta=0, beta=0, out=None
         selected_idx = torch.empty(th, device=grads.device, dtype=torch.int32)
     wp, wb = _ws(workspace)
     if grads.dtype == torch.bfloat16:
-        if mode != MODE_SELECTED:
-            raise ValueError("bfloat16 gradients: MODE_SELECTED only")
-        _check(lib.mbulyan_aggregate_bf16(p, n, f, d, ld, theta, beta, _dev(out, torch.float32, "out"),
+        _check(lib.mbulyan_aggregate_bf16(p, n, f, d, ld, mode, theta, beta, _dev(out, torch.float32, "out"),
                                           _dev(selected_idx, torch.int32, "selected_idx"), wp, wb,
                                           _stream(stream)))
         return out, selected_idx
@@ -180,14 +178,12 @@ def mbulyan_aggregate_ex(grads, f, mode=MODE_SELECTED, theta=0, beta=0, out=None
 def mbulyan_aggregate_chunked(chunks, f, mode=MODE_SELECTED, outs=None, selected_idx=None, workspace=None,
                               stream=None):
     """chunks: list of (n, d_c) float32 CUDA tensors, the column chunks of one matrix (all bfloat16
-    instead: the bf16 entry point, MODE_SELECTED only)."""
+    instead: the bf16 entry point)."""
     k = len(chunks)
     mats = [_matrix(c, bf16_ok=True) for c in chunks]
     in16 = chunks[0].dtype == torch.bfloat16
     if any(c.dtype != chunks[0].dtype for c in chunks):
         raise TypeError("all chunks must have the same dtype")
-    if in16 and mode != MODE_SELECTED:
-        raise ValueError("bfloat16 gradients: MODE_SELECTED only")
     n = mats[0][1]
     if any(m[1] != n for m in mats):
         raise ValueError("all chunks must have the same number of rows")
@@ -202,7 +198,7 @@ def mbulyan_aggregate_chunked(chunks, f, mode=MODE_SELECTED, outs=None, selected
     op = (C.c_void_p * k)(*[_dev(o, torch.float32, "out") for o in outs])
     wp, wb = _ws(workspace)
     if in16:
-        _check(lib.mbulyan_aggregate_chunked_bf16(cp, k, cd, cl, n, f, op,
+        _check(lib.mbulyan_aggregate_chunked_bf16(cp, k, cd, cl, n, f, mode, op,
                                                   _dev(selected_idx, torch.int32, "selected_idx"), wp, wb,
                                                   _stream(stream)))
         return outs, selected_idx
@@ -250,16 +246,14 @@ def multikrum_select(dist, f, theta, want_sets=True, stream=None):
 
 
 def coordwise_trimmed_avg(grads, selected_idx, beta, agr_sets=None, out=None, stream=None):
-    """grads may be bfloat16 when agr_sets is None."""
+    """grads may be bfloat16."""
     p, n, d, ld = _matrix(grads, bf16_ok=True)
     if out is None:
         out = torch.empty(d, device=grads.device, dtype=torch.float32)
     if grads.dtype == torch.bfloat16:
-        if agr_sets is not None:
-            raise ValueError("bfloat16 gradients: agr_sets must be None")
         _check(lib.coordwise_trimmed_avg_bf16(p, n, d, ld, _dev(selected_idx, torch.int32, "selected_idx"),
-                                              selected_idx.numel(), beta, _dev(out, torch.float32, "out"),
-                                              _stream(stream)))
+                                              selected_idx.numel(), beta, _dev(agr_sets, torch.uint8, "agr_sets"),
+                                              _dev(out, torch.float32, "out"), _stream(stream)))
         return out
     _check(lib.coordwise_trimmed_avg(p, n, d, ld, _dev(selected_idx, torch.int32, "selected_idx"),
                                      selected_idx.numel(), beta, _dev(agr_sets, torch.uint8, "agr_sets"),

@@ -51,6 +51,7 @@ def units():
         u.append((f"coordwise16_g{g}.o", "coordwise.hip", NO_NANS + [f"-DMB_GROUP={g}", "-DMB_IN16=1"]))
     for g in range(8):
         u.append((f"coordwise_alg1_g{g}.o", "coordwise_alg1.hip", NO_NANS + [f"-DMB_GROUP={g}"]))
+        u.append((f"coordwise_alg1_16_g{g}.o", "coordwise_alg1.hip", NO_NANS + [f"-DMB_GROUP={g}", "-DMB_IN16=1"]))
     return u
 
 

@@ -228,8 +228,7 @@ int run_coord(const void *grads, int in16, int n, int64_t d, int64_t ld, int mod
         mb::CoordArgs a{grads, n, d, ld, sel, theta, beta, 0, out, in16};
         MB_HIP(mb::launch_coord_selected(a, s));
     } else {
-        if (in16) return MB_EUNSUPPORTED;
-        mb::CoordAlg1Args a{static_cast<const float *>(grads), n, d, ld, sel, sets, theta, beta, out, plan};
+        mb::CoordAlg1Args a{grads, n, d, ld, sel, sets, theta, beta, out, plan, in16};
         MB_HIP(mb::launch_alg1_plan(n, theta, sel, sets, plan, s));
         MB_HIP(mb::launch_coord_alg1(a, s));
     }
@@ -279,6 +278,18 @@ hipError_t launch_coord_selected(const CoordArgs &a, hipStream_t s)
 hipError_t launch_coord_alg1(const CoordAlg1Args &a, hipStream_t s)
 {
     if (a.theta < 1 || a.theta > kMaxN) return hipErrorInvalidValue;
+    if (a.in16) {
+        switch ((a.theta - 1) / 8) {
+            case 0: return launch_coord_alg1_16_group0(a, s);
+            case 1: return launch_coord_alg1_16_group1(a, s);
+            case 2: return launch_coord_alg1_16_group2(a, s);
+            case 3: return launch_coord_alg1_16_group3(a, s);
+            case 4: return launch_coord_alg1_16_group4(a, s);
+            case 5: return launch_coord_alg1_16_group5(a, s);
+            case 6: return launch_coord_alg1_16_group6(a, s);
+            default: return launch_coord_alg1_16_group7(a, s);
+        }
+    }
     switch ((a.theta - 1) / 8) {
         case 0: return launch_coord_alg1_group0(a, s);
         case 1: return launch_coord_alg1_group1(a, s);
@@ -389,7 +400,6 @@ static int aggregate_chunked(const void *const *chunks, int in16, int nchunks, c
                              const int64_t *chunk_ld, int n, int f, int mode, float *const *outs,
                              int32_t *selected_idx, void *workspace, size_t ws_bytes, void *stream)
 {
-    if (in16 && mode != MB_MODE_SELECTED) return MB_EUNSUPPORTED;
     if (!chunks || !chunk_d || !chunk_ld || !outs || nchunks < 1) return MB_EINVAL;
     int theta = 0, beta = 0;
     int rc = resolve_params(n, f, mode, &theta, &beta);
@@ -436,11 +446,11 @@ int mbulyan_aggregate_chunked(const float *const *chunks, int nchunks, const int
 }
 
 int mbulyan_aggregate_chunked_bf16(const uint16_t *const *chunks, int nchunks, const int64_t *chunk_d,
-                                   const int64_t *chunk_ld, int n, int f, float *const *outs,
+                                   const int64_t *chunk_ld, int n, int f, int mode, float *const *outs,
                                    int32_t *selected_idx, void *workspace, size_t ws_bytes, void *stream)
 {
     return aggregate_chunked(reinterpret_cast<const void *const *>(chunks), 1, nchunks, chunk_d, chunk_ld, n, f,
-                             MB_MODE_SELECTED, outs, selected_idx, workspace, ws_bytes, stream);
+                             mode, outs, selected_idx, workspace, ws_bytes, stream);
 }
 
 int mbulyan_aggregate_ex(const float *grads, int n, int f, int64_t d, int64_t ld, int mode, int theta,
@@ -537,13 +547,18 @@ int pairwise_sqdist_bf16(const uint16_t *grads, int n, int64_t d, int64_t ld, do
 }
 
 int coordwise_trimmed_avg_bf16(const uint16_t *grads, int n, int64_t d, int64_t ld, const int32_t *selected_idx,
-                               int theta, int beta, float *out, void *stream)
+                               int theta, int beta, const uint8_t *agr_sets, float *out, void *stream)
 {
     const int rc = check_matrix(grads, n, d, ld);
     if (rc != MB_OK) return rc;
     if (!selected_idx || !out || theta < 1 || theta > n || beta < 1 || beta > theta) return MB_EINVAL;
-    return run_coord(grads, 1, n, d, ld, MB_MODE_SELECTED, theta, beta, selected_idx, nullptr, nullptr, out,
-                     (hipStream_t)stream);
+    Workspace ws{nullptr};
+    if (agr_sets) {   // the Algorithm-1 pass keeps its plan in the library's own workspace
+        const int wrc = own_workspace(kOffPartials, &ws);
+        if (wrc != MB_OK) return wrc;
+    }
+    return run_coord(grads, 1, n, d, ld, agr_sets ? MB_MODE_ALG1 : MB_MODE_SELECTED, theta, beta, selected_idx,
+                     agr_sets, agr_sets ? ws.plan() : nullptr, out, (hipStream_t)stream);
 }
 
 int multikrum_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d, int64_t ld, float *out,
@@ -587,14 +602,16 @@ int coordwise_median_bf16(const uint16_t *grads, int n, int64_t d, int64_t ld, f
     return MB_OK;
 }
 
-int mbulyan_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d, int64_t ld, int theta, int beta,
-                           float *out, int32_t *selected_idx, void *workspace, size_t ws_bytes, void *stream)
+int mbulyan_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d, int64_t ld, int mode, int theta,
+                           int beta, float *out, int32_t *selected_idx, void *workspace, size_t ws_bytes,
+                           void *stream)
 {
     int rc = check_matrix(grads, n, d, ld);
     if (rc != MB_OK) return rc;
     if (!out || f < 0 || theta < 0 || beta < 0) return MB_EINVAL;
+    if (mode != MB_MODE_SELECTED && mode != MB_MODE_ALG1) return MB_EINVAL;
     if (n < 4 * f + 3) return MB_EPRECOND;
-    rc = resolve_params(n, f, MB_MODE_SELECTED, &theta, &beta);
+    rc = resolve_params(n, f, mode, &theta, &beta);
     if (rc != MB_OK) return rc;
     Workspace ws;
     rc = get_workspace(workspace, ws_bytes, n, d, &ws);
@@ -606,12 +623,13 @@ int mbulyan_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d, int64
     if (rc != MB_OK) return rc;
     {
         StageTimer t(MB_STAGE_SELECT, s);
+        uint8_t *sets = mode == MB_MODE_ALG1 ? ws.sets() : nullptr;
         if (deferred)
-            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, theta, ws.sel(), nullptr, ws.m(), s));
+            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, theta, ws.sel(), sets, ws.m(), s));
         else
-            MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, ws.sel(), nullptr, ws.m(), nullptr, s));
+            MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, ws.sel(), sets, ws.m(), nullptr, s));
     }
-    rc = run_coord(grads, 1, n, d, ld, MB_MODE_SELECTED, theta, beta, ws.sel(), nullptr, nullptr, out, s);
+    rc = run_coord(grads, 1, n, d, ld, mode, theta, beta, ws.sel(), ws.sets(), ws.plan(), out, s);
     if (rc != MB_OK) return rc;
     if (selected_idx)
         MB_HIP(hipMemcpyAsync(selected_idx, ws.sel(), sizeof(int32_t) * theta, hipMemcpyDeviceToDevice, s));

@@ -11,7 +11,8 @@
 // kernel (rowops.hip) prepares the row list and the updates; the kernel here
 // reads its plan with scalar loads and keeps everything else in registers.
 //
-// Compiled once per group of 8 values of theta (-DMB_GROUP=0..7).
+// Compiled once per group of 8 values of theta (-DMB_GROUP=0..7), and a second time with
+// -DMB_IN16=1 for gradients stored as bf16.
 #include <hip/hip_runtime.h>
 
 #include "mb_internal.hpp"
@@ -27,6 +28,38 @@ namespace mb {
 namespace {
 
 typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+#ifndef MB_IN16
+#define MB_IN16 0   // 1: this unit holds the kernels for gradients stored as bf16 (raw 16-bit words)
+#endif
+constexpr bool kIn16 = MB_IN16 != 0;
+typedef typename std::conditional<kIn16, unsigned short, float>::type Elem;
+
+// x[0], x[1] = the lane's one or two coordinates of a row, widened to fp32.  `pair`: one load of
+// both (8 bytes of fp32, 4 bytes of bf16; the address is aligned for it), `two`: there is a second
+// coordinate at all.
+__device__ __forceinline__ void load_coords(const Elem *p, bool pair, bool two, float (&x)[2])
+{
+    if constexpr (kIn16) {
+        if (pair) {
+            const unsigned w = __builtin_nontemporal_load(reinterpret_cast<const unsigned *>(p));
+            x[0] = __uint_as_float(w << 16);
+            x[1] = __uint_as_float(w & 0xffff0000u);
+        } else {
+            x[0] = __uint_as_float((unsigned)__builtin_nontemporal_load(p) << 16);
+            x[1] = two ? __uint_as_float((unsigned)__builtin_nontemporal_load(p + 1) << 16) : x[0];
+        }
+    } else {
+        if (pair) {
+            const floatx2 v = __builtin_nontemporal_load(reinterpret_cast<const floatx2 *>(p));
+            x[0] = v[0];
+            x[1] = v[1];
+        } else {
+            x[0] = __builtin_nontemporal_load(p);
+            x[1] = two ? __builtin_nontemporal_load(p + 1) : x[0];
+        }
+    }
+}
 
 // average of the beta values a[.] closest to med (closeness |a - med| in fp32, ties to the smaller value)
 template <int THETA>
@@ -100,7 +133,7 @@ __device__ __forceinline__ void more_slots(int U, Y &y, Load &load, X &x, Apply 
 }
 
 template <int THETA, bool B1>
-__global__ __launch_bounds__(kThreads) void coord_alg1_kernel(const float *__restrict__ G, int64_t d, int64_t ld,
+__global__ __launch_bounds__(kThreads) void coord_alg1_kernel(const Elem *__restrict__ G, int64_t d, int64_t ld,
                                                               int beta, const int32_t *__restrict__ plan,
                                                               int unless_nested, float *__restrict__ out)
 {
@@ -117,7 +150,7 @@ __global__ __launch_bounds__(kThreads) void coord_alg1_kernel(const float *__res
     const int U = plan[kPlanNSlots];
     const float *inv_m = reinterpret_cast<const float *>(plan + kPlanInvM);
     const float *delta = reinterpret_cast<const float *>(plan + kPlanDelta);
-    const bool pairs_ok = VEC == 2 && ((uintptr_t)G % 8 == 0) && (ld % 2 == 0) && ((uintptr_t)out % 8 == 0);
+    const bool pairs_ok = VEC == 2 && ((uintptr_t)G % (2 * sizeof(Elem)) == 0) && (ld % 2 == 0) && ((uintptr_t)out % 8 == 0);
     const bool vec = pairs_ok && two;
 
     float e[VEC][THETA], P[VEC][THETA];
@@ -126,17 +159,7 @@ __global__ __launch_bounds__(kThreads) void coord_alg1_kernel(const float *__res
 #pragma unroll
         for (int k = 0; k < VEC; ++k) P[k][t] = 0.0f;
     float x[2];
-    auto load = [&](int slot) {
-        const float *p = G + (int64_t)plan[kPlanRows + slot] * ld + c;
-        if (vec) {
-            const floatx2 v = __builtin_nontemporal_load(reinterpret_cast<const floatx2 *>(p));
-            x[0] = v[0];
-            x[1] = v[1];
-        } else {
-            x[0] = __builtin_nontemporal_load(p);
-            x[1] = (VEC == 2 && two) ? __builtin_nontemporal_load(p + 1) : x[0];
-        }
-    };
+    auto load = [&](int slot) { load_coords(G + (int64_t)plan[kPlanRows + slot] * ld + c, vec, two, x); };
     // P[t] += sum over the slots [lo, hi) of delta[t][s] * v[s - base], group by group
     auto apply = [&](auto lo_c, auto hi_c, auto base_c, const auto &v) {
         constexpr int LO = decltype(lo_c)::value, HI = decltype(hi_c)::value, BASE = decltype(base_c)::value;
@@ -243,7 +266,7 @@ constexpr int kBaseRegs = 16;   // rows of the last set loaded in one batch (the
 
 template <int THETA>
 __global__ __launch_bounds__(kThreads) void coord_alg1_nested_kernel(
-    const float *__restrict__ G, int64_t d, int64_t ld, int beta, const int32_t *__restrict__ plan,
+    const Elem *__restrict__ G, int64_t d, int64_t ld, int beta, const int32_t *__restrict__ plan,
     float *__restrict__ out)
 {
     if (!plan[kPlanNested]) return;
@@ -252,21 +275,11 @@ __global__ __launch_bounds__(kThreads) void coord_alg1_nested_kernel(
     if (c >= d) return;
     const int nb = plan[kPlanNSlots] - THETA;     // rows of the last set without its winner
     const float *inv_m = reinterpret_cast<const float *>(plan + kPlanInvM);
-    const bool pairs_ok = VEC == 2 && ((uintptr_t)G % 8 == 0) && (ld % 2 == 0) && ((uintptr_t)out % 8 == 0);
+    const bool pairs_ok = VEC == 2 && ((uintptr_t)G % (2 * sizeof(Elem)) == 0) && (ld % 2 == 0) && ((uintptr_t)out % 8 == 0);
     const bool two = VEC == 2 && c + 1 < d;
     const bool vec = pairs_ok && two;
     float x[2];
-    auto load = [&](int row) {
-        const float *p = G + (int64_t)row * ld + c;
-        if (vec) {
-            const floatx2 v = __builtin_nontemporal_load(reinterpret_cast<const floatx2 *>(p));
-            x[0] = v[0];
-            x[1] = v[1];
-        } else {
-            x[0] = __builtin_nontemporal_load(p);
-            x[1] = two ? __builtin_nontemporal_load(p + 1) : x[0];
-        }
-    };
+    auto load = [&](int row) { load_coords(G + (int64_t)row * ld + c, vec, two, x); };
     float e[VEC][THETA];
 #pragma unroll
     for (int t = 0; t < THETA; ++t) {
@@ -351,13 +364,13 @@ hipError_t launch_theta(const CoordAlg1Args &a, hipStream_t s)
         // more than it saves.
         const int both = a.d >= (int64_t)1 << 22;
         if (both)
-            coord_alg1_nested_kernel<THETA><<<dim3((unsigned)blocks), dim3(kThreads), 0, s>>>(a.G, a.d, a.ld, a.beta,
+            coord_alg1_nested_kernel<THETA><<<dim3((unsigned)blocks), dim3(kThreads), 0, s>>>(static_cast<const Elem *>(a.G), a.d, a.ld, a.beta,
                                                                                              a.plan, a.out);
-        coord_alg1_kernel<THETA, true><<<dim3((unsigned)blocks), dim3(kThreads), 0, s>>>(a.G, a.d, a.ld, a.beta,
+        coord_alg1_kernel<THETA, true><<<dim3((unsigned)blocks), dim3(kThreads), 0, s>>>(static_cast<const Elem *>(a.G), a.d, a.ld, a.beta,
                                                                                        a.plan, both, a.out);
     } else {
         const int64_t blocks = (a.d + kThreads - 1) / kThreads;
-        coord_alg1_kernel<THETA, false><<<dim3((unsigned)blocks), dim3(kThreads), 0, s>>>(a.G, a.d, a.ld, a.beta,
+        coord_alg1_kernel<THETA, false><<<dim3((unsigned)blocks), dim3(kThreads), 0, s>>>(static_cast<const Elem *>(a.G), a.d, a.ld, a.beta,
                                                                                         a.plan, 0, a.out);
     }
     return hipGetLastError();
@@ -370,7 +383,11 @@ hipError_t launch_theta(const CoordAlg1Args &a, hipStream_t s)
 #define MB_CASE(k) \
     case k: return launch_theta<8 * MB_GROUP + k>(a, s);
 
+#if MB_IN16
+hipError_t MB_CAT(launch_coord_alg1_16_group, MB_GROUP)(const CoordAlg1Args &a, hipStream_t s)
+#else
 hipError_t MB_CAT(launch_coord_alg1_group, MB_GROUP)(const CoordAlg1Args &a, hipStream_t s)
+#endif
 {
     switch (a.theta - 8 * MB_GROUP) {
         MB_CASE(1) MB_CASE(2) MB_CASE(3) MB_CASE(4) MB_CASE(5) MB_CASE(6) MB_CASE(7) MB_CASE(8)

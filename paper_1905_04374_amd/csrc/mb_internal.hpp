@@ -78,7 +78,7 @@ MB_DECL_GROUP(4) MB_DECL_GROUP(5) MB_DECL_GROUP(6) MB_DECL_GROUP(7)
 
 // Algorithm-1 mode: values are averages over row sets.
 struct CoordAlg1Args {
-    const float *G;
+    const void *G;           // fp32, or bf16 as raw 16-bit words when in16 is set
     int n;
     int64_t d;
     int64_t ld;
@@ -88,6 +88,7 @@ struct CoordAlg1Args {
     int beta;
     float *out;
     int32_t *plan;           // kPlanWords words of scratch, written by launch_alg1_plan
+    int in16;
 };
 // Plan of the Algorithm-1 coordinate pass (int32 words), written by launch_alg1_plan.
 // Every row that some round needs gets a slot: the winner of round t in slot t, the other rows
@@ -109,13 +110,21 @@ hipError_t launch_alg1_plan(int n, int theta, const int32_t *sel, const uint8_t 
 hipError_t launch_coord_alg1(const CoordAlg1Args &a, hipStream_t s);
 // one per translation unit, covering theta in [8g+1, 8g+8]
 hipError_t launch_coord_alg1_group0(const CoordAlg1Args &a, hipStream_t s);
+hipError_t launch_coord_alg1_16_group0(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_group1(const CoordAlg1Args &a, hipStream_t s);
+hipError_t launch_coord_alg1_16_group1(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_group2(const CoordAlg1Args &a, hipStream_t s);
+hipError_t launch_coord_alg1_16_group2(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_group3(const CoordAlg1Args &a, hipStream_t s);
+hipError_t launch_coord_alg1_16_group3(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_group4(const CoordAlg1Args &a, hipStream_t s);
+hipError_t launch_coord_alg1_16_group4(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_group5(const CoordAlg1Args &a, hipStream_t s);
+hipError_t launch_coord_alg1_16_group5(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_group6(const CoordAlg1Args &a, hipStream_t s);
+hipError_t launch_coord_alg1_16_group6(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_group7(const CoordAlg1Args &a, hipStream_t s);
+hipError_t launch_coord_alg1_16_group7(const CoordAlg1Args &a, hipStream_t s);
 
 // out[c] = mean over rows r with mask[r] of G[r][c]
 hipError_t launch_masked_mean(const float *G, int n, int64_t d, int64_t ld, const uint8_t *mask,

@@ -188,7 +188,49 @@ def test_coordwise_median_bf16():
             assert np.array_equal(got.cpu().numpy(), ref)
 
 
-def test_bf16_rejects_alg1_mode():
-    Gt = torch.zeros(11, 64, device=DEV, dtype=torch.bfloat16)
-    with pytest.raises(ValueError):
-        mb.mbulyan_aggregate_ex(Gt, 2, mode=mb.MODE_ALG1)
+def alg1_compare(got, ref, scale, margin, alt):
+    """Accept the reference, or, where the decision margin is below the rounding noise of an fp32
+    evaluation of the multi-Krum averages, the other candidate."""
+    got = got.cpu().numpy()
+    tol = 1e-5 * np.maximum(np.abs(ref), scale) + 1e-37
+    ok = np.abs(got - ref) <= tol
+    close_call = margin <= 4e-6 * scale
+    ok_alt = close_call & (np.abs(got - alt) <= 1e-5 * np.maximum(np.abs(alt), scale) + 1e-37)
+    assert np.all(ok | ok_alt), f"{np.sum(~(ok | ok_alt))} coordinates differ beyond an ambiguous choice"
+    return int(np.sum(~ok & ok_alt))
+
+
+@pytest.mark.parametrize("n,f,d", [(7, 1, 3000), (11, 2, 100_000), (13, 2, 5001), (19, 4, 30_000), (39, 9, 20_011),
+                                   (51, 12, 10_000), (64, 15, 4000)])
+def test_coordwise_alg1_bf16(n, f, d):
+    """Algorithm-1 form on bf16 gradients: sets from the oracle's selection on random data (the
+    general membership changes) against the oracle on the widened values.  With 8 significand bits
+    the averages tie often; the comparison allows the other candidate where the margin is tiny."""
+    say("coordwise_alg1 bf16", n, f, d)
+    rng = np.random.default_rng(n * 100 + f + 3)
+    Gt, G = to_bf16(rng.standard_normal((n, d)).astype(np.float32))
+    theta, beta = O.params(n, f, O.MODE_ALG1)
+    D = O.pairwise_sqdist(G)
+    ext, sets, m = O.multikrum_select(D, f, theta)
+    ref, scale, margin, alt = O.coordwise_alg1(G, ext, sets, beta, want_extra=True)
+    got = mb.coordwise_trimmed_avg(Gt, torch.as_tensor(ext).to(DEV), beta, agr_sets=torch.as_tensor(sets).to(DEV))
+    flips = alg1_compare(got, ref, scale, margin, alt)
+    assert flips <= max(4, d // 200)
+
+
+@pytest.mark.parametrize("cfg,d", [(1, None), (2, 400_000), (4, 100_004), (4, 5_000_001)])
+def test_aggregate_alg1_mode_bf16(cfg, d):
+    """Whole rule in Algorithm-1 mode on the workloads rounded to bf16 (nested sets: above 2^22
+    coordinates the kernel for that case runs, below it the general one)."""
+    say("aggregate alg1 bf16", cfg, d)
+    s = W.spec(cfg)
+    Gt = W.make(cfg, DEV, d=d).to(torch.bfloat16)
+    G = Gt.float().cpu().numpy()
+    theta, beta = O.params(s["n"], s["f"], O.MODE_ALG1)
+    D = O.pairwise_sqdist(G)
+    ext, sets, m = O.multikrum_select(D, s["f"], theta)
+    ref, scale, margin, alt = O.coordwise_alg1(G, ext, sets, beta, want_extra=True)
+    out, sel = mb.mbulyan_aggregate_ex(Gt, s["f"], mode=mb.MODE_ALG1)
+    assert sel.cpu().numpy().tolist() == ext.tolist()
+    flips = alg1_compare(out, ref, scale, margin, alt)
+    assert flips <= max(4, G.shape[1] // 200)

@@ -325,7 +325,7 @@ def test_aggregate_matches_oracle(cfg, d, placement, algo):
         assert torch.equal(out, out2) and torch.equal(sel, sel2)      # run-to-run bit-identical
 
 
-@pytest.mark.parametrize("cfg,d", [(1, None), (2, 400_000), (4, 100_003)])
+@pytest.mark.parametrize("cfg,d", [(1, None), (2, 400_000), (4, 100_003), (4, 4_500_000)])   # the last: above 2^22, the nested-sets kernel
 def test_aggregate_alg1_mode(cfg, d):
     say("aggregate alg1", cfg, d)
     s = W.spec(cfg)
