@@ -35,31 +35,47 @@ typedef float floatx2 __attribute__((ext_vector_type(2)));
 constexpr bool kIn16 = MB_IN16 != 0;
 typedef typename std::conditional<kIn16, unsigned short, float>::type Elem;
 
-// x[0], x[1] = the lane's one or two coordinates of a row, widened to fp32.  `pair`: one load of
-// both (8 bytes of fp32, 4 bytes of bf16; the address is aligned for it), `two`: there is a second
-// coordinate at all.
-__device__ __forceinline__ void load_coords(const Elem *p, bool pair, bool two, float (&x)[2])
-{
-    if constexpr (kIn16) {
-        if (pair) {
-            const unsigned w = __builtin_nontemporal_load(reinterpret_cast<const unsigned *>(p));
-            x[0] = __uint_as_float(w << 16);
-            x[1] = __uint_as_float(w & 0xffff0000u);
-        } else {
-            x[0] = __uint_as_float((unsigned)__builtin_nontemporal_load(p) << 16);
-            x[1] = two ? __uint_as_float((unsigned)__builtin_nontemporal_load(p + 1) << 16) : x[0];
-        }
-    } else {
-        if (pair) {
-            const floatx2 v = __builtin_nontemporal_load(reinterpret_cast<const floatx2 *>(p));
-            x[0] = v[0];
-            x[1] = v[1];
-        } else {
-            x[0] = __builtin_nontemporal_load(p);
-            x[1] = two ? __builtin_nontemporal_load(p + 1) : x[0];
-        }
+// The lane's one or two coordinates of a row as they come from memory (two floats, or one word
+// holding two bf16), and their fp32 values.  Kept apart so that nothing consumes a loaded value
+// between two loads: the loads sit behind per-lane branches (pair or not), and a conversion right
+// after one would make every load wait for the one before.
+// `pair`: one load of both coordinates (8 bytes of fp32, 4 bytes of bf16; the address is aligned
+// for it), `two`: there is a second coordinate at all.
+template <class R>
+struct RawOps;
+
+template <>
+struct RawOps<floatx2> {   // fp32 gradients
+    static __device__ __forceinline__ floatx2 load(const float *p, bool pair, bool two)
+    {
+        if (pair) return __builtin_nontemporal_load(reinterpret_cast<const floatx2 *>(p));
+        const float x0 = __builtin_nontemporal_load(p);
+        return floatx2{x0, two ? __builtin_nontemporal_load(p + 1) : x0};
     }
-}
+    static __device__ __forceinline__ floatx2 zero() { return floatx2{0.0f, 0.0f}; }
+    static __device__ __forceinline__ float widen(floatx2 r, int k) { return r[k]; }
+};
+
+template <>
+struct RawOps<unsigned> {   // bf16 gradients: one word holds both
+    static __device__ __forceinline__ unsigned load(const unsigned short *p, bool pair, bool two)
+    {
+        if (pair) return __builtin_nontemporal_load(reinterpret_cast<const unsigned *>(p));
+        const unsigned lo = __builtin_nontemporal_load(p);
+        const unsigned hi = two ? (unsigned)__builtin_nontemporal_load(p + 1) : lo;
+        return lo | (hi << 16);
+    }
+    static __device__ __forceinline__ unsigned zero() { return 0u; }
+    static __device__ __forceinline__ float widen(unsigned r, int k)
+    {
+        return __uint_as_float(k == 0 ? r << 16 : r & 0xffff0000u);
+    }
+};
+
+typedef typename std::conditional<kIn16, unsigned, floatx2>::type Raw;
+__device__ __forceinline__ Raw load_raw(const Elem *p, bool pair, bool two) { return RawOps<Raw>::load(p, pair, two); }
+__device__ __forceinline__ Raw raw_zero() { return RawOps<Raw>::zero(); }
+__device__ __forceinline__ float widen(Raw r, int k) { return RawOps<Raw>::widen(r, k); }   // coordinate k as fp32
 
 // average of the beta values a[.] closest to med (closeness |a - med| in fp32, ties to the smaller value)
 template <int THETA>
@@ -108,26 +124,23 @@ constexpr int kThreads = 256;
 constexpr int kBatch = 16;
 
 // the slots from B0 on, kBatch at a time (compile-time recursion over the batches)
-template <int B0, class Y, class Load, class X, class Apply>
-__device__ __forceinline__ void more_slots(int U, Y &y, Load &load, X &x, Apply &apply)
+template <int B0, int VEC, class Load, class Apply>
+__device__ __forceinline__ void more_slots(int U, Load &load, Apply &apply)
 {
     if constexpr (B0 < kMaxN) {
         constexpr int END = B0 + kBatch < kMaxN ? B0 + kBatch : kMaxN;
         if (B0 < U) {                                // same for every lane
-            constexpr int VEC = sizeof(y) / sizeof(y[0]);
+            Raw yr[kBatch];
 #pragma unroll
-            for (int j = 0; j < END - B0; ++j) {
+            for (int j = 0; j < END - B0; ++j) yr[j] = (B0 + j < U) ? load(B0 + j) : raw_zero();
+            float y[VEC][kBatch];
 #pragma unroll
-                for (int k = 0; k < VEC; ++k) y[k][j] = 0.0f;
-                if (B0 + j < U) {
-                    load(B0 + j);
+            for (int j = 0; j < END - B0; ++j)
 #pragma unroll
-                    for (int k = 0; k < VEC; ++k) y[k][j] = x[k];
-                }
-            }
+                for (int k = 0; k < VEC; ++k) y[k][j] = widen(yr[j], k);
             apply(std::integral_constant<int, B0>{}, std::integral_constant<int, END>{},
                   std::integral_constant<int, B0>{}, y);
-            more_slots<END>(U, y, load, x, apply);
+            more_slots<END, VEC>(U, load, apply);
         }
     }
 }
@@ -158,8 +171,7 @@ __global__ __launch_bounds__(kThreads) void coord_alg1_kernel(const Elem *__rest
     for (int t = 0; t < THETA; ++t)
 #pragma unroll
         for (int k = 0; k < VEC; ++k) P[k][t] = 0.0f;
-    float x[2];
-    auto load = [&](int slot) { load_coords(G + (int64_t)plan[kPlanRows + slot] * ld + c, vec, two, x); };
+    auto load = [&](int slot) { return load_raw(G + (int64_t)plan[kPlanRows + slot] * ld + c, vec, two); };
     // P[t] += sum over the slots [lo, hi) of delta[t][s] * v[s - base], group by group
     auto apply = [&](auto lo_c, auto hi_c, auto base_c, const auto &v) {
         constexpr int LO = decltype(lo_c)::value, HI = decltype(hi_c)::value, BASE = decltype(base_c)::value;
@@ -183,23 +195,19 @@ __global__ __launch_bounds__(kThreads) void coord_alg1_kernel(const Elem *__rest
     };
 
     // the winners (slots 0 .. theta-1, always there) and the next kBatch rows: all loads in flight at once
+    constexpr int kFirstEnd = THETA + kBatch < kMaxN ? THETA + kBatch : kMaxN;
+    Raw er[THETA], yr[kBatch];
+#pragma unroll
+    for (int t = 0; t < THETA; ++t) er[t] = load(t);
+#pragma unroll
+    for (int j = 0; j < kFirstEnd - THETA; ++j) yr[j] = (THETA + j < U) ? load(THETA + j) : raw_zero();
     float y[VEC][kBatch];
 #pragma unroll
-    for (int t = 0; t < THETA; ++t) {
-        load(t);
+    for (int k = 0; k < VEC; ++k) {
 #pragma unroll
-        for (int k = 0; k < VEC; ++k) e[k][t] = x[k];
-    }
-    constexpr int kFirstEnd = THETA + kBatch < kMaxN ? THETA + kBatch : kMaxN;
+        for (int t = 0; t < THETA; ++t) e[k][t] = widen(er[t], k);
 #pragma unroll
-    for (int j = 0; j < kFirstEnd - THETA; ++j) {
-#pragma unroll
-        for (int k = 0; k < VEC; ++k) y[k][j] = 0.0f;
-        if (THETA + j < U) {                         // same for every lane
-            load(THETA + j);
-#pragma unroll
-            for (int k = 0; k < VEC; ++k) y[k][j] = x[k];
-        }
+        for (int j = 0; j < kFirstEnd - THETA; ++j) y[k][j] = widen(yr[j], k);
     }
     apply(std::integral_constant<int, 0>{}, std::integral_constant<int, THETA>{}, std::integral_constant<int, 0>{}, e);
     if constexpr (kFirstEnd > THETA) {
@@ -208,7 +216,7 @@ __global__ __launch_bounds__(kThreads) void coord_alg1_kernel(const Elem *__rest
                   std::integral_constant<int, THETA>{}, y);
     }
     // more rows than that (only with a theta below the default or a membership matrix of one's own)
-    more_slots<THETA + kBatch>(U, y, load, x, apply);
+    more_slots<THETA + kBatch, VEC>(U, load, apply);
 
     float res[VEC];
 #pragma unroll
@@ -278,51 +286,31 @@ __global__ __launch_bounds__(kThreads) void coord_alg1_nested_kernel(
     const bool pairs_ok = VEC == 2 && ((uintptr_t)G % (2 * sizeof(Elem)) == 0) && (ld % 2 == 0) && ((uintptr_t)out % 8 == 0);
     const bool two = VEC == 2 && c + 1 < d;
     const bool vec = pairs_ok && two;
-    float x[2];
-    auto load = [&](int row) { load_coords(G + (int64_t)row * ld + c, vec, two, x); };
+    auto load = [&](int row) { return load_raw(G + (int64_t)row * ld + c, vec, two); };
+    // all loads first (the winners' rows and one batch of the last set), conversions after
+    Raw er[THETA], br[kBaseRegs];
+#pragma unroll
+    for (int t = 0; t < THETA; ++t) er[t] = load(plan[kPlanRows + t]);
+#pragma unroll
+    for (int j = 0; j < kBaseRegs; ++j) br[j] = (j < nb) ? load(plan[kPlanRows + THETA + j]) : raw_zero();
     float e[VEC][THETA];
-#pragma unroll
-    for (int t = 0; t < THETA; ++t) {
-        load(plan[kPlanRows + t]);
-#pragma unroll
-        for (int k = 0; k < VEC; ++k) e[k][t] = x[k];
-    }
     float S[VEC];
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) S[k] = 0.0f;
-    {
-        float xb[VEC][kBaseRegs];
+    for (int k = 0; k < VEC; ++k) {
 #pragma unroll
-        for (int j = 0; j < kBaseRegs; ++j) {
+        for (int t = 0; t < THETA; ++t) e[k][t] = widen(er[t], k);
+        S[k] = 0.0f;
 #pragma unroll
-            for (int k = 0; k < VEC; ++k) xb[k][j] = 0.0f;
-            if (j < nb) {                    // same for every lane
-                load(plan[kPlanRows + THETA + j]);
-#pragma unroll
-                for (int k = 0; k < VEC; ++k) xb[k][j] = x[k];
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < kBaseRegs; ++j)
-#pragma unroll
-            for (int k = 0; k < VEC; ++k) S[k] += xb[k][j];
+        for (int j = 0; j < kBaseRegs; ++j) S[k] += widen(br[j], k);
     }
-    for (int s0 = kBaseRegs; s0 < nb; s0 += 8) {   // more base rows than one batch
-        float xb[VEC][8];
+    for (int s0 = kBaseRegs; s0 < nb; s0 += 8) {   // more rows in the last set than one batch
+        Raw xr[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-#pragma unroll
-            for (int k = 0; k < VEC; ++k) xb[k][j] = 0.0f;
-            if (s0 + j < nb) {
-                load(plan[kPlanRows + THETA + s0 + j]);
-#pragma unroll
-                for (int k = 0; k < VEC; ++k) xb[k][j] = x[k];
-            }
-        }
+        for (int j = 0; j < 8; ++j) xr[j] = (s0 + j < nb) ? load(plan[kPlanRows + THETA + s0 + j]) : raw_zero();
 #pragma unroll
         for (int j = 0; j < 8; ++j)
 #pragma unroll
-            for (int k = 0; k < VEC; ++k) S[k] += xb[k][j];
+            for (int k = 0; k < VEC; ++k) S[k] += widen(xr[j], k);
     }
     float res[VEC];
 #pragma unroll
