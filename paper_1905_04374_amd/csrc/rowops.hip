@@ -35,23 +35,26 @@ __global__ __launch_bounds__(256) void masked_mean_kernel(const void *__restrict
     // not read; members are added in ascending row order
     for (int r0 = 0; r0 < n; r0 += 8) {
         float x[8][VEC];
+        unsigned raw[8];   // bf16: the words as loaded; widened after the batch is out, so that no
+                           // load waits for the conversion of the one before
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
 #pragma unroll
             for (int e = 0; e < VEC; ++e) x[j][e] = 0.0f;
+            raw[j] = 0u;
             const int r = r0 + j;
             if (r < n && ((members >> r) & 1ull)) {
                 ++m;
                 if constexpr (IN16) {
                     const unsigned short *p16 = G16 + (int64_t)r * ld + c0;
                     if (VEC == 2 && full) {
-                        const unsigned w = __builtin_nontemporal_load(reinterpret_cast<const unsigned *>(p16));
-                        x[j][0] = __uint_as_float(w << 16);
-                        x[j][1 % VEC] = __uint_as_float(w & 0xffff0000u);
+                        raw[j] = __builtin_nontemporal_load(reinterpret_cast<const unsigned *>(p16));
                     } else {
+                        unsigned w = 0u;
 #pragma unroll
                         for (int e = 0; e < VEC; ++e)
-                            x[j][e] = (c0 + e < d) ? __uint_as_float((unsigned)p16[e] << 16) : 0.0f;
+                            w |= (c0 + e < d) ? (unsigned)p16[e] << (16 * e) : 0u;
+                        raw[j] = w;
                     }
                     continue;
                 }
@@ -63,6 +66,13 @@ __global__ __launch_bounds__(256) void masked_mean_kernel(const void *__restrict
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) x[j][e] = (c0 + e < d) ? p[e] : 0.0f;
                 }
+            }
+        }
+        if constexpr (IN16) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                x[j][0] = __uint_as_float(raw[j] << 16);
+                x[j][1 % VEC] = __uint_as_float(VEC == 2 ? raw[j] & 0xffff0000u : raw[j] << 16);
             }
         }
 #pragma unroll
