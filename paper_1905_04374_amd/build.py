@@ -24,7 +24,8 @@ LIB = os.path.join(HERE, "libmbulyan.so")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 
 ARCH = "gfx950"
-# packed fp32 VALU instructions are switched off on purpose ("compiler flags")
+# packed fp32 VALU instructions are switched off on purpose: some of their forms have given wrong
+# results on these machines now and then, with no error
 COMMON = ["-std=c++17", "-O3", f"--offload-arch={ARCH}", "-fPIC",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
           "-Wno-unused-command-line-argument", f"-I{INCLUDE}"]
