@@ -143,7 +143,7 @@ __global__ __launch_bounds__(1024) void finalize_gram_kernel(const double *__res
         D[i * kMaxN + j] = v;
     }
     __syncthreads();
-    if (threadIdx.x < n) {
+    if ((int)threadIdx.x < n) {
         int r = threadIdx.x;
         if (canon)
             for (int i = 0; i < (int)threadIdx.x; ++i)

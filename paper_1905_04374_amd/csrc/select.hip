@@ -85,7 +85,7 @@ __device__ __forceinline__ void play_rounds(const Rounds &a, int i)
         while (lo < hi) {
             const int mid = (lo + hi) >> 1;
             const unsigned long long below = mid >= 64 ? ~0ull : ((1ull << mid) - 1ull);
-            if (__popcll(near & below) >= q) hi = mid; else lo = mid + 1;
+            if ((int)__popcll(near & below) >= q) hi = mid; else lo = mid + 1;
         }
         take = near & (lo >= 64 ? ~0ull : ((1ull << lo) - 1ull));
     }
