@@ -390,6 +390,39 @@ def test_multikrum_aggregate():
         assert_out_close(out, ref, np.abs(G[mask.astype(bool)]).mean(0))
 
 
+def test_aggregate_can_be_captured_in_a_graph():
+    """An aggregation with a caller workspace allocates nothing and issues only kernels and one
+    device-to-device copy, so a stream capture records it.  Replays (with eager work and
+    synchronisation in between, on fresh inputs) must equal the eager result each time."""
+    say("graph capture")
+    n, f, d = 19, 4, 200_000
+    G = W.uniform(n, d, DEV, seed=1)
+    ws = torch.empty(mb.mbulyan_workspace_bytes(n, d), dtype=torch.uint8, device=DEV)
+    theta, _ = mb.mbulyan_params(n, f)
+    out = torch.empty(d, device=DEV)
+    sel = torch.empty(theta, device=DEV, dtype=torch.int32)
+    for mode in (mb.MODE_SELECTED, mb.MODE_ALG1):
+        th, _ = mb.mbulyan_params(n, f, mode)
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            mb.mbulyan_aggregate_ex(G, f, mode=mode, out=out, selected_idx=sel[:th], workspace=ws)   # warm-up: one-time set-up
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                mb.mbulyan_aggregate_ex(G, f, mode=mode, out=out, selected_idx=sel[:th], workspace=ws)
+        torch.cuda.synchronize()
+        for rep in range(3):
+            G.copy_(W.uniform(n, d, DEV, seed=2 + rep))
+            eager, esel = mb.mbulyan_aggregate_ex(G, f, mode=mode, workspace=ws)
+            torch.cuda.synchronize()
+            out.zero_()
+            sel.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, eager) and torch.equal(sel[:th], esel), (mode, rep)
+
+
 def test_stream_argument_is_honoured():
     say("stream")
     s = W.spec(1)
