@@ -176,3 +176,47 @@ def test_full_size_chunked():
             worst = max(worst, check_chunk(got[lo:hi], ref, scale))
         say("oracle coordinate phase of chunk", k)
     say(f"cfg 5 (d={d}): selected {ext.tolist()}, score gap {gap:.2e}, out worst err/tol {worst:.3g}")
+
+
+def test_more_than_2_to_the_31_coordinates():
+    """d = 2^31 + 2^27 + 77 per row (n = 11, 100 GB): every index computation has to be 64-bit.  The oracle
+    cannot take the whole matrix in reasonable time, so: the distance matrix equals the one accumulated
+    over four chunks (each below 2^31 columns, the path the other tests pin), the extracted list is the
+    oracle's for that matrix, and the output is compared with the oracle on blocks of columns sampled
+    over the whole range, the last block ending at d."""
+    n, f = 11, 2
+    d = (1 << 31) + (1 << 27) + 77
+    say("d > 2^31", n, f, d)
+    # one round fewer than the default: in the last default round (one neighbour each) two gradients
+    # that are each other's nearest tie exactly, which is fine but not what check_separation expects
+    theta, beta = 6, 2
+    Gt = torch.empty(n, d, device=DEV, dtype=torch.float32)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(1905)
+    step = 1 << 27
+    noise = 1.0 + 0.05 * torch.arange(n, device=DEV, dtype=torch.float32)[:, None]   # a noise ladder: scores apart
+    for lo in range(0, d, step):                       # filled in slabs: no d-sized temporaries
+        hi = min(d, lo + step)
+        mu = torch.randn(1, hi - lo, generator=gen, device=DEV)
+        Gt[:, lo:hi] = mu + noise * torch.randn(n, hi - lo, generator=gen, device=DEV)
+    ws = torch.empty(mb.mbulyan_workspace_bytes(n, d), dtype=torch.uint8, device=DEV)
+    out, sel = mb.mbulyan_aggregate_ex(Gt, f, theta=theta, beta=beta, workspace=ws)
+    D = mb.pairwise_sqdist(Gt, workspace=ws).cpu().numpy()
+    torch.cuda.synchronize()
+    cuts = [0, d // 4, d // 2, 3 * (d // 4) + 5, d]
+    Dc = None
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        Dc = mb.pairwise_sqdist(Gt[:, a:b], dist=Dc, accumulate=Dc is not None, workspace=ws)
+    Dc = Dc.cpu().numpy()
+    assert np.all(np.abs(D - Dc) <= 1e-9 * np.maximum(D, 1.0)), float(np.max(np.abs(D - Dc) / np.maximum(D, 1.0)))
+    ext, _, _ = O.multikrum_select(D, f, theta)
+    check_separation(D, f, theta, ext)
+    assert sel.cpu().numpy().tolist() == ext.tolist()
+    width = 1 << 20
+    worst = 0.0
+    for b in range(33):
+        lo = (d - width) * b // 32
+        G = Gt[:, lo:lo + width].cpu().numpy()
+        ref, scale = O.coordwise_selected(np.ascontiguousarray(G), ext, beta, want_scale=True)
+        worst = max(worst, check_chunk(out[lo:lo + width].cpu().numpy(), ref, scale))
+    say(f"d = {d}: selected {ext.tolist()}, out worst err/tol {worst:.3g} on 33 blocks of 2^20 columns")
