@@ -164,30 +164,56 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const double inf = __builtin_huge_val();
 
     if (dist) {
-        for (int e = tid; e < n * n; e += kSelThreads) {
-            double x = dist[e];
-            if (!(x == x)) x = inf;                 // a NaN distance never makes a neighbour
-            sD[(e / n) * kMaxN + (e % n)] = x;
+        double x[kPerThread];
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) {
+            const int e = tid + k * kSelThreads;
+            x[k] = e < n * n ? dist[e] : 0.0;
+        }
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) {
+            const int e = tid + k * kSelThreads;
+            if (e < n * n) sD[(e / n) * kMaxN + (e % n)] = (x[k] == x[k]) ? x[k] : inf;   // a NaN distance never makes a neighbour
         }
         __syncthreads();
     } else {
-        for (int e = tid; e < n * n; e += kSelThreads) {
-            const int i = e / n, j = e % n;
-            const int hi = i > j ? i : j, lo = i > j ? j : i;
-            double v = 0.0;
-            if (hi != lo) {
-                v = (gram_at(gram, hi, hi) + gram_at(gram, lo, lo)) - 2.0 * gram_at(gram, hi, lo);
-                v = v < 0.0 ? 0.0 : v;
+        // the Gram entries of all of a thread's elements first (up to 3 x kPerThread loads in
+        // flight), the arithmetic after
+        double gh[kPerThread], gl[kPerThread], gx[kPerThread];
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) {
+            const int e = tid + k * kSelThreads;
+            gh[k] = gl[k] = gx[k] = 0.0;
+            if (e < n * n) {
+                const int i = e / n, j = e % n;
+                const int hi = i > j ? i : j, lo = i > j ? j : i;
+                if (hi != lo) {
+                    gh[k] = gram_at(gram, hi, hi);
+                    gl[k] = gram_at(gram, lo, lo);
+                    gx[k] = gram_at(gram, hi, lo);
+                }
             }
-            sD[i * kMaxN + j] = v;
         }
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) {
+            const int e = tid + k * kSelThreads;
+            if (e < n * n) {
+                double v = (gh[k] + gl[k]) - 2.0 * gx[k];      // 0 on the diagonal
+                v = v < 0.0 ? 0.0 : v;
+                sD[(e / n) * kMaxN + (e % n)] = v;
+            }
+        }
+        if (tid < kMaxN) rep[tid] = tid;
         __syncthreads();
-        if (tid < n) {
-            int r = tid;
-            if (canon)
-                for (int i = 0; i < tid; ++i)
-                    if (sD[i * kMaxN + tid] == 0.0) { r = i; break; }
-            rep[tid] = r;
+        if (canon) {   // rep[j] = the first row at distance exactly 0 from row j (j itself if none)
+#pragma unroll
+            for (int k = 0; k < kPerThread; ++k) {
+                const int e = tid + k * kSelThreads;
+                if (e < n * n) {
+                    const int i = e / n, j = e % n;
+                    if (i < j && sD[i * kMaxN + j] == 0.0) atomicMin(&rep[j], i);
+                }
+            }
         }
         __syncthreads();
         double mine[kPerThread];
