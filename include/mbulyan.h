@@ -19,7 +19,10 @@
  *   - Gradients: n rows of d floats (fp32), row i starting at grads + i*ld,
  *     ld >= d the row stride in elements.  Fastest when grads is 16-byte
  *     aligned and ld is a multiple of 4; other strides are handled by a
- *     slower load path.  Inputs must be finite.
+ *     slower load path.  Results are defined for finite inputs; a gradient
+ *     that holds a NaN or an infinity is at distance +inf from every other,
+ *     so it is never a neighbour and, while no more than f rows are like
+ *     that, never chosen nor read by the coordinate pass.
  *   - n <= MB_MAX_N.
  *   - Arguments are validated on the host before anything is launched; an
  *     invalid call launches nothing.

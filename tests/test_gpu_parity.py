@@ -378,6 +378,44 @@ def test_explicit_theta_beta_and_no_byzantine():
     assert_out_close(out, ref, scale)
 
 
+@pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("mode", ["selected", "alg1"])
+def test_non_finite_byzantine_rows_are_never_chosen(algo, mode):
+    """Byzantine rows full of NaN / inf have no finite distance to anyone: they are never a neighbour and never
+    chosen, so the result is that of the same matrix with those rows moved far away (finite, 1e10)."""
+    say("non-finite rows", algo, mode)
+    s = W.spec(2)
+    n, f = s["n"], s["f"]
+    d = 40_003
+    Gt = W.make(2, DEV, d=d)                       # Byzantine rows are the last f
+    far = Gt.clone()
+    bad = Gt.clone()
+    for k in range(f):
+        far[n - 1 - k] = 1e10 * (k + 1)
+        bad[n - 1 - k] = [float("nan"), float("inf"), -float("inf")][k % 3]
+    if f >= 2:
+        bad[n - 2, ::2] = float("nan")             # a mixed row
+    G = far.cpu().numpy()
+    omode = O.MODE_ALG1 if mode == "alg1" else O.MODE_SELECTED
+    theta, beta = O.params(n, f, omode)
+    ext, sets, m = O.multikrum_select(O.pairwise_sqdist(G), f, theta)
+    assert set(ext.tolist()).isdisjoint(range(n - f, n))
+    mb.mbulyan_set_dist_algo(algo)
+    try:
+        out, sel = mb.mbulyan_aggregate_ex(bad, f, mode=mb.MODE_ALG1 if mode == "alg1" else mb.MODE_SELECTED)
+        torch.cuda.synchronize()
+    finally:
+        mb.mbulyan_set_dist_algo(mb.DIST_AUTO)
+    assert sel.cpu().numpy().tolist() == ext.tolist()
+    assert torch.isfinite(out).all()
+    if mode == "alg1":
+        ref, scale, margin, alt = O.coordwise_alg1(G, ext, sets, beta, want_extra=True)
+        assert alg1_compare(out, ref, scale, margin, alt) <= max(2, d // 1000)
+    else:
+        ref, scale = O.coordwise_selected(G, ext, beta, want_scale=True)
+        assert_out_close(out, ref, scale)
+
+
 def test_multikrum_aggregate():
     say("multikrum_aggregate")
     for cfg, d in [(1, 50_001), (2, 20_000)]:
