@@ -148,6 +148,30 @@ def test_aggregate_bf16_matches_oracle(cfg, d, placement):
     assert torch.equal(out, out2) and torch.equal(sel, sel2)
 
 
+def test_non_finite_byzantine_rows_are_never_chosen_bf16():
+    """Rows full of NaN / inf are at distance +inf from everyone: the result is that of the same matrix with
+    those rows moved far away (finite), for the whole rule and for the multi-Krum average."""
+    say("non-finite rows bf16")
+    s = W.spec(2)
+    n, f = s["n"], s["f"]
+    Gt = W.make(2, DEV, d=60_002).to(torch.bfloat16)       # Byzantine rows are the last f
+    far, bad = Gt.clone(), Gt.clone()
+    for k in range(f):
+        far[n - 1 - k] = 1e10 * (k + 1)
+        bad[n - 1 - k] = [float("nan"), float("inf"), -float("inf")][k % 3]
+    bad[n - 2, 1::2] = float("nan")
+    G = far.float().cpu().numpy()
+    ref, ext = O.mbulyan(G, f)
+    _, scale = O.coordwise_selected(G, ext, O.params(n, f)[1], want_scale=True)
+    out, sel = mb.mbulyan_aggregate_ex(bad, f)
+    assert sel.cpu().numpy().tolist() == ext.tolist()
+    assert_out_close(out, ref, scale)
+    ref, mask = O.multikrum_aggregate(G, f)
+    out, mask_g = mb.multikrum_aggregate(bad, f)
+    assert np.array_equal(mask_g.cpu().numpy(), mask) and not mask[n - f:].any()
+    assert_out_close(out, ref, np.abs(G[mask.astype(bool)]).mean(0))
+
+
 def test_aggregate_chunked_bf16_equals_whole():
     say("chunked bf16")
     s = W.spec(5)

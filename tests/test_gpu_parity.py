@@ -414,6 +414,10 @@ def test_non_finite_byzantine_rows_are_never_chosen(algo, mode):
     else:
         ref, scale = O.coordwise_selected(G, ext, beta, want_scale=True)
         assert_out_close(out, ref, scale)
+        ref, mask = O.multikrum_aggregate(G, f)
+        out, mask_g = mb.multikrum_aggregate(bad, f)
+        assert np.array_equal(mask_g.cpu().numpy(), mask) and not mask[n - f:].any()
+        assert_out_close(out, ref, np.abs(G[mask.astype(bool)]).mean(0))
 
 
 def test_multikrum_aggregate():
