@@ -422,18 +422,17 @@ static int aggregate_chunked(const void *const *chunks, int in16, int nchunks, c
                              MB_DIST_AUTO, ws, s);
         if (rc != MB_OK) return rc;
     }
+    int32_t *sel = selected_idx ? selected_idx : ws.sel();   // the selection writes the caller's list in place
     {
         StageTimer t(MB_STAGE_SELECT, s);
-        MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, ws.sel(),
+        MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, sel,
                                  mode == MB_MODE_ALG1 ? ws.sets() : nullptr, ws.m(), nullptr, s));
     }
     for (int c = 0; c < nchunks; ++c) {
-        rc = run_coord(chunks[c], in16, n, chunk_d[c], chunk_ld[c], mode, theta, beta, ws.sel(), ws.sets(), ws.plan(),
+        rc = run_coord(chunks[c], in16, n, chunk_d[c], chunk_ld[c], mode, theta, beta, sel, ws.sets(), ws.plan(),
                        outs[c], s);
         if (rc != MB_OK) return rc;
     }
-    if (selected_idx)
-        MB_HIP(hipMemcpyAsync(selected_idx, ws.sel(), sizeof(int32_t) * theta, hipMemcpyDeviceToDevice, s));
     return MB_OK;
 }
 
@@ -470,19 +469,16 @@ int mbulyan_aggregate_ex(const float *grads, int n, int f, int64_t d, int64_t ld
     bool canon = false;
     rc = run_dist(grads, n, d, ld, ws.dist(), 0, MB_DIST_AUTO, ws, s, &deferred, &canon);
     if (rc != MB_OK) return rc;
+    int32_t *sel = selected_idx ? selected_idx : ws.sel();   // the selection writes the caller's list in place
     {
         StageTimer t(MB_STAGE_SELECT, s);
         uint8_t *sets = mode == MB_MODE_ALG1 ? ws.sets() : nullptr;
         if (deferred)
-            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, theta, ws.sel(), sets, ws.m(), s));
+            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, theta, sel, sets, ws.m(), s));
         else
-            MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, ws.sel(), sets, ws.m(), nullptr, s));
+            MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, sel, sets, ws.m(), nullptr, s));
     }
-    rc = run_coord(grads, 0, n, d, ld, mode, theta, beta, ws.sel(), ws.sets(), ws.plan(), out, s);
-    if (rc != MB_OK) return rc;
-    if (selected_idx)
-        MB_HIP(hipMemcpyAsync(selected_idx, ws.sel(), sizeof(int32_t) * theta, hipMemcpyDeviceToDevice, s));
-    return MB_OK;
+    return run_coord(grads, 0, n, d, ld, mode, theta, beta, sel, ws.sets(), ws.plan(), out, s);
 }
 
 int mbulyan_aggregate(const float *grads, int n, int f, int64_t d, float *out, int32_t *selected_idx,
@@ -507,18 +503,18 @@ int multikrum_aggregate(const float *grads, int n, int f, int64_t d, int64_t ld,
     bool canon = false;
     rc = run_dist(grads, n, d, ld, ws.dist(), 0, MB_DIST_AUTO, ws, s, &deferred, &canon);
     if (rc != MB_OK) return rc;
+    uint8_t *mask = selected_mask ? selected_mask : ws.sets();   // written in place by the selection
     {
         StageTimer t(MB_STAGE_SELECT, s);
         if (deferred)
-            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, 1, ws.sel(), ws.sets(), ws.m(), s));
+            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, 1, ws.sel(), mask, ws.m(), s));
         else
-            MB_HIP(mb::launch_select(ws.dist(), n, f, 1, nullptr, ws.sel(), ws.sets(), ws.m(), nullptr, s));
+            MB_HIP(mb::launch_select(ws.dist(), n, f, 1, nullptr, ws.sel(), mask, ws.m(), nullptr, s));
     }
     {
         StageTimer t(MB_STAGE_COORD, s);
-        MB_HIP(mb::launch_masked_mean(grads, n, d, ld, ws.sets(), out, s));
+        MB_HIP(mb::launch_masked_mean(grads, n, d, ld, mask, out, s));
     }
-    if (selected_mask) MB_HIP(hipMemcpyAsync(selected_mask, ws.sets(), (size_t)n, hipMemcpyDeviceToDevice, s));
     return MB_OK;
 }
 
@@ -576,18 +572,18 @@ int multikrum_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d, int
     bool canon = false;
     rc = run_dist_in16(grads, n, d, ld, ws.dist(), 0, ws, s, &deferred, &canon);
     if (rc != MB_OK) return rc;
+    uint8_t *mask = selected_mask ? selected_mask : ws.sets();   // written in place by the selection
     {
         StageTimer t(MB_STAGE_SELECT, s);
         if (deferred)
-            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, 1, ws.sel(), ws.sets(), ws.m(), s));
+            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, 1, ws.sel(), mask, ws.m(), s));
         else
-            MB_HIP(mb::launch_select(ws.dist(), n, f, 1, nullptr, ws.sel(), ws.sets(), ws.m(), nullptr, s));
+            MB_HIP(mb::launch_select(ws.dist(), n, f, 1, nullptr, ws.sel(), mask, ws.m(), nullptr, s));
     }
     {
         StageTimer t(MB_STAGE_COORD, s);
-        MB_HIP(mb::launch_masked_mean_in16(grads, n, d, ld, ws.sets(), out, s));
+        MB_HIP(mb::launch_masked_mean_in16(grads, n, d, ld, mask, out, s));
     }
-    if (selected_mask) MB_HIP(hipMemcpyAsync(selected_mask, ws.sets(), (size_t)n, hipMemcpyDeviceToDevice, s));
     return MB_OK;
 }
 
@@ -621,19 +617,16 @@ int mbulyan_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d, int64
     bool canon = false;
     rc = run_dist_in16(grads, n, d, ld, ws.dist(), 0, ws, s, &deferred, &canon);
     if (rc != MB_OK) return rc;
+    int32_t *sel = selected_idx ? selected_idx : ws.sel();   // the selection writes the caller's list in place
     {
         StageTimer t(MB_STAGE_SELECT, s);
         uint8_t *sets = mode == MB_MODE_ALG1 ? ws.sets() : nullptr;
         if (deferred)
-            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, theta, ws.sel(), sets, ws.m(), s));
+            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, theta, sel, sets, ws.m(), s));
         else
-            MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, ws.sel(), sets, ws.m(), nullptr, s));
+            MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, sel, sets, ws.m(), nullptr, s));
     }
-    rc = run_coord(grads, 1, n, d, ld, mode, theta, beta, ws.sel(), ws.sets(), ws.plan(), out, s);
-    if (rc != MB_OK) return rc;
-    if (selected_idx)
-        MB_HIP(hipMemcpyAsync(selected_idx, ws.sel(), sizeof(int32_t) * theta, hipMemcpyDeviceToDevice, s));
-    return MB_OK;
+    return run_coord(grads, 1, n, d, ld, mode, theta, beta, sel, ws.sets(), ws.plan(), out, s);
 }
 
 int mbulyan_timing_enable(int on)

@@ -433,8 +433,8 @@ def test_multikrum_aggregate():
 
 
 def test_aggregate_can_be_captured_in_a_graph():
-    """An aggregation with a caller workspace allocates nothing and issues only kernels and one
-    device-to-device copy, so a stream capture records it.  Replays (with eager work and
+    """An aggregation with a caller workspace allocates nothing and issues only kernels, so a
+    stream capture records it.  Replays (with eager work and
     synchronisation in between, on fresh inputs) must equal the eager result each time."""
     say("graph capture")
     n, f, d = 19, 4, 200_000
