@@ -159,36 +159,42 @@ __global__ __launch_bounds__(1024) void finalize_gram_kernel(const double *__res
 }
 
 // ------------------------------------------------------------------ reduce
-// reduced[e] = sum over workgroups b of partials[b][e], added in a fixed order: 16 contiguous
-// segments of workgroups are summed independently, then the 16 segment sums are added in order.
-__global__ __launch_bounds__(1024) void reduce_partials_kernel(const double *__restrict__ partials,
-                                                               int nblocks, int stride, int slots,
-                                                               double *__restrict__ reduced)
+// reduced[e] = sum over workgroups b of partials[b][e], added in a fixed order: kRedSegs contiguous
+// segments of workgroups are summed independently, then the segment sums are added in order.  A
+// workgroup takes kRedSlots consecutive entries (128 contiguous bytes per partial tile) so that the
+// launch has many workgroups and every thread only a few loads, all in flight at once: the kernel
+// is a chain of memory latencies, not of bytes.
+constexpr int kRedSegs = 64;
+constexpr int kRedSlots = 16;
+constexpr int kRedBatch = 16;
+
+__global__ __launch_bounds__(kRedSegs * kRedSlots) void reduce_partials_kernel(
+    const double *__restrict__ partials, int nblocks, int stride, int slots, double *__restrict__ reduced)
 {
-    __shared__ double seg_sum[16][64];
-    const int el = threadIdx.x & 63;
-    const int seg = threadIdx.x >> 6;
-    const int e = blockIdx.x * 64 + el;
-    const int per = (nblocks + 15) / 16;
+    __shared__ double seg_sum[kRedSegs][kRedSlots + 1];
+    const int el = threadIdx.x % kRedSlots;
+    const int seg = threadIdx.x / kRedSlots;
+    const int e = blockIdx.x * kRedSlots + el;
+    const int per = (nblocks + kRedSegs - 1) / kRedSegs;
     const int b0 = seg * per;
     const int b1 = (b0 + per < nblocks) ? b0 + per : nblocks;
     double s = 0.0;
     if (e < slots) {
-        // eight loads in flight, added in workgroup order all the same
-        for (int b = b0; b < b1; b += 8) {
-            double x[8];
+        for (int b = b0; b < b1; b += kRedBatch) {
+            double x[kRedBatch];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) x[k] = (b + k < b1) ? partials[(int64_t)(b + k) * stride + e] : 0.0;
+            for (int k = 0; k < kRedBatch; ++k)
+                x[k] = (b + k < b1) ? partials[(int64_t)(b + k) * stride + e] : 0.0;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) s += x[k];
+            for (int k = 0; k < kRedBatch; ++k) s += x[k];
         }
     }
     seg_sum[seg][el] = s;
     __syncthreads();
     if (seg == 0 && e < slots) {
         double tot = 0.0;
-#pragma unroll
-        for (int k = 0; k < 16; ++k) tot += seg_sum[k][el];
+#pragma unroll 8
+        for (int k = 0; k < kRedSegs; ++k) tot += seg_sum[k][el];
         reduced[e] = tot;
     }
 }
@@ -220,8 +226,8 @@ hipError_t launch_dist_direct(const float *G, int n, int64_t d, int64_t ld, doub
 hipError_t launch_reduce(const double *partials, int nblocks, int stride, int slots, double *reduced,
                          hipStream_t s)
 {
-    reduce_partials_kernel<<<dim3((slots + 63) / 64), dim3(1024), 0, s>>>(partials, nblocks, stride, slots,
-                                                                          reduced);
+    reduce_partials_kernel<<<dim3((slots + kRedSlots - 1) / kRedSlots), dim3(kRedSegs * kRedSlots), 0, s>>>(
+        partials, nblocks, stride, slots, reduced);
     return hipGetLastError();
 }
 
