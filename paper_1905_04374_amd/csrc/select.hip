@@ -6,8 +6,10 @@
 // counting, keys (distance, index)); then a single wave, lane i = gradient i,
 // plays the rounds with its ordered row held in registers and a bit mask of the
 // ranks still active: add the q nearest distances in ascending order in fp64,
-// find the smallest (score, index) by a wave reduction (or rank all scores by
-// lane broadcasts when the averaged sets are wanted), extract it.
+// find the smallest (score, index) by a wave reduction, extract it.  When the
+// averaged sets are wanted every score has to be ranked in every round: the
+// scores go through LDS and all eight waves count, each over an eighth of the
+// gradients.
 #include <hip/hip_runtime.h>
 
 #include "mb_internal.hpp"
@@ -28,6 +30,9 @@ struct Rounds {
     uint8_t *agr_sets;
     int32_t *m_out;
     double *scores_out;
+    double *sS;                  // LDS, 64 scores of the current round      } only when the sets are
+    unsigned long long *sAct;    // LDS, the active gradients of that round  } wanted: see
+    unsigned char *sCnt;         // LDS, [lane][wave] partial counts         } count_before
 };
 
 __device__ __forceinline__ double read_lane(double x, int lane)   // lane: the same for the whole wave
@@ -45,6 +50,38 @@ __device__ __forceinline__ double dpp_move(double x)   // x of the lane the DPP 
     const int lo = __builtin_amdgcn_update_dpp(0, (int)(unsigned)u, CTRL, 0xf, 0xf, true);
     const int hi = __builtin_amdgcn_update_dpp(0, (int)(unsigned)(u >> 32), CTRL, 0xf, 0xf, true);
     return __longlong_as_double((long long)(((unsigned long long)(unsigned)hi << 32) | (unsigned)lo));
+}
+
+constexpr int kSelWaves = kSelThreads / 64;
+
+// Wave `wave` of kSelWaves, lane i: how many active gradients j = wave, wave + 8, ... come before
+// gradient i in the order (score, index).  Scores of lanes that hold no active gradient are +inf
+// and their bit in `act` is clear.
+__device__ __forceinline__ void count_before(const double *sS, unsigned long long act, int wave, int i,
+                                             unsigned char *sCnt)
+{
+    const double S = sS[i];
+    double Sj[64 / kSelWaves];
+#pragma unroll
+    for (int k = 0; k < 64 / kSelWaves; ++k) Sj[k] = sS[wave + kSelWaves * k];
+    int cnt = 0;
+#pragma unroll
+    for (int k = 0; k < 64 / kSelWaves; ++k) {
+        const int j = wave + kSelWaves * k;
+        if ((act >> j) & 1ull) cnt += (Sj[k] < S || (Sj[k] == S && j < i)) ? 1 : 0;
+    }
+    sCnt[i * kSelWaves + wave] = (unsigned char)cnt;
+}
+
+// The waves that do not play the rounds: one count per round, between the two barriers of that
+// round (the same two that play_rounds goes through).
+__device__ __forceinline__ void help_rounds(const Rounds &a, int wave, int i)
+{
+    for (int t = 0; t < a.rounds; ++t) {
+        __syncthreads();
+        count_before(a.sS, *a.sAct, wave, i, a.sCnt);
+        __syncthreads();
+    }
 }
 
 // One wave, lane i = gradient i, ordered row in NV >= n - 1 registers.
@@ -107,14 +144,14 @@ __device__ __forceinline__ void play_rounds(const Rounds &a, int i)
 
         int w;            // the first of the active gradients in the order (score, index)
         if (a.agr_sets) {
-            int pos = 0;  // position of i in that order
-#pragma unroll
-            for (int j = 0; j <= NV; ++j) {
-                if ((act >> j) & 1ull) {       // active gradients only (same test in every lane)
-                    const double Sj = read_lane(S, j);
-                    pos += (Sj < S || (Sj == S && j < i)) ? 1 : 0;
-                }
-            }
+            // position of i in that order: every wave counts over its eighth of the gradients
+            a.sS[i] = S;
+            if (i == 0) *a.sAct = act;
+            __syncthreads();
+            count_before(a.sS, act, 0, i, a.sCnt);
+            __syncthreads();
+            const uint2 c = *reinterpret_cast<const uint2 *>(a.sCnt + i * kSelWaves);   // 8 counts of at most 8
+            const int pos = (int)((c.x * 0x01010101u) >> 24) + (int)((c.y * 0x01010101u) >> 24);
             const unsigned long long first = __ballot(mine && pos == 0);
             w = first ? (int)__builtin_ctzll(first) : 0;
             if (i < n) a.agr_sets[t * n + i] = (mine && pos < q) ? 1 : 0;
@@ -160,6 +197,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     __shared__ unsigned char sJ[kMaxN * kMaxN]; // neighbour index by rank within row i
     __shared__ unsigned char sR[kMaxN * kMaxN]; // rank of neighbour j within row i
     __shared__ int rep[kMaxN];
+    __shared__ double sS[64];
+    __shared__ unsigned long long sAct;
+    __shared__ __attribute__((aligned(8))) unsigned char sCnt[64 * kSelWaves];
+    static_assert(kSelWaves == 8 && kMaxN <= 64, "count_before: eight counts of at most eight per lane");
     const int tid = threadIdx.x;
     const double inf = __builtin_huge_val();
 
@@ -278,8 +319,11 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
         }
     }
     __syncthreads();
-    if (tid >= 64) return;   // one wave plays the rounds; no workgroup barrier below this line
-    const Rounds rd{sD, sJ, sR, n, f, rounds, active_in, sel, agr_sets, m_out, scores_out};
+    const Rounds rd{sD, sJ, sR, n, f, rounds, active_in, sel, agr_sets, m_out, scores_out, sS, &sAct, sCnt};
+    if (tid >= 64) {   // one wave plays the rounds; the others only help to rank the scores for the sets
+        if (agr_sets) help_rounds(rd, tid >> 6, tid & 63);
+        return;
+    }
     if (n <= 16) play_rounds<15>(rd, tid);
     else if (n <= 32) play_rounds<31>(rd, tid);
     else if (n <= 48) play_rounds<47>(rd, tid);
