@@ -12,6 +12,7 @@ from __future__ import annotations
 
 import argparse
 import os
+import re
 import shutil
 import subprocess
 import sys
@@ -56,12 +57,24 @@ def units():
     return u
 
 
+def _local_includes(path: str, seen: set) -> set:
+    """The headers beside the sources that `path` includes with quotes, directly or through them."""
+    with open(path) as fh:
+        names = re.findall(r'^\s*#\s*include\s+"([^"]+)"', fh.read(), flags=re.M)
+    for name in names:
+        dep = os.path.join(CSRC, name)
+        if dep not in seen and os.path.exists(dep):
+            seen.add(dep)
+            _local_includes(dep, seen)
+    return seen
+
+
 def _deps_newer(obj: str, src: str) -> bool:
-    """An object depends on its own source, every header beside it and this file; the C-ABI layer
-    also on the public headers (no other source includes them)."""
+    """An object depends on its own source, the headers beside it that it includes and this file;
+    the C-ABI layer also on the public headers (no other source includes them)."""
     t = os.path.getmtime(obj)
     deps = [os.path.join(CSRC, src), __file__]
-    deps += [os.path.join(CSRC, name) for name in os.listdir(CSRC) if name.endswith(".hpp")]
+    deps += sorted(_local_includes(os.path.join(CSRC, src), set()))
     if src == "api.hip":
         deps += [os.path.join(INCLUDE, name) for name in os.listdir(INCLUDE)]
     return any(os.path.getmtime(dep) > t for dep in deps)

@@ -220,8 +220,9 @@ int run_dist(const float *grads, int n, int64_t d, int64_t ld, double *dist, int
     return MB_OK;
 }
 
+// plan_ready: the selection has already written the plan for (sel, sets)
 int run_coord(const void *grads, int in16, int n, int64_t d, int64_t ld, int mode, int theta, int beta,
-              const int32_t *sel, const uint8_t *sets, int32_t *plan, float *out, hipStream_t s)
+              const int32_t *sel, const uint8_t *sets, int32_t *plan, bool plan_ready, float *out, hipStream_t s)
 {
     StageTimer t(MB_STAGE_COORD, s);
     if (mode == MB_MODE_SELECTED) {
@@ -229,7 +230,7 @@ int run_coord(const void *grads, int in16, int n, int64_t d, int64_t ld, int mod
         MB_HIP(mb::launch_coord_selected(a, s));
     } else {
         mb::CoordAlg1Args a{grads, n, d, ld, sel, sets, theta, beta, out, plan, in16};
-        MB_HIP(mb::launch_alg1_plan(n, theta, sel, sets, plan, s));
+        if (!plan_ready) MB_HIP(mb::launch_alg1_plan(n, theta, sel, sets, plan, s));
         MB_HIP(mb::launch_coord_alg1(a, s));
     }
     return MB_OK;
@@ -366,7 +367,7 @@ int krum_scores(const double *dist, int n, int f, const uint8_t *active, double 
     if (!dist || !scores || n < 1 || f < 0) return MB_EINVAL;
     if (n > MB_MAX_N) return MB_EUNSUPPORTED;
     StageTimer t(MB_STAGE_SELECT, (hipStream_t)stream);
-    MB_HIP(mb::launch_select(dist, n, f, 1, active, nullptr, nullptr, nullptr, scores, (hipStream_t)stream));
+    MB_HIP(mb::launch_select(dist, n, f, 1, active, nullptr, nullptr, nullptr, scores, nullptr, (hipStream_t)stream));
     return MB_OK;
 }
 
@@ -376,7 +377,7 @@ int multikrum_select(const double *dist, int n, int f, int theta, int32_t *selec
     if (!dist || !selected_idx || n < 1 || f < 0 || theta < 1 || theta > n) return MB_EINVAL;
     if (n > MB_MAX_N) return MB_EUNSUPPORTED;
     StageTimer t(MB_STAGE_SELECT, (hipStream_t)stream);
-    MB_HIP(mb::launch_select(dist, n, f, theta, nullptr, selected_idx, agr_sets, m_out, nullptr,
+    MB_HIP(mb::launch_select(dist, n, f, theta, nullptr, selected_idx, agr_sets, m_out, nullptr, nullptr,
                              (hipStream_t)stream));
     return MB_OK;
 }
@@ -393,7 +394,7 @@ int coordwise_trimmed_avg(const float *grads, int n, int64_t d, int64_t ld, cons
         if (wrc != MB_OK) return wrc;
     }
     return run_coord(grads, 0, n, d, ld, agr_sets ? MB_MODE_ALG1 : MB_MODE_SELECTED, theta, beta,
-                     selected_idx, agr_sets, agr_sets ? ws.plan() : nullptr, out, (hipStream_t)stream);
+                     selected_idx, agr_sets, agr_sets ? ws.plan() : nullptr, false, out, (hipStream_t)stream);
 }
 
 static int aggregate_chunked(const void *const *chunks, int in16, int nchunks, const int64_t *chunk_d,
@@ -426,11 +427,12 @@ static int aggregate_chunked(const void *const *chunks, int in16, int nchunks, c
     {
         StageTimer t(MB_STAGE_SELECT, s);
         MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, sel,
-                                 mode == MB_MODE_ALG1 ? ws.sets() : nullptr, ws.m(), nullptr, s));
+                                 mode == MB_MODE_ALG1 ? ws.sets() : nullptr, ws.m(), nullptr,
+                                 mode == MB_MODE_ALG1 ? ws.plan() : nullptr, s));
     }
     for (int c = 0; c < nchunks; ++c) {
         rc = run_coord(chunks[c], in16, n, chunk_d[c], chunk_ld[c], mode, theta, beta, sel, ws.sets(), ws.plan(),
-                       outs[c], s);
+                       true, outs[c], s);
         if (rc != MB_OK) return rc;
     }
     return MB_OK;
@@ -473,12 +475,13 @@ int mbulyan_aggregate_ex(const float *grads, int n, int f, int64_t d, int64_t ld
     {
         StageTimer t(MB_STAGE_SELECT, s);
         uint8_t *sets = mode == MB_MODE_ALG1 ? ws.sets() : nullptr;
+        int32_t *plan = mode == MB_MODE_ALG1 ? ws.plan() : nullptr;   // written by the selection as well
         if (deferred)
-            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, theta, sel, sets, ws.m(), s));
+            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, theta, sel, sets, ws.m(), plan, s));
         else
-            MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, sel, sets, ws.m(), nullptr, s));
+            MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, sel, sets, ws.m(), nullptr, plan, s));
     }
-    return run_coord(grads, 0, n, d, ld, mode, theta, beta, sel, ws.sets(), ws.plan(), out, s);
+    return run_coord(grads, 0, n, d, ld, mode, theta, beta, sel, ws.sets(), ws.plan(), true, out, s);
 }
 
 int mbulyan_aggregate(const float *grads, int n, int f, int64_t d, float *out, int32_t *selected_idx,
@@ -507,9 +510,9 @@ int multikrum_aggregate(const float *grads, int n, int f, int64_t d, int64_t ld,
     {
         StageTimer t(MB_STAGE_SELECT, s);
         if (deferred)
-            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, 1, ws.sel(), mask, ws.m(), s));
+            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, 1, ws.sel(), mask, ws.m(), nullptr, s));
         else
-            MB_HIP(mb::launch_select(ws.dist(), n, f, 1, nullptr, ws.sel(), mask, ws.m(), nullptr, s));
+            MB_HIP(mb::launch_select(ws.dist(), n, f, 1, nullptr, ws.sel(), mask, ws.m(), nullptr, nullptr, s));
     }
     {
         StageTimer t(MB_STAGE_COORD, s);
@@ -554,7 +557,7 @@ int coordwise_trimmed_avg_bf16(const uint16_t *grads, int n, int64_t d, int64_t 
         if (wrc != MB_OK) return wrc;
     }
     return run_coord(grads, 1, n, d, ld, agr_sets ? MB_MODE_ALG1 : MB_MODE_SELECTED, theta, beta, selected_idx,
-                     agr_sets, agr_sets ? ws.plan() : nullptr, out, (hipStream_t)stream);
+                     agr_sets, agr_sets ? ws.plan() : nullptr, false, out, (hipStream_t)stream);
 }
 
 int multikrum_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d, int64_t ld, float *out,
@@ -576,9 +579,9 @@ int multikrum_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d, int
     {
         StageTimer t(MB_STAGE_SELECT, s);
         if (deferred)
-            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, 1, ws.sel(), mask, ws.m(), s));
+            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, 1, ws.sel(), mask, ws.m(), nullptr, s));
         else
-            MB_HIP(mb::launch_select(ws.dist(), n, f, 1, nullptr, ws.sel(), mask, ws.m(), nullptr, s));
+            MB_HIP(mb::launch_select(ws.dist(), n, f, 1, nullptr, ws.sel(), mask, ws.m(), nullptr, nullptr, s));
     }
     {
         StageTimer t(MB_STAGE_COORD, s);
@@ -621,12 +624,13 @@ int mbulyan_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d, int64
     {
         StageTimer t(MB_STAGE_SELECT, s);
         uint8_t *sets = mode == MB_MODE_ALG1 ? ws.sets() : nullptr;
+        int32_t *plan = mode == MB_MODE_ALG1 ? ws.plan() : nullptr;   // written by the selection as well
         if (deferred)
-            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, theta, sel, sets, ws.m(), s));
+            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, theta, sel, sets, ws.m(), plan, s));
         else
-            MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, sel, sets, ws.m(), nullptr, s));
+            MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, sel, sets, ws.m(), nullptr, plan, s));
     }
-    return run_coord(grads, 1, n, d, ld, mode, theta, beta, sel, ws.sets(), ws.plan(), out, s);
+    return run_coord(grads, 1, n, d, ld, mode, theta, beta, sel, ws.sets(), ws.plan(), true, out, s);
 }
 
 int mbulyan_timing_enable(int on)

@@ -46,13 +46,16 @@ hipError_t launch_finalize_gram(const double *reduced, int n, double *dist, int 
 
 // ---- selection -----------------------------------------------------------
 // rounds >= 1: multi-Krum rounds; scores_out (may be null) gets the scores of the first round.
+// plan (may be null; needs sel and agr_sets): kPlanWords words that get the plan of the
+// Algorithm-1 coordinate pass for the result, as launch_alg1_plan(n, rounds, sel, agr_sets, plan)
+// would write it.
 hipError_t launch_select(const double *dist, int n, int f, int rounds, const uint8_t *active_in,
-                         int32_t *sel, uint8_t *agr_sets, int32_t *m_out, double *scores_out,
+                         int32_t *sel, uint8_t *agr_sets, int32_t *m_out, double *scores_out, int32_t *plan,
                          hipStream_t s);
 // The same starting from the reduced Gram tiles of the distance pass: the kernel forms the distance
 // matrix itself (what launch_finalize_gram would write, canon as there) and saves that launch.
 hipError_t launch_select_gram(const double *reduced, bool canon, int n, int f, int rounds, int32_t *sel,
-                              uint8_t *agr_sets, int32_t *m_out, hipStream_t s);
+                              uint8_t *agr_sets, int32_t *m_out, int32_t *plan, hipStream_t s);
 
 // ---- coordinate pass -----------------------------------------------------
 struct CoordArgs {
@@ -87,10 +90,11 @@ struct CoordAlg1Args {
     int theta;
     int beta;
     float *out;
-    int32_t *plan;           // kPlanWords words of scratch, written by launch_alg1_plan
+    int32_t *plan;           // kPlanWords words, written by launch_alg1_plan or by the selection
     int in16;
 };
-// Plan of the Algorithm-1 coordinate pass (int32 words), written by launch_alg1_plan.
+// Plan of the Algorithm-1 coordinate pass (int32 words), written by launch_alg1_plan or, for its
+// own result, by launch_select.
 // Every row that some round needs gets a slot: the winner of round t in slot t, the other rows
 // after them in ascending order (nslots in all).  delta[t][s] in {-1, 0, +1} (float bits) is the
 // change of slot s's membership from round t-1 to round t (round -1: the empty set), groups[t] has

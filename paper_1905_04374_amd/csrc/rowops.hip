@@ -6,6 +6,7 @@
 // Also here: the plan of the Algorithm-1 coordinate pass (one small kernel).
 #include <hip/hip_runtime.h>
 
+#include "alg1_plan.hpp"
 #include "mb_internal.hpp"
 
 namespace mb {
@@ -88,89 +89,15 @@ __global__ __launch_bounds__(256) void masked_mean_kernel(const void *__restrict
         if (c0 + e < d) out[c0 + e] = acc[e] * inv;
 }
 
-// Plan of the Algorithm-1 coordinate pass (layout in mb_internal.hpp).  One workgroup; the
-// membership matrix and the winners are brought into LDS first, everything else works from there.
+// The plan from sets the caller supplies (coordwise_trimmed_avg with agr_sets); the aggregate entry
+// points get theirs from select_kernel.
 constexpr int kPlanThreads = 256;
 
 __global__ __launch_bounds__(kPlanThreads) void alg1_plan_kernel(int n, int theta, const int32_t *__restrict__ sel,
                                                                  const uint8_t *__restrict__ sets,
                                                                  int32_t *__restrict__ plan)
 {
-    __shared__ unsigned char member[kMaxN * kMaxN];   // member[t * kMaxN + r]
-    __shared__ int winner[kMaxN];
-    __shared__ int slot_of[kMaxN];                    // row -> slot, -1: no round needs the row
-    __shared__ int rows[kMaxN];                       // slot -> row
-    __shared__ int nslots;
-    __shared__ int bad;
-    __shared__ int not_nested;
-    __shared__ unsigned groups[kMaxN];
-    __shared__ unsigned char used[kMaxN];             // some round's set holds the row
-    const int tid = threadIdx.x;
-    if (tid == 0) { bad = 0; not_nested = 0; }
-    if (tid < kMaxN) { slot_of[tid] = -1; groups[tid] = 0; }
-    for (int e = tid; e < theta * n; e += kPlanThreads) member[(e / n) * kMaxN + (e % n)] = sets[e] ? 1 : 0;
-    __syncthreads();
-    if (tid < theta) {
-        const int w = sel[tid];
-        const bool valid = (unsigned)w < (unsigned)n;
-        winner[tid] = valid ? w : 0;
-        if (!valid) bad = 1;
-        int m = 0;
-        bool ok = valid && member[tid * kMaxN + (valid ? w : 0)] != 0;
-        for (int r = 0; r < n; ++r) {
-            const int cur = member[tid * kMaxN + r];
-            m += cur;
-            if (tid + 1 < theta) ok = ok && (member[(tid + 1) * kMaxN + r] == ((r == w) ? 0 : cur));
-        }
-        if (!ok) not_nested = 1;
-        plan[kPlanInvM + tid] = __float_as_int(m > 0 ? 1.0f / (float)m : 0.0f);
-    }
-    __syncthreads();
-    if (tid < theta)                   // a winner that an earlier round already extracted
-        for (int u = 0; u < tid; ++u)
-            if (winner[u] == winner[tid]) bad = 1;
-    if (tid >= 64 && tid < 64 + n) {   // (another wave than the one above)
-        const int r = tid - 64;
-        int any = 0;
-        for (int u = 0; u < theta; ++u) any |= member[u * kMaxN + r];
-        used[r] = (unsigned char)any;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        int ns = 0;
-        for (int u = 0; u < theta; ++u) {          // winners first: slot t = round t
-            if (slot_of[winner[u]] < 0) slot_of[winner[u]] = ns;
-            rows[ns++] = winner[u];
-        }
-        if (!bad) {                                // (with repeated winners the slots could run past kMaxN)
-            for (int r = 0; r < n; ++r) {
-                if (slot_of[r] < 0 && used[r]) {
-                    slot_of[r] = ns;
-                    rows[ns++] = r;
-                }
-            }
-        }
-        nslots = ns;
-        plan[kPlanNSlots] = ns;
-        plan[kPlanBad] = bad;
-        plan[kPlanNested] = (!bad && !not_nested) ? 1 : 0;
-    }
-    __syncthreads();
-    const int ns = nslots;
-    if (tid < kMaxN) plan[kPlanRows + tid] = tid < ns ? rows[tid] : 0;
-    for (int e = tid; e < kMaxN * kMaxN; e += kPlanThreads) {
-        const int t = e / kMaxN, s = e % kMaxN;
-        float dl = 0.0f;
-        if (!bad && t < theta && s < ns && slot_of[rows[s]] == s) {   // a row counts in its first slot only
-            const int cur = member[t * kMaxN + rows[s]];
-            const int prev = t > 0 ? member[(t - 1) * kMaxN + rows[s]] : 0;
-            dl = (float)(cur - prev);
-        }
-        plan[kPlanDelta + e] = __float_as_int(dl);
-        if (dl != 0.0f) atomicOr(&groups[t], 1u << (s >> 3));
-    }
-    __syncthreads();
-    if (tid < kMaxN) plan[kPlanGroups + tid] = (int)groups[tid];
+    alg1_plan_body<kPlanThreads>(n, theta, sel, sets, plan, (int)threadIdx.x);
 }
 
 }  // namespace

@@ -12,6 +12,7 @@
 // gradients.
 #include <hip/hip_runtime.h>
 
+#include "alg1_plan.hpp"
 #include "mb_internal.hpp"
 
 namespace mb {
@@ -188,10 +189,12 @@ __device__ __forceinline__ void play_rounds(const Rounds &a, int i)
 
 // dist != null: the distance matrix.  Otherwise gram = the reduced Gram tiles of the distance pass,
 // and the matrix is formed here exactly as finalize_gram_kernel forms it (canon as there).
+// plan != null (needs sel and agr_sets): the plan of the Algorithm-1 coordinate pass for the
+// chosen gradients and sets is written as well, once the last round is over.
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const double *__restrict__ dist, const double *__restrict__ gram, int canon, int n, int f, int rounds,
     const uint8_t *__restrict__ active_in, int32_t *__restrict__ sel, uint8_t *__restrict__ agr_sets,
-    int32_t *__restrict__ m_out, double *__restrict__ scores_out)
+    int32_t *__restrict__ m_out, double *__restrict__ scores_out, int32_t *__restrict__ plan)
 {
     __shared__ double sD[kMaxN * kMaxN];        // first dist[i][j], then row i in ascending order
     __shared__ unsigned char sJ[kMaxN * kMaxN]; // neighbour index by rank within row i
@@ -322,30 +325,38 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const Rounds rd{sD, sJ, sR, n, f, rounds, active_in, sel, agr_sets, m_out, scores_out, sS, &sAct, sCnt};
     if (tid >= 64) {   // one wave plays the rounds; the others only help to rank the scores for the sets
         if (agr_sets) help_rounds(rd, tid >> 6, tid & 63);
-        return;
+    } else if (n <= 16) {
+        play_rounds<15>(rd, tid);
+    } else if (n <= 32) {
+        play_rounds<31>(rd, tid);
+    } else if (n <= 48) {
+        play_rounds<47>(rd, tid);
+    } else {
+        play_rounds<63>(rd, tid);
     }
-    if (n <= 16) play_rounds<15>(rd, tid);
-    else if (n <= 32) play_rounds<31>(rd, tid);
-    else if (n <= 48) play_rounds<47>(rd, tid);
-    else play_rounds<63>(rd, tid);
+    if (!plan) return;
+    __syncthreads();   // sel and agr_sets as the first wave has written them
+    alg1_plan_body<kSelThreads>(n, rounds, sel, agr_sets, plan, tid);
 }
 
 }  // namespace
 
 hipError_t launch_select(const double *dist, int n, int f, int rounds, const uint8_t *active_in,
-                         int32_t *sel, uint8_t *agr_sets, int32_t *m_out, double *scores_out,
+                         int32_t *sel, uint8_t *agr_sets, int32_t *m_out, double *scores_out, int32_t *plan,
                          hipStream_t s)
 {
+    if (plan && !(sel && agr_sets)) return hipErrorInvalidValue;
     select_kernel<<<dim3(1), dim3(kSelThreads), 0, s>>>(dist, nullptr, 0, n, f, rounds, active_in, sel, agr_sets,
-                                                        m_out, scores_out);
+                                                        m_out, scores_out, plan);
     return hipGetLastError();
 }
 
 hipError_t launch_select_gram(const double *reduced, bool canon, int n, int f, int rounds, int32_t *sel,
-                              uint8_t *agr_sets, int32_t *m_out, hipStream_t s)
+                              uint8_t *agr_sets, int32_t *m_out, int32_t *plan, hipStream_t s)
 {
+    if (plan && !(sel && agr_sets)) return hipErrorInvalidValue;
     select_kernel<<<dim3(1), dim3(kSelThreads), 0, s>>>(nullptr, reduced, canon ? 1 : 0, n, f, rounds, nullptr, sel,
-                                                        agr_sets, m_out, nullptr);
+                                                        agr_sets, m_out, nullptr, plan);
     return hipGetLastError();
 }
 
