@@ -362,6 +362,29 @@ def test_aggregate_chunked_equals_whole():
     assert_out_close(torch.cat(outs2), ref, scale)
 
 
+@pytest.mark.parametrize("in16", [False, True])
+def test_aggregate_chunked_alg1_mode(in16):
+    """Algorithm-1 mode over column chunks (one selection and one plan for all chunks) against the oracle
+    on the whole matrix, and bit-identical to itself from call to call."""
+    say("chunked alg1", in16)
+    s = W.spec(3)
+    n, f, d = s["n"], s["f"], 120_003
+    Gt = W.make(3, DEV, d=d)
+    if in16:
+        Gt = Gt.to(torch.bfloat16)
+    G = Gt.float().cpu().numpy()
+    theta, beta = O.params(n, f, O.MODE_ALG1)
+    ext, sets, m = O.multikrum_select(O.pairwise_sqdist(G), f, theta)
+    ref, scale, margin, alt = O.coordwise_alg1(G, ext, sets, beta, want_extra=True)
+    cuts = [0, 50_000, 50_002, 90_001, d] if in16 else [0, 50_000, 50_001, 90_004, d]
+    chunks = [Gt[:, a:b].contiguous() for a, b in zip(cuts[:-1], cuts[1:])]
+    outs, sel = mb.mbulyan_aggregate_chunked(chunks, f, mode=mb.MODE_ALG1)
+    assert sel.cpu().numpy().tolist() == ext.tolist()
+    assert alg1_compare(torch.cat(outs), ref, scale, margin, alt) <= max(2, d // 1000)
+    outs2, sel2 = mb.mbulyan_aggregate_chunked(chunks, f, mode=mb.MODE_ALG1)
+    assert torch.equal(sel, sel2) and torch.equal(torch.cat(outs), torch.cat(outs2))
+
+
 def test_explicit_theta_beta_and_no_byzantine():
     say("explicit theta/beta, f=0")
     rng = np.random.default_rng(3)
