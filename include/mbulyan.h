@@ -27,6 +27,9 @@
  *   - Arguments are validated on the host before anything is launched; an
  *     invalid call launches nothing.
  *   - Calls that share a workspace (or the internal one) must not overlap.
+ *     Host threads may call concurrently with workspaces of their own; the
+ *     internal workspace is one per device and is shared by every call that
+ *     passes none.
  */
 #ifndef MBULYAN_H
 #define MBULYAN_H
