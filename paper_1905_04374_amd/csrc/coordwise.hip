@@ -65,27 +65,28 @@ __device__ __forceinline__ float closest_sum(const float (&v)[THETA], int K, boo
                 }
             }
         } else {
-            // rank of every candidate in the merged order, by counting
+            // Rank of every left candidate in the merged order, by counting.  The ranks are a
+            // permutation and both sides are sorted, so the K closest are the first `na` on the left
+            // and the first K - na on the right.
             float dL[H], dR[H];
 #pragma unroll
             for (int a = 0; a < H; ++a) {
                 dL[a] = med - v[H - 1 - a];
                 dR[a] = v[H + (ODD ? 1 : 0) + a] - med;
             }
+            int na = 0;
 #pragma unroll
             for (int a = 0; a < H; ++a) {
                 int rank = a;
 #pragma unroll
                 for (int b = 0; b < H; ++b) rank += (dR[b] < dL[a]) ? 1 : 0;
-                sum += (rank < K) ? v[H - 1 - a] : 0.0f;
+                na += (rank < K) ? 1 : 0;
             }
+            const int nb = K - na;
 #pragma unroll
-            for (int b = 0; b < H; ++b) {
-                int rank = b;
+            for (int a = 0; a < H; ++a) sum += (a < na) ? v[H - 1 - a] : 0.0f;
 #pragma unroll
-                for (int a = 0; a < H; ++a) rank += (dL[a] <= dR[b]) ? 1 : 0;
-                sum += (rank < K) ? v[H + (ODD ? 1 : 0) + b] : 0.0f;
-            }
+            for (int b = 0; b < H; ++b) sum += (b < nb) ? v[H + (ODD ? 1 : 0) + b] : 0.0f;
         }
     }
     return sum;
