@@ -385,6 +385,28 @@ def test_aggregate_chunked_alg1_mode(in16):
     assert torch.equal(sel, sel2) and torch.equal(torch.cat(outs), torch.cat(outs2))
 
 
+@pytest.mark.parametrize("in16", [False, True])
+@pytest.mark.parametrize("mode", ["selected", "alg1"])
+def test_scaling_by_a_power_of_two_is_exact(mode, in16):
+    """Every operation of the path commutes exactly with a scaling of all gradients by a power of two
+    (the bf16 pieces, the fp32 and fp64 sums, the comparisons, the weights 1/beta and 1/|set|): the
+    same gradients are chosen and the output scales bit for bit.  Holds at any size."""
+    say("scaling", mode, in16)
+    s = W.spec(3)
+    Gt = W.make(3, DEV, d=1_000_003)
+    if in16:
+        Gt = Gt.to(torch.bfloat16)
+    m = mb.MODE_ALG1 if mode == "alg1" else mb.MODE_SELECTED
+    out, sel = mb.mbulyan_aggregate_ex(Gt, s["f"], mode=m)
+    for factor in (4.0, 0.125):
+        out_s, sel_s = mb.mbulyan_aggregate_ex(Gt * factor, s["f"], mode=m)
+        assert torch.equal(sel_s, sel)
+        assert torch.equal(out_s, out * factor)
+    mk, mask = mb.multikrum_aggregate(Gt, s["f"])
+    mk_s, mask_s = mb.multikrum_aggregate(Gt * 4.0, s["f"])
+    assert torch.equal(mask_s, mask) and torch.equal(mk_s, mk * 4.0)
+
+
 def test_explicit_theta_beta_and_no_byzantine():
     say("explicit theta/beta, f=0")
     rng = np.random.default_rng(3)
