@@ -124,6 +124,35 @@ int mbulyan_aggregate_ex(const float *grads, int n, int f, int64_t d,
                          size_t ws_bytes, void *stream);
 
 /*
+ * mbulyan_aggregate_ex for callers that cannot allocate device memory or let
+ * the library do it: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same kernels, same results; the workspace
+ * is a device array of MB_NOALLOC_SCRATCH_BYTES that is part of the library
+ * itself (every GPU the library runs on holds it until the process ends), so
+ * the call allocates and frees nothing, on the device or through any library.
+ * theta and beta are the mode's defaults.
+ *   grads, out, selected_idx   as for mbulyan_aggregate_ex (selected_idx may
+ *                              be NULL)
+ * Limits: n <= MB_MAX_N (MB_EUNSUPPORTED beyond, nothing launched), any d: the
+ * distance pass is launched with no more workgroups than the array has room
+ * for (16 MiB hold the partial sums of at least 815 of them at n = 64, more
+ * than stay resident on the device).  MB_EWORKSPACE if the array could not
+ * hold one workgroup's sums (cannot happen with the sizes above).
+ * The first call on a device looks up the address of that device's copy of the
+ * array (the HIP runtime places the library's device variables at that point);
+ * no later call touches the allocator.
+ * All calls on one GPU share that GPU's array, which keeps the contents of the
+ * last call (nothing in it has to start at zero: every stage reads only what
+ * the stage before it wrote in the same call): calls that overlap on one GPU (different streams or threads)
+ * race and must be serialised by the caller.  Per-stage timing
+ * (mbulyan_timing_enable) does not see these calls.
+ */
+#define MB_NOALLOC_SCRATCH_BYTES (16u << 20)
+int mbulyan_aggregate_noalloc(const float *grads, int n, int f, int64_t d,
+                              int64_t ld, int mode, float *out,
+                              int32_t *selected_idx, void *stream);
+
+/*
  * The same rule over a matrix given as column chunks (for d too large for one
  * buffer): chunk c holds columns [sum of chunk_d[0..c), +chunk_d[c]) as n rows
  * of stride chunk_ld[c], and its part of the result goes to outs[c].

@@ -28,6 +28,7 @@ EXPORTS = [
     "mbulyan_timing_reset", "mbulyan_timing_read", "mbulyan_release",
     "pairwise_sqdist_bf16", "coordwise_trimmed_avg_bf16", "mbulyan_aggregate_bf16",
     "mbulyan_aggregate_chunked_bf16", "multikrum_aggregate_bf16", "coordwise_median_bf16",
+    "mbulyan_aggregate_noalloc",
 ]
 
 
@@ -53,6 +54,7 @@ def _load() -> C.CDLL:
     lib.mbulyan_set_dist_algo.argtypes = [ci]
     lib.mbulyan_aggregate.argtypes = [vp, ci, ci, i64, vp, vp, vp]
     lib.mbulyan_aggregate_ex.argtypes = [vp, ci, ci, i64, i64, ci, ci, ci, vp, vp, vp, sz, vp]
+    lib.mbulyan_aggregate_noalloc.argtypes = [vp, ci, ci, i64, i64, ci, vp, vp, vp]
     lib.mbulyan_aggregate_chunked.argtypes = [C.POINTER(vp), ci, C.POINTER(i64), C.POINTER(i64), ci, ci, ci,
                                               C.POINTER(vp), vp, vp, sz, vp]
     lib.pairwise_sqdist.argtypes = [vp, ci, i64, i64, vp, ci, ci, vp, sz, vp]
@@ -172,6 +174,15 @@ def mbulyan_aggregate_ex(grads, f, mode=MODE_SELECTED, theta=0, beta=0, out=None
         return out, selected_idx
     _check(lib.mbulyan_aggregate_ex(p, n, f, d, ld, mode, theta, beta, _dev(out, torch.float32, "out"),
                                     _dev(selected_idx, torch.int32, "selected_idx"), wp, wb, _stream(stream)))
+    return out, selected_idx
+
+
+def mbulyan_aggregate_noalloc(grads, f, out, selected_idx=None, mode=MODE_SELECTED, stream=None):
+    """mbulyan_aggregate_ex on the library's static device array: the call allocates nothing, so the
+    caller passes `out` (and `selected_idx`, if wanted).  Returns (out, selected_idx)."""
+    p, n, d, ld = _matrix(grads)
+    _check(lib.mbulyan_aggregate_noalloc(p, n, f, d, ld, mode, _dev(out, torch.float32, "out"),
+                                         _dev(selected_idx, torch.int32, "selected_idx"), _stream(stream)))
     return out, selected_idx
 
 

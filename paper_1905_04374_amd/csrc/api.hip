@@ -41,6 +41,13 @@ static_assert(mb::kPlanWords * sizeof(int32_t) <= kPlanBytes, "plan segment");
 
 struct Workspace {
     char *base;
+    size_t bytes;   // of the whole workspace: what follows kOffPartials holds the distance pass's partial sums
+    // workgroups whose partial sums (stride doubles each) fit
+    int max_blocks(int stride) const
+    {
+        const size_t room = bytes > kOffPartials ? (bytes - kOffPartials) / ((size_t)stride * sizeof(double)) : 0;
+        return room > (size_t)mb::kGramMaxBlocks ? mb::kGramMaxBlocks : (int)room;
+    }
     double *dist() const { return reinterpret_cast<double *>(base + kOffDist); }
     double *reduced() const { return reinterpret_cast<double *>(base + kOffReduced); }
     int32_t *sel() const { return reinterpret_cast<int32_t *>(base + kOffSel); }
@@ -94,6 +101,7 @@ int own_workspace(size_t need, Workspace *ws)
         o.bytes = need;
     }
     ws->base = static_cast<char *>(o.ptr);
+    ws->bytes = o.bytes;
     return MB_OK;
 }
 
@@ -103,6 +111,7 @@ int get_workspace(void *user, size_t user_bytes, int n, int64_t d, Workspace *ws
     if (user) {
         if ((uintptr_t)user % 256 != 0 || user_bytes < need) return MB_EWORKSPACE;
         ws->base = static_cast<char *>(user);
+        ws->bytes = user_bytes;
         return MB_OK;
     }
     return own_workspace(need, ws);
@@ -114,6 +123,7 @@ struct Span {
     hipEvent_t a, b;
 };
 bool g_timing = false;
+thread_local bool tl_no_timing = false;   // set while an entry point that must not create events runs
 std::vector<Span> g_spans;
 double g_ms[MB_NUM_STAGES] = {0, 0, 0, 0};
 int64_t g_launches[MB_NUM_STAGES] = {0, 0, 0, 0};
@@ -122,7 +132,7 @@ struct StageTimer {
     bool on;
     Span sp;
     hipStream_t s;
-    StageTimer(int stage, hipStream_t stream) : on(g_timing), s(stream)
+    StageTimer(int stage, hipStream_t stream) : on(g_timing && !tl_no_timing), s(stream)
     {
         if (!on) return;
         sp.stage = stage;
@@ -173,7 +183,9 @@ int run_dist_in16(const uint16_t *grads, int n, int64_t d, int64_t ld, double *d
     int nblocks = 0;
     {
         StageTimer t(MB_STAGE_DIST, s);
-        MB_HIP(mb::launch_dist_gram_in16(grads, n, d, ld, ws.partials(), &nblocks, s));
+        const int room = ws.max_blocks(slots);
+        if (room < 1) return MB_EWORKSPACE;
+        MB_HIP(mb::launch_dist_gram_in16(grads, n, d, ld, ws.partials(), room, &nblocks, s));
     }
     StageTimer t(MB_STAGE_REDUCE, s);
     MB_HIP(mb::launch_reduce(ws.partials(), nblocks, slots, slots, ws.reduced(), s));
@@ -193,6 +205,9 @@ int run_dist(const float *grads, int n, int64_t d, int64_t ld, double *dist, int
     int nblocks = mb::dist_grid_blocks(d, algo);
     if (algo == MB_DIST_DIRECT) {
         const int nb = (n + 7) / 8, slots = nb * (nb + 1) / 2 * 64;
+        const int room = ws.max_blocks(mb::kDirectSlots);
+        if (room < 1) return MB_EWORKSPACE;
+        nblocks = nblocks < room ? nblocks : room;
         {
             StageTimer t(MB_STAGE_DIST, s);
             MB_HIP(mb::launch_dist_direct(grads, n, d, ld, ws.partials(), nblocks, s));
@@ -204,7 +219,9 @@ int run_dist(const float *grads, int n, int64_t d, int64_t ld, double *dist, int
         const int slots = mb::gram_slots(n);
         {
             StageTimer t(MB_STAGE_DIST, s);
-            MB_HIP(mb::launch_dist_gram(grads, n, d, ld, ws.partials(), algo == MB_DIST_GRAM_BF16, &nblocks, s));
+            const int room = ws.max_blocks(slots);
+            if (room < 1) return MB_EWORKSPACE;
+            MB_HIP(mb::launch_dist_gram(grads, n, d, ld, ws.partials(), algo == MB_DIST_GRAM_BF16, room, &nblocks, s));
         }
         StageTimer t(MB_STAGE_REDUCE, s);
         MB_HIP(mb::launch_reduce(ws.partials(), nblocks, slots, slots, ws.reduced(), s));
@@ -388,7 +405,7 @@ int coordwise_trimmed_avg(const float *grads, int n, int64_t d, int64_t ld, cons
     const int rc = check_matrix(grads, n, d, ld);
     if (rc != MB_OK) return rc;
     if (!selected_idx || !out || theta < 1 || theta > n || beta < 1 || beta > theta) return MB_EINVAL;
-    Workspace ws{nullptr};
+    Workspace ws{nullptr, 0};
     if (agr_sets) {   // the Algorithm-1 pass keeps its plan in the library's own workspace
         const int wrc = own_workspace(kOffPartials, &ws);
         if (wrc != MB_OK) return wrc;
@@ -454,22 +471,13 @@ int mbulyan_aggregate_chunked_bf16(const uint16_t *const *chunks, int nchunks, c
                              mode, outs, selected_idx, workspace, ws_bytes, stream);
 }
 
-int mbulyan_aggregate_ex(const float *grads, int n, int f, int64_t d, int64_t ld, int mode, int theta,
-                         int beta, float *out, int32_t *selected_idx, void *workspace, size_t ws_bytes,
-                         void *stream)
+// distance pass, reduction, selection, coordinate pass of one fp32 matrix on the workspace `ws`
+static int aggregate_on(const Workspace &ws, const float *grads, int n, int f, int64_t d, int64_t ld, int mode,
+                        int theta, int beta, float *out, int32_t *selected_idx, hipStream_t s)
 {
-    int rc = check_matrix(grads, n, d, ld);
-    if (rc != MB_OK) return rc;
-    if (!out) return MB_EINVAL;
-    rc = resolve_params(n, f, mode, &theta, &beta);
-    if (rc != MB_OK) return rc;
-    Workspace ws;
-    rc = get_workspace(workspace, ws_bytes, n, d, &ws);
-    if (rc != MB_OK) return rc;
-    hipStream_t s = (hipStream_t)stream;
     int deferred = 0;
     bool canon = false;
-    rc = run_dist(grads, n, d, ld, ws.dist(), 0, MB_DIST_AUTO, ws, s, &deferred, &canon);
+    int rc = run_dist(grads, n, d, ld, ws.dist(), 0, MB_DIST_AUTO, ws, s, &deferred, &canon);
     if (rc != MB_OK) return rc;
     int32_t *sel = selected_idx ? selected_idx : ws.sel();   // the selection writes the caller's list in place
     {
@@ -482,6 +490,72 @@ int mbulyan_aggregate_ex(const float *grads, int n, int f, int64_t d, int64_t ld
             MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, sel, sets, ws.m(), nullptr, plan, s));
     }
     return run_coord(grads, 0, n, d, ld, mode, theta, beta, sel, ws.sets(), ws.plan(), true, out, s);
+}
+
+int mbulyan_aggregate_ex(const float *grads, int n, int f, int64_t d, int64_t ld, int mode, int theta,
+                         int beta, float *out, int32_t *selected_idx, void *workspace, size_t ws_bytes,
+                         void *stream)
+{
+    int rc = check_matrix(grads, n, d, ld);
+    if (rc != MB_OK) return rc;
+    if (!out) return MB_EINVAL;
+    rc = resolve_params(n, f, mode, &theta, &beta);
+    if (rc != MB_OK) return rc;
+    Workspace ws;
+    rc = get_workspace(workspace, ws_bytes, n, d, &ws);
+    if (rc != MB_OK) return rc;
+    return aggregate_on(ws, grads, n, f, d, ld, mode, theta, beta, out, selected_idx, (hipStream_t)stream);
+}
+
+// ---- the same with nothing allocated: the workspace is a device array of the library itself ----
+// Every device that loads the library holds its own copy of the array at its own address; the
+// address is looked up once per device (with that device current) and used from then on.  The
+// array's name in host code is only a handle for that lookup, never a pointer to pass on.
+constexpr size_t kScratchBytes = (size_t)MB_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+static_assert(kScratchBytes > kOffPartials + (size_t)mb::gram_slots(MB_MAX_N) * sizeof(double),
+              "room for the fixed segments and at least one workgroup's partial sums");
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices] = {};   // guarded by g_mu
+
+static int scratch_workspace(Workspace *ws)
+{
+    int dev = 0;
+    MB_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return hip_fail(hipErrorInvalidDevice);
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        MB_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || (uintptr_t)p % 256 != 0) return hip_fail(hipErrorInvalidSymbol);
+        g_scratch_ptr[dev] = p;
+    }
+    ws->base = static_cast<char *>(g_scratch_ptr[dev]);
+    ws->bytes = kScratchBytes;
+    return MB_OK;
+}
+
+int mbulyan_aggregate_noalloc(const float *grads, int n, int f, int64_t d, int64_t ld, int mode, float *out,
+                              int32_t *selected_idx, void *stream)
+{
+    int rc = check_matrix(grads, n, d, ld);   // n > MB_MAX_N: MB_EUNSUPPORTED, nothing is launched
+    if (rc != MB_OK) return rc;
+    if (!out) return MB_EINVAL;
+    int theta = 0, beta = 0;
+    rc = resolve_params(n, f, mode, &theta, &beta);
+    if (rc != MB_OK) return rc;
+    Workspace ws;
+    rc = scratch_workspace(&ws);
+    if (rc != MB_OK) return rc;
+    if (ws.max_blocks(mb::gram_slots(n)) < 1) return MB_EWORKSPACE;
+    // Nothing in the array has to start at zero: the distance pass overwrites the partial sums of
+    // every workgroup it launches, and every later stage reads only what the stage before it wrote
+    // in this call.  No timing events either (creating one may allocate).
+    struct Quiet {
+        Quiet() { tl_no_timing = true; }
+        ~Quiet() { tl_no_timing = false; }
+    } quiet;
+    return aggregate_on(ws, grads, n, f, d, ld, mode, theta, beta, out, selected_idx, (hipStream_t)stream);
 }
 
 int mbulyan_aggregate(const float *grads, int n, int f, int64_t d, float *out, int32_t *selected_idx,
@@ -551,7 +625,7 @@ int coordwise_trimmed_avg_bf16(const uint16_t *grads, int n, int64_t d, int64_t 
     const int rc = check_matrix(grads, n, d, ld);
     if (rc != MB_OK) return rc;
     if (!selected_idx || !out || theta < 1 || theta > n || beta < 1 || beta > theta) return MB_EINVAL;
-    Workspace ws{nullptr};
+    Workspace ws{nullptr, 0};
     if (agr_sets) {   // the Algorithm-1 pass keeps its plan in the library's own workspace
         const int wrc = own_workspace(kOffPartials, &ws);
         if (wrc != MB_OK) return wrc;

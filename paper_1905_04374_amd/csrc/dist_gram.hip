@@ -33,6 +33,8 @@
 // order by reduce_partials_kernel.  No atomics: the result is a function of the data only.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "mb_internal.hpp"
 
 namespace mb {
@@ -563,36 +565,59 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
     for (int t = 0; t < NT; ++t) out[t * 256 + tid] = total[t];
 }
 
-template <int NB, int KIND, int L>
-hipError_t launch_dma_l(const void *G, int n, int64_t d, int64_t ld, bool aligned, double *partials, int *nblocks,
-                        hipStream_t s)
+// What the host knows about one kernel on one device: whether the LDS limit has been raised and how
+// many workgroups stay resident.  Kept per device (the attribute and the occupancy are the
+// device's) and behind a mutex (host threads may call concurrently).
+constexpr int kMaxDevices = 64;
+std::mutex g_launch_mu;
+
+inline hipError_t current_device(int *dev)
 {
-    static bool prepared = false;
-    static int resident[65] = {0};   // workgroups the device holds at once, by n (LDS use grows with n)
+    const hipError_t e = hipGetDevice(dev);
+    if (e != hipSuccess) return e;
+    return (*dev >= 0 && *dev < kMaxDevices) ? hipSuccess : hipErrorInvalidDevice;
+}
+
+template <int NB, int KIND, int L>
+hipError_t launch_dma_l(const void *G, int n, int64_t d, int64_t ld, bool aligned, double *partials, int max_blocks,
+                        int *nblocks, hipStream_t s)
+{
+    struct PerDevice {
+        bool prepared;
+        int resident[65];   // workgroups the device holds at once, by n (LDS use grows with n)
+    };
+    static PerDevice cache[kMaxDevices] = {};
     hipError_t e;
-    if (!prepared) {
-        if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gram_dma_kernel<NB, KIND, L>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)dma_lds_bytes(16 * NB))) !=
-            hipSuccess)
-            return e;
-        prepared = true;
-    }
+    int dev = 0;
+    if ((e = current_device(&dev)) != hipSuccess) return e;
     const size_t bytes = dma_lds_bytes(n);
-    if (!resident[n]) {
-        int dev = 0, cus = 0, per_cu = 0;
-        if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
-        if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
-        if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gram_dma_kernel<NB, KIND, L>, kThreads,
-                                                              bytes)) != hipSuccess)
-            return e;
-        resident[n] = cus * (per_cu < 1 ? 1 : per_cu);
+    int resident = 0;
+    {
+        std::lock_guard<std::mutex> lock(g_launch_mu);
+        PerDevice &c = cache[dev];
+        if (!c.prepared) {
+            if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gram_dma_kernel<NB, KIND, L>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (int)dma_lds_bytes(16 * NB))) != hipSuccess)
+                return e;
+            c.prepared = true;
+        }
+        if (!c.resident[n]) {
+            int cus = 0, per_cu = 0;
+            if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+            if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gram_dma_kernel<NB, KIND, L>, kThreads,
+                                                                  bytes)) != hipSuccess)
+                return e;
+            c.resident[n] = cus * (per_cu < 1 ? 1 : per_cu);
+        }
+        resident = c.resident[n];
     }
     // at least four tiles per workgroup: with fewer, writing and adding up the partial tiles costs
     // more than the distance pass itself
     constexpr int TC = tile_cols<KIND>();
     const int64_t tiles = aligned ? d / TC : 0;
     const int64_t work = aligned ? tiles : (d + TC - 1) / TC;   // element loads: a workgroup per TC columns
-    int64_t g = resident[n] < kGramMaxBlocks ? resident[n] : kGramMaxBlocks;
+    int64_t g = resident < max_blocks ? resident : max_blocks;
     if (work < 4 * g) g = work < 4 ? 1 : work / 4;
     *nblocks = (int)g;
     gram_dma_kernel<NB, KIND, L><<<dim3((unsigned)g), dim3(kThreads), bytes, s>>>(G, n, d, ld, tiles, partials);
@@ -600,13 +625,13 @@ hipError_t launch_dma_l(const void *G, int n, int64_t d, int64_t ld, bool aligne
 }
 
 template <int NB, int KIND>
-hipError_t launch_dma(const void *G, int n, int64_t d, int64_t ld, bool aligned, double *partials, int *nblocks,
-                      hipStream_t s)
+hipError_t launch_dma(const void *G, int n, int64_t d, int64_t ld, bool aligned, double *partials, int max_blocks,
+                      int *nblocks, hipStream_t s)
 {
     // load instructions per wave and tile: ceil(pairs / 4), one of two values for each NB
     if ((dma_pairs(n) + 3) / 4 == 2 * NB)
-        return launch_dma_l<NB, KIND, 2 * NB>(G, n, d, ld, aligned, partials, nblocks, s);
-    return launch_dma_l<NB, KIND, 2 * NB - 1>(G, n, d, ld, aligned, partials, nblocks, s);
+        return launch_dma_l<NB, KIND, 2 * NB>(G, n, d, ld, aligned, partials, max_blocks, nblocks, s);
+    return launch_dma_l<NB, KIND, 2 * NB - 1>(G, n, d, ld, aligned, partials, max_blocks, nblocks, s);
 }
 
 template <int NB, bool BF16, int DEPTH>
@@ -621,25 +646,26 @@ hipError_t launch_one(const float *G, int n, int64_t d, int64_t ld, double *part
 template <int NB, bool BF16, int DEPTH>
 int resident_blocks()
 {
-    static int cached = 0;
-    if (cached) return cached;
+    static int cache[kMaxDevices] = {};
     int dev = 0, cus = 0, per_cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 1024;
+    if (current_device(&dev) != hipSuccess) return 1024;
+    std::lock_guard<std::mutex> lock(g_launch_mu);
+    if (cache[dev]) return cache[dev];
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 1024;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gram_kernel<NB, BF16, DEPTH>, kThreads, 0) !=
         hipSuccess)
         return 1024;
     if (per_cu < 1) per_cu = 1;
-    cached = cus * per_cu;
-    return cached;
+    cache[dev] = cus * per_cu;
+    return cache[dev];
 }
 
 template <int NB, bool BF16, int DEPTH>
-int grid_for(int64_t d)
+int grid_for(int64_t d, int max_blocks)
 {
     const int64_t steps = (d + 4 * kCols - 1) / (4 * kCols);   // one step for each of the 4 waves
     int64_t g = resident_blocks<NB, BF16, DEPTH>();
-    if (g > kGramMaxBlocks) g = kGramMaxBlocks;
+    if (g > max_blocks) g = max_blocks;
     if (steps < g) g = steps < 1 ? 1 : steps;
     return (int)g;
 }
@@ -651,48 +677,52 @@ struct Depth {
 };
 
 template <int NB, bool BF16>
-hipError_t launch_nb(const float *G, int n, int64_t d, int64_t ld, double *partials, int *nblocks,
+hipError_t launch_nb(const float *G, int n, int64_t d, int64_t ld, double *partials, int max_blocks, int *nblocks,
                      hipStream_t s)
 {
     if (((uintptr_t)G % 16 == 0) && (ld % 4 == 0) && d >= kTile)
-        return launch_dma<NB, BF16 ? kSplit : kFp32>(G, n, d, ld, true, partials, nblocks, s);
+        return launch_dma<NB, BF16 ? kSplit : kFp32>(G, n, d, ld, true, partials, max_blocks, nblocks, s);
     constexpr int D = Depth<NB, BF16>::value;
-    *nblocks = grid_for<NB, BF16, D>(d);
+    *nblocks = grid_for<NB, BF16, D>(d, max_blocks);
     return launch_one<NB, BF16, D>(G, n, d, ld, partials, *nblocks, s);
 }
 
 }  // namespace
 
-hipError_t launch_dist_gram_in16(const uint16_t *G, int n, int64_t d, int64_t ld, double *partials, int *nblocks,
-                                 hipStream_t s)
+hipError_t launch_dist_gram_in16(const uint16_t *G, int n, int64_t d, int64_t ld, double *partials, int max_blocks,
+                                 int *nblocks, hipStream_t s)
 {
+    if (max_blocks < 1) return hipErrorInvalidValue;
+    if (max_blocks > kGramMaxBlocks) max_blocks = kGramMaxBlocks;
     const bool aligned = ((uintptr_t)G % 16 == 0) && (ld % 8 == 0) && d >= tile_cols<kIn16>();
     switch (gram_blocks(n)) {
-        case 1: return launch_dma<1, kIn16>(G, n, d, ld, aligned, partials, nblocks, s);
-        case 2: return launch_dma<2, kIn16>(G, n, d, ld, aligned, partials, nblocks, s);
-        case 3: return launch_dma<3, kIn16>(G, n, d, ld, aligned, partials, nblocks, s);
-        case 4: return launch_dma<4, kIn16>(G, n, d, ld, aligned, partials, nblocks, s);
+        case 1: return launch_dma<1, kIn16>(G, n, d, ld, aligned, partials, max_blocks, nblocks, s);
+        case 2: return launch_dma<2, kIn16>(G, n, d, ld, aligned, partials, max_blocks, nblocks, s);
+        case 3: return launch_dma<3, kIn16>(G, n, d, ld, aligned, partials, max_blocks, nblocks, s);
+        case 4: return launch_dma<4, kIn16>(G, n, d, ld, aligned, partials, max_blocks, nblocks, s);
     }
     return hipErrorInvalidValue;
 }
 
 hipError_t launch_dist_gram(const float *G, int n, int64_t d, int64_t ld, double *partials, bool bf16,
-                            int *nblocks, hipStream_t s)
+                            int max_blocks, int *nblocks, hipStream_t s)
 {
+    if (max_blocks < 1) return hipErrorInvalidValue;
+    if (max_blocks > kGramMaxBlocks) max_blocks = kGramMaxBlocks;
     const int nb = gram_blocks(n);
     if (bf16) {
         switch (nb) {
-            case 1: return launch_nb<1, true>(G, n, d, ld, partials, nblocks, s);
-            case 2: return launch_nb<2, true>(G, n, d, ld, partials, nblocks, s);
-            case 3: return launch_nb<3, true>(G, n, d, ld, partials, nblocks, s);
-            case 4: return launch_nb<4, true>(G, n, d, ld, partials, nblocks, s);
+            case 1: return launch_nb<1, true>(G, n, d, ld, partials, max_blocks, nblocks, s);
+            case 2: return launch_nb<2, true>(G, n, d, ld, partials, max_blocks, nblocks, s);
+            case 3: return launch_nb<3, true>(G, n, d, ld, partials, max_blocks, nblocks, s);
+            case 4: return launch_nb<4, true>(G, n, d, ld, partials, max_blocks, nblocks, s);
         }
     } else {
         switch (nb) {
-            case 1: return launch_nb<1, false>(G, n, d, ld, partials, nblocks, s);
-            case 2: return launch_nb<2, false>(G, n, d, ld, partials, nblocks, s);
-            case 3: return launch_nb<3, false>(G, n, d, ld, partials, nblocks, s);
-            case 4: return launch_nb<4, false>(G, n, d, ld, partials, nblocks, s);
+            case 1: return launch_nb<1, false>(G, n, d, ld, partials, max_blocks, nblocks, s);
+            case 2: return launch_nb<2, false>(G, n, d, ld, partials, max_blocks, nblocks, s);
+            case 3: return launch_nb<3, false>(G, n, d, ld, partials, max_blocks, nblocks, s);
+            case 4: return launch_nb<4, false>(G, n, d, ld, partials, max_blocks, nblocks, s);
         }
     }
     return hipErrorInvalidValue;

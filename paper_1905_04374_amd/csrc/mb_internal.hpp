@@ -13,8 +13,8 @@ constexpr int kMaxN = 64;
 //   gram:   NT(NB) tiles x 256 entries, NB = ceil(n/16), NT = NB(NB+1)/2
 constexpr int kDirectSlots = 36 * 64;
 constexpr int kGramMaxBlocks = 2048;
-inline int gram_blocks(int n) { return (n + 15) / 16; }
-inline int gram_slots(int n) { int nb = gram_blocks(n); return nb * (nb + 1) / 2 * 256; }
+constexpr int gram_blocks(int n) { return (n + 15) / 16; }
+constexpr int gram_slots(int n) { return gram_blocks(n) * (gram_blocks(n) + 1) / 2 * 256; }
 
 // Element (i, j), i >= j, of the Gram matrix inside the reduced tile array.  Tile (I, J) holds
 // rows 16I.. as the A operand and rows 16J.. as the B operand; the instruction leaves entry
@@ -31,12 +31,13 @@ int dist_grid_blocks(int64_t d, int algo);
 
 hipError_t launch_dist_direct(const float *G, int n, int64_t d, int64_t ld, double *partials,
                               int nblocks, hipStream_t s);
-// launches with as many workgroups as stay resident (at most dist_grid_blocks) and reports the count
+// launches with as many workgroups as stay resident (at most dist_grid_blocks, and at most
+// max_blocks >= 1: what `partials` has room for) and reports the count
 hipError_t launch_dist_gram(const float *G, int n, int64_t d, int64_t ld, double *partials, bool bf16,
-                            int *nblocks, hipStream_t s);
+                            int max_blocks, int *nblocks, hipStream_t s);
 // the same for gradients stored as bf16 (raw 16-bit words, ld in elements)
-hipError_t launch_dist_gram_in16(const uint16_t *G, int n, int64_t d, int64_t ld, double *partials, int *nblocks,
-                                 hipStream_t s);
+hipError_t launch_dist_gram_in16(const uint16_t *G, int n, int64_t d, int64_t ld, double *partials, int max_blocks,
+                                 int *nblocks, hipStream_t s);
 // partials[nblocks][stride] -> reduced[0..slots) (fixed summation order), then -> dist[n*n]
 hipError_t launch_reduce(const double *partials, int nblocks, int stride, int slots, double *reduced,
                          hipStream_t s);

@@ -87,5 +87,10 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert lib.coordwise_trimmed_avg(one, 11, 100, 100, None, 7, 3, None, one, None) == mb.MB_EINVAL
     assert lib.multikrum_aggregate(one, 6, 2, 100, 100, one, None, None, 0, None) == mb.MB_EPRECOND
     assert lib.coordwise_median(one, 11, 100, 100, None, None) == mb.MB_EINVAL
+    # the entry point that allocates nothing: same checks, and n beyond what its static array is sized for
+    assert lib.mbulyan_aggregate_noalloc(one, 65, 0, 100, 100, 0, one, None, None) == mb.MB_EUNSUPPORTED
+    assert lib.mbulyan_aggregate_noalloc(one, 10, 2, 100, 100, 0, one, None, None) == mb.MB_EPRECOND
+    assert lib.mbulyan_aggregate_noalloc(one, 11, 2, 100, 99, 0, one, None, None) == mb.MB_EINVAL
+    assert lib.mbulyan_aggregate_noalloc(one, 11, 2, 100, 100, 0, None, None, None) == mb.MB_EINVAL
     assert lib.mbulyan_set_dist_algo(5) == mb.MB_EINVAL
     assert lib.mbulyan_set_dist_algo(0) == mb.MB_OK
