@@ -4,7 +4,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
-#include "mb_internal.hpp"
+#include "mb_coord.hpp"
 
 namespace mb {
 

@@ -12,7 +12,7 @@
 // with -DMB_IN16=1 for gradients stored as bf16.
 #include <hip/hip_runtime.h>
 
-#include "mb_internal.hpp"
+#include "mb_coord.hpp"
 #include "sortnet.hpp"
 
 #ifndef MB_GROUP

@@ -15,7 +15,7 @@
 // -DMB_IN16=1 for gradients stored as bf16.
 #include <hip/hip_runtime.h>
 
-#include "mb_internal.hpp"
+#include "mb_coord.hpp"
 #include "sortnet.hpp"
 
 #include <type_traits>
