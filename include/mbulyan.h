@@ -68,7 +68,11 @@ extern "C" {
 #define MB_DIST_AUTO 0   /* library picks */
 #define MB_DIST_DIRECT 1 /* sum of (x_i - x_j)^2 on the vector ALU, fp32 partial sums */
 #define MB_DIST_GRAM 2   /* Gram matrix on the fp32 matrix cores (MFMA), fp64 running sums,
-                            D_ij = G_ii + G_jj - 2 G_ij in fp64 */
+                            D_ij = G_ii + G_jj - 2 G_ij in fp64.  The error of that form grows with
+                            the norms, not with D_ij: where some pair has G_ii + G_jj > 256 D_ij
+                            (gradients with a large common component) a second pass repeats the
+                            Gram matrix on the rows minus a pivot row chosen among the bulk of
+                            them, and every pair takes the better-conditioned of its two values */
 #define MB_DIST_GRAM_BF16 3 /* the same Gram matrix on the bf16 matrix cores: every fp32 value is
                             split exactly into three bf16 pieces and the six significant piece
                             products are accumulated in fp32 (error of the order of one fp32
@@ -293,14 +297,18 @@ int coordwise_median(const float *grads, int n, int64_t d, int64_t ld,
  * own stream.  mbulyan_timing_enable(1) starts collecting, (0) stops.
  * mbulyan_timing_read synchronises the recorded events and returns, per stage,
  * the summed milliseconds and the number of launches since the last
- * mbulyan_timing_reset.  Stages: 0 distance pass, 1 distance reduction,
- * 2 selection, 3 coordinate pass.  Host only; not thread safe.
+ * mbulyan_timing_reset.  Stages: 0 distance pass (first pass of the Gram
+ * forms), 1 distance reduction, 2 selection, 3 coordinate pass, 4 the second
+ * pass of the Gram forms and its reduction (launched every time; a few
+ * microseconds when the first pass was well conditioned).  Both arrays have
+ * MB_NUM_STAGES entries.  Host only; not thread safe.
  */
 #define MB_STAGE_DIST 0
 #define MB_STAGE_REDUCE 1
 #define MB_STAGE_SELECT 2
 #define MB_STAGE_COORD 3
-#define MB_NUM_STAGES 4
+#define MB_STAGE_REFINE 4
+#define MB_NUM_STAGES 5
 int mbulyan_timing_enable(int on);
 int mbulyan_timing_reset(void);
 int mbulyan_timing_read(double *ms_per_stage, int64_t *launches_per_stage);

@@ -18,7 +18,7 @@ MB_MAX_N = 64
 MB_OK, MB_EINVAL, MB_EPRECOND, MB_EUNSUPPORTED, MB_EWORKSPACE, MB_EHIP = range(6)
 MODE_SELECTED, MODE_ALG1 = 0, 1
 DIST_AUTO, DIST_DIRECT, DIST_GRAM, DIST_GRAM_BF16 = 0, 1, 2, 3
-STAGES = ("dist", "reduce", "select", "coord")
+STAGES = ("dist", "reduce", "select", "coord", "refine")
 
 EXPORTS = [
     "mbulyan_strerror", "mbulyan_last_hip_error", "mbulyan_version", "mbulyan_params",

@@ -31,7 +31,9 @@ int hip_fail(hipError_t e)
 // ---- workspace layout (offsets in bytes, every segment 256-byte aligned) ----
 constexpr size_t kOffDist = 0;                                   // 64*64 doubles
 constexpr size_t kOffReduced = kOffDist + 64 * 64 * 8;           // up to 2560 doubles
-constexpr size_t kOffSel = kOffReduced + 2560 * 8;               // 64 int32
+constexpr size_t kOffReduced2 = kOffReduced + 2560 * 8;          // the same of the second (centred) pass
+constexpr size_t kOffGate = kOffReduced2 + 2560 * 8;             // flag and pivot row of the second pass
+constexpr size_t kOffSel = kOffGate + 256;                       // 64 int32
 constexpr size_t kOffM = kOffSel + 256;                          // 64 int32
 constexpr size_t kOffSets = kOffM + 256;                         // 64*64 bytes
 constexpr size_t kOffPlan = kOffSets + 4096;                     // plan of the Algorithm-1 coordinate pass
@@ -50,6 +52,8 @@ struct Workspace {
     }
     double *dist() const { return reinterpret_cast<double *>(base + kOffDist); }
     double *reduced() const { return reinterpret_cast<double *>(base + kOffReduced); }
+    double *reduced2() const { return reinterpret_cast<double *>(base + kOffReduced2); }
+    int *gate() const { return reinterpret_cast<int *>(base + kOffGate); }
     int32_t *sel() const { return reinterpret_cast<int32_t *>(base + kOffSel); }
     int32_t *m() const { return reinterpret_cast<int32_t *>(base + kOffM); }
     uint8_t *sets() const { return reinterpret_cast<uint8_t *>(base + kOffSets); }
@@ -125,8 +129,8 @@ struct Span {
 bool g_timing = false;
 thread_local bool tl_no_timing = false;   // set while an entry point that must not create events runs
 std::vector<Span> g_spans;
-double g_ms[MB_NUM_STAGES] = {0, 0, 0, 0};
-int64_t g_launches[MB_NUM_STAGES] = {0, 0, 0, 0};
+double g_ms[MB_NUM_STAGES] = {};
+int64_t g_launches[MB_NUM_STAGES] = {};
 
 struct StageTimer {
     bool on;
@@ -172,38 +176,54 @@ int check_matrix(const void *grads, int n, int64_t d, int64_t ld)
 }
 
 // distances of one matrix into ws.dist()
-// gradients stored as bf16: Gram form only (one exact bf16 product per pair and coordinate)
+// Gram form: first pass, its reduction, then the second (centred) pass and its reduction, both of
+// which find out on the device whether they are needed (gram_combine.hpp) and return at once if not.
 // `defer` (may be null): leave the last step, Gram tiles -> distance matrix, to the selection kernel
-// (it forms the matrix itself from ws.reduced()); set to 1 when that was possible, *canon as for
-// launch_finalize_gram.
-int run_dist_in16(const uint16_t *grads, int n, int64_t d, int64_t ld, double *dist, int accumulate,
-                  const Workspace &ws, hipStream_t s, int *defer = nullptr, bool *canon = nullptr)
+// (it forms the matrix itself from ws.reduced(), ws.reduced2(), ws.gate()); set to 1 when that was possible.
+// gradients stored as bf16: Gram form only (one exact bf16 product per pair and coordinate)
+int run_dist_gram(const void *grads, int in16, bool bf16, int n, int64_t d, int64_t ld, double *dist, int accumulate,
+                  const Workspace &ws, hipStream_t s, int *defer)
 {
     const int slots = mb::gram_slots(n);
-    int nblocks = 0;
-    {
-        StageTimer t(MB_STAGE_DIST, s);
-        const int room = ws.max_blocks(slots);
-        if (room < 1) return MB_EWORKSPACE;
-        MB_HIP(mb::launch_dist_gram_in16(grads, n, d, ld, ws.partials(), room, &nblocks, s));
+    const int room = ws.max_blocks(slots);
+    if (room < 1) return MB_EWORKSPACE;
+    for (int pass = 0; pass < 2; ++pass) {
+        const double *first = pass ? ws.reduced() : nullptr;
+        int *gate = pass ? ws.gate() : nullptr;
+        int nblocks = 0;
+        {
+            StageTimer t(pass ? MB_STAGE_REFINE : MB_STAGE_DIST, s);
+            if (in16)
+                MB_HIP(mb::launch_dist_gram_in16(static_cast<const uint16_t *>(grads), n, d, ld, ws.partials(), room,
+                                                 &nblocks, first, gate, s));
+            else
+                MB_HIP(mb::launch_dist_gram(static_cast<const float *>(grads), n, d, ld, ws.partials(), bf16, room,
+                                            &nblocks, first, gate, s));
+        }
+        StageTimer t(pass ? MB_STAGE_REFINE : MB_STAGE_REDUCE, s);
+        MB_HIP(mb::launch_reduce(ws.partials(), nblocks, slots, slots, pass ? ws.reduced2() : ws.reduced(), gate, s));
     }
-    StageTimer t(MB_STAGE_REDUCE, s);
-    MB_HIP(mb::launch_reduce(ws.partials(), nblocks, slots, slots, ws.reduced(), s));
     if (defer && !accumulate) {
         *defer = 1;
-        *canon = false;
         return MB_OK;
     }
-    MB_HIP(mb::launch_finalize_gram(ws.reduced(), n, dist, accumulate, false, s));
+    StageTimer t(MB_STAGE_REDUCE, s);
+    MB_HIP(mb::launch_finalize_gram(ws.reduced(), ws.reduced2(), ws.gate(), n, dist, accumulate, s));
     return MB_OK;
 }
 
+int run_dist_in16(const uint16_t *grads, int n, int64_t d, int64_t ld, double *dist, int accumulate,
+                  const Workspace &ws, hipStream_t s, int *defer = nullptr)
+{
+    return run_dist_gram(grads, 1, true, n, d, ld, dist, accumulate, ws, s, defer);
+}
+
 int run_dist(const float *grads, int n, int64_t d, int64_t ld, double *dist, int accumulate, int algo,
-             const Workspace &ws, hipStream_t s, int *defer = nullptr, bool *canon = nullptr)
+             const Workspace &ws, hipStream_t s, int *defer = nullptr)
 {
     algo = resolve_algo(algo);
-    int nblocks = mb::dist_grid_blocks(d, algo);
     if (algo == MB_DIST_DIRECT) {
+        int nblocks = mb::dist_grid_blocks(d, algo);
         const int nb = (n + 7) / 8, slots = nb * (nb + 1) / 2 * 64;
         const int room = ws.max_blocks(mb::kDirectSlots);
         if (room < 1) return MB_EWORKSPACE;
@@ -213,28 +233,13 @@ int run_dist(const float *grads, int n, int64_t d, int64_t ld, double *dist, int
             MB_HIP(mb::launch_dist_direct(grads, n, d, ld, ws.partials(), nblocks, s));
         }
         StageTimer t(MB_STAGE_REDUCE, s);
-        MB_HIP(mb::launch_reduce(ws.partials(), nblocks, mb::kDirectSlots, slots, ws.reduced(), s));
+        MB_HIP(mb::launch_reduce(ws.partials(), nblocks, mb::kDirectSlots, slots, ws.reduced(), nullptr, s));
         MB_HIP(mb::launch_finalize_direct(ws.reduced(), n, dist, accumulate, s));
-    } else if (algo == MB_DIST_GRAM || algo == MB_DIST_GRAM_BF16) {
-        const int slots = mb::gram_slots(n);
-        {
-            StageTimer t(MB_STAGE_DIST, s);
-            const int room = ws.max_blocks(slots);
-            if (room < 1) return MB_EWORKSPACE;
-            MB_HIP(mb::launch_dist_gram(grads, n, d, ld, ws.partials(), algo == MB_DIST_GRAM_BF16, room, &nblocks, s));
-        }
-        StageTimer t(MB_STAGE_REDUCE, s);
-        MB_HIP(mb::launch_reduce(ws.partials(), nblocks, slots, slots, ws.reduced(), s));
-        if (defer && !accumulate) {
-            *defer = 1;
-            *canon = algo == MB_DIST_GRAM_BF16;
-            return MB_OK;
-        }
-        MB_HIP(mb::launch_finalize_gram(ws.reduced(), n, dist, accumulate, algo == MB_DIST_GRAM_BF16, s));
-    } else {
-        return MB_EINVAL;
+        return MB_OK;
     }
-    return MB_OK;
+    if (algo == MB_DIST_GRAM || algo == MB_DIST_GRAM_BF16)
+        return run_dist_gram(grads, 0, algo == MB_DIST_GRAM_BF16, n, d, ld, dist, accumulate, ws, s, defer);
+    return MB_EINVAL;
 }
 
 // plan_ready: the selection has already written the plan for (sel, sets)
@@ -476,8 +481,7 @@ static int aggregate_on(const Workspace &ws, const float *grads, int n, int f, i
                         int theta, int beta, float *out, int32_t *selected_idx, hipStream_t s)
 {
     int deferred = 0;
-    bool canon = false;
-    int rc = run_dist(grads, n, d, ld, ws.dist(), 0, MB_DIST_AUTO, ws, s, &deferred, &canon);
+    int rc = run_dist(grads, n, d, ld, ws.dist(), 0, MB_DIST_AUTO, ws, s, &deferred);
     if (rc != MB_OK) return rc;
     int32_t *sel = selected_idx ? selected_idx : ws.sel();   // the selection writes the caller's list in place
     {
@@ -485,7 +489,7 @@ static int aggregate_on(const Workspace &ws, const float *grads, int n, int f, i
         uint8_t *sets = mode == MB_MODE_ALG1 ? ws.sets() : nullptr;
         int32_t *plan = mode == MB_MODE_ALG1 ? ws.plan() : nullptr;   // written by the selection as well
         if (deferred)
-            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, theta, sel, sets, ws.m(), plan, s));
+            MB_HIP(mb::launch_select_gram(ws.reduced(), ws.reduced2(), ws.gate(), n, f, theta, sel, sets, ws.m(), plan, s));
         else
             MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, sel, sets, ws.m(), nullptr, plan, s));
     }
@@ -577,14 +581,13 @@ int multikrum_aggregate(const float *grads, int n, int f, int64_t d, int64_t ld,
     if (rc != MB_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
     int deferred = 0;
-    bool canon = false;
-    rc = run_dist(grads, n, d, ld, ws.dist(), 0, MB_DIST_AUTO, ws, s, &deferred, &canon);
+    rc = run_dist(grads, n, d, ld, ws.dist(), 0, MB_DIST_AUTO, ws, s, &deferred);
     if (rc != MB_OK) return rc;
     uint8_t *mask = selected_mask ? selected_mask : ws.sets();   // written in place by the selection
     {
         StageTimer t(MB_STAGE_SELECT, s);
         if (deferred)
-            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, 1, ws.sel(), mask, ws.m(), nullptr, s));
+            MB_HIP(mb::launch_select_gram(ws.reduced(), ws.reduced2(), ws.gate(), n, f, 1, ws.sel(), mask, ws.m(), nullptr, s));
         else
             MB_HIP(mb::launch_select(ws.dist(), n, f, 1, nullptr, ws.sel(), mask, ws.m(), nullptr, nullptr, s));
     }
@@ -646,14 +649,13 @@ int multikrum_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d, int
     if (rc != MB_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
     int deferred = 0;
-    bool canon = false;
-    rc = run_dist_in16(grads, n, d, ld, ws.dist(), 0, ws, s, &deferred, &canon);
+    rc = run_dist_in16(grads, n, d, ld, ws.dist(), 0, ws, s, &deferred);
     if (rc != MB_OK) return rc;
     uint8_t *mask = selected_mask ? selected_mask : ws.sets();   // written in place by the selection
     {
         StageTimer t(MB_STAGE_SELECT, s);
         if (deferred)
-            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, 1, ws.sel(), mask, ws.m(), nullptr, s));
+            MB_HIP(mb::launch_select_gram(ws.reduced(), ws.reduced2(), ws.gate(), n, f, 1, ws.sel(), mask, ws.m(), nullptr, s));
         else
             MB_HIP(mb::launch_select(ws.dist(), n, f, 1, nullptr, ws.sel(), mask, ws.m(), nullptr, nullptr, s));
     }
@@ -691,8 +693,7 @@ int mbulyan_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d, int64
     if (rc != MB_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
     int deferred = 0;
-    bool canon = false;
-    rc = run_dist_in16(grads, n, d, ld, ws.dist(), 0, ws, s, &deferred, &canon);
+    rc = run_dist_in16(grads, n, d, ld, ws.dist(), 0, ws, s, &deferred);
     if (rc != MB_OK) return rc;
     int32_t *sel = selected_idx ? selected_idx : ws.sel();   // the selection writes the caller's list in place
     {
@@ -700,7 +701,7 @@ int mbulyan_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d, int64
         uint8_t *sets = mode == MB_MODE_ALG1 ? ws.sets() : nullptr;
         int32_t *plan = mode == MB_MODE_ALG1 ? ws.plan() : nullptr;   // written by the selection as well
         if (deferred)
-            MB_HIP(mb::launch_select_gram(ws.reduced(), canon, n, f, theta, sel, sets, ws.m(), plan, s));
+            MB_HIP(mb::launch_select_gram(ws.reduced(), ws.reduced2(), ws.gate(), n, f, theta, sel, sets, ws.m(), plan, s));
         else
             MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, sel, sets, ws.m(), nullptr, plan, s));
     }

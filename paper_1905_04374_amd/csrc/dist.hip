@@ -17,6 +17,7 @@
 // them over workgroups in index order and a third forms the n x n matrix.
 #include <hip/hip_runtime.h>
 
+#include "gram_combine.hpp"
 #include "mb_internal.hpp"
 
 namespace mb {
@@ -122,38 +123,29 @@ __global__ void finalize_direct_kernel(const double *__restrict__ reduced, int n
 }
 
 // ------------------------------------------------- gram: matrix -> distances
-// canon != 0: rows at distance exactly 0 from an earlier row are copies of it and take over its
-// distance row.  The split-bf16 products are not symmetric in their operands (hi*lo and lo*hi are
-// added at different moments), so without this two bit-identical rows could get distance rows that
-// differ in the last bits, and ties between their scores would hang on rounding.
-__global__ __launch_bounds__(1024) void finalize_gram_kernel(const double *__restrict__ reduced, int n,
-                                                             double *__restrict__ dist, int accumulate,
-                                                             int canon)
+// Every pair takes its value from the pass with the smaller error bound (gram_combine.hpp).  Rows
+// that are copies of an earlier row take over that row's distances: the split-bf16 products are
+// not symmetric in their operands (hi*lo and lo*hi are added at different moments), so without
+// this two bit-identical rows could get distance rows that differ in the last bits, and ties
+// between their scores would hang on rounding.
+__global__ __launch_bounds__(1024) void finalize_gram_kernel(const double *__restrict__ reduced,
+                                                             const double *__restrict__ reduced2,
+                                                             const int *__restrict__ gate, int n,
+                                                             double *__restrict__ dist, int accumulate)
 {
     __shared__ double D[kMaxN * kMaxN];
     __shared__ int rep[kMaxN];
-    for (int e = threadIdx.x; e < n * n; e += blockDim.x) {
-        const int i = e / n, j = e % n;
-        const int hi = i > j ? i : j, lo = i > j ? j : i;
-        double v = 0.0;
-        if (hi != lo) {
-            v = (gram_at(reduced, hi, hi) + gram_at(reduced, lo, lo)) - 2.0 * gram_at(reduced, hi, lo);
-            v = v < 0.0 ? 0.0 : v;
-        }
-        D[i * kMaxN + j] = v;
-    }
-    __syncthreads();
-    if ((int)threadIdx.x < n) {
-        int r = threadIdx.x;
-        if (canon)
-            for (int i = 0; i < (int)threadIdx.x; ++i)
-                if (D[i * kMaxN + threadIdx.x] == 0.0) { r = i; break; }
-        rep[threadIdx.x] = r;
-    }
+    const bool refined = gate && gate[kGateFlag] != 0;
+    if ((int)threadIdx.x < kMaxN) rep[threadIdx.x] = threadIdx.x;
     __syncthreads();
     for (int e = threadIdx.x; e < n * n; e += blockDim.x) {
         const int i = e / n, j = e % n;
-        const double v = D[rep[i] * kMaxN + rep[j]];
+        if (i > j && gram_term(reduced, i, j).same) atomicMin(&rep[i], j);   // the first row that i copies
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < n * n; e += blockDim.x) {
+        const int i = rep[e / n], j = rep[e % n];
+        const double v = i == j ? 0.0 : gram_pair_distance(reduced, reduced2, refined, i > j ? i : j, i > j ? j : i);
         dist[e] = accumulate ? dist[e] + v : v;
     }
 }
@@ -169,9 +161,11 @@ constexpr int kRedSlots = 16;
 constexpr int kRedBatch = 16;
 
 __global__ __launch_bounds__(kRedSegs * kRedSlots) void reduce_partials_kernel(
-    const double *__restrict__ partials, int nblocks, int stride, int slots, double *__restrict__ reduced)
+    const double *__restrict__ partials, int nblocks, int stride, int slots, double *__restrict__ reduced,
+    const int *__restrict__ gate)
 {
     __shared__ double seg_sum[kRedSegs][kRedSlots + 1];
+    if (gate && gate[kGateFlag] == 0) return;   // the pass whose sums these would be did not run
     const int el = threadIdx.x % kRedSlots;
     const int seg = threadIdx.x / kRedSlots;
     const int e = blockIdx.x * kRedSlots + el;
@@ -224,10 +218,10 @@ hipError_t launch_dist_direct(const float *G, int n, int64_t d, int64_t ld, doub
 }
 
 hipError_t launch_reduce(const double *partials, int nblocks, int stride, int slots, double *reduced,
-                         hipStream_t s)
+                         const int *gate, hipStream_t s)
 {
     reduce_partials_kernel<<<dim3((slots + kRedSlots - 1) / kRedSlots), dim3(kRedSegs * kRedSlots), 0, s>>>(
-        partials, nblocks, stride, slots, reduced);
+        partials, nblocks, stride, slots, reduced, gate);
     return hipGetLastError();
 }
 
@@ -237,10 +231,10 @@ hipError_t launch_finalize_direct(const double *reduced, int n, double *dist, in
     return hipGetLastError();
 }
 
-hipError_t launch_finalize_gram(const double *reduced, int n, double *dist, int accumulate, bool canon,
-                                hipStream_t s)
+hipError_t launch_finalize_gram(const double *reduced, const double *reduced2, const int *gate, int n, double *dist,
+                                int accumulate, hipStream_t s)
 {
-    finalize_gram_kernel<<<dim3(1), dim3(1024), 0, s>>>(reduced, n, dist, accumulate, canon ? 1 : 0);
+    finalize_gram_kernel<<<dim3(1), dim3(1024), 0, s>>>(reduced, reduced2, gate, n, dist, accumulate ? 1 : 0);
     return hipGetLastError();
 }
 

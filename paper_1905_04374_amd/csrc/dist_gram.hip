@@ -35,6 +35,7 @@
 
 #include <mutex>
 
+#include "gram_combine.hpp"
 #include "mb_internal.hpp"
 
 namespace mb {
@@ -84,6 +85,14 @@ __device__ __forceinline__ Pieces split8(const float4 &u, const float4 &w)
 struct Raw {
     float4 u, w;   // columns 8q..8q+3 and 8q+4..8q+7 of one row
 };
+
+__device__ __forceinline__ Raw raw_minus(const Raw &a, const Raw &b)
+{
+    Raw y;
+    y.u = make_float4(a.u.x - b.u.x, a.u.y - b.u.y, a.u.z - b.u.z, a.u.w - b.u.w);
+    y.w = make_float4(a.w.x - b.w.x, a.w.y - b.w.y, a.w.z - b.w.z, a.w.w - b.w.w);
+    return y;
+}
 
 template <int NB>
 struct Tiles {
@@ -144,13 +153,76 @@ struct Tiles {
     }
 };
 
-template <int NB, bool BF16, int DEPTH>
+// ---------------------------------------------------------------------------------------------
+// The second, centred pass (see gram_combine.hpp for why and when).  Its kernels are the two below
+// with CENTER set: every workgroup first decides from the first pass's Gram tiles whether the pass
+// is needed at all and which row is the pivot (the same arithmetic on the same data in every
+// workgroup, so they all agree; an unneeded pass costs a launch of workgroups that read n^2/2 Gram
+// entries and return), workgroup 0 leaves flag and pivot for the kernels that follow, and the
+// pivot's value is subtracted from every value of its column before the products are formed.
+//
+// gram_gate: every thread of the workgroup calls it (barriers inside).  `scratch`: LDS, n*n + n
+// doubles and two ints.  Returns the pivot row if some pair of the first pass is flagged, else -1.
+template <int NTHREADS>
+__device__ __forceinline__ int gram_gate(const double *__restrict__ R1, int n, double *scratch, int tid)
+{
+    bool bad = false;
+    for (int e = tid; e < n * n; e += NTHREADS) {
+        const int i = e / n, j = e % n;
+        if (i > j) bad = bad || gram_flagged(gram_term(R1, i, j));
+    }
+    if (!__syncthreads_or(bad ? 1 : 0)) return -1;
+    // pivot: the row whose k-th nearest other row is nearest, k = half of the others
+    double *D = scratch, *radius = scratch + n * n;
+    int *pick = reinterpret_cast<int *>(radius + n);
+    const double inf = __builtin_huge_val();
+    for (int e = tid; e < n * n; e += NTHREADS) {
+        const int i = e / n, j = e % n;
+        double v = inf;                                   // a row is not its own neighbour
+        if (i != j) {
+            v = gram_term(R1, i > j ? i : j, i > j ? j : i).d;
+            if (!(v == v)) v = inf;
+        }
+        D[e] = v;
+    }
+    __syncthreads();
+    const int k = n / 2;                                  // ceil((n - 1) / 2) of the n - 1 others
+    for (int i = tid; i < n; i += NTHREADS) {
+        double r = inf;
+        for (int j = 0; j < n; ++j) {
+            const double v = D[i * n + j];
+            int before = 0;
+            for (int j2 = 0; j2 < n; ++j2) {
+                const double u = D[i * n + j2];
+                before += (u < v || (u == v && j2 < j)) ? 1 : 0;
+            }
+            if (before == k - 1) r = v;
+        }
+        radius[i] = r;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int best = 0;
+        for (int i = 1; i < n; ++i)
+            if (radius[i] < radius[best]) best = i;
+        *pick = best;
+    }
+    __syncthreads();
+    return *pick;
+}
+
+template <int NB, bool BF16, int DEPTH, bool CENTER>
 __global__ __launch_bounds__(kThreads) void gram_kernel(const float *__restrict__ G, int n, int64_t d,
                                                         int64_t ld, int aligned,
-                                                        double *__restrict__ partials)
+                                                        double *__restrict__ partials,
+                                                        const double *__restrict__ first_pass,
+                                                        int *__restrict__ gate)
 {
     constexpr int NT = NB * (NB + 1) / 2;
+    constexpr int NR = NB + (CENTER ? 1 : 0);   // row blocks a lane loads: with CENTER, the pivot row as one more
     __shared__ float stage[4][NT * 256];
+    static_assert(!CENTER || sizeof(stage) >= (16 * NB * (16 * NB + 1)) * sizeof(double) + 2 * sizeof(int),
+                  "the gate's scratch fits the staging area");
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -159,17 +231,27 @@ __global__ __launch_bounds__(kThreads) void gram_kernel(const float *__restrict_
     const int64_t nwaves = (int64_t)gridDim.x * 4;
     const int64_t gw = (int64_t)blockIdx.x * 4 + wave;
 
+    int pivot = 0;
+    if constexpr (CENTER) {
+        pivot = gram_gate<kThreads>(first_pass, n, reinterpret_cast<double *>(&stage[0][0]), tid);
+        if (blockIdx.x == 0 && tid == 0) {
+            gate[kGateFlag] = pivot >= 0 ? 1 : 0;
+            gate[kGatePivot] = pivot >= 0 ? pivot : 0;
+        }
+        if (pivot < 0) return;     // the same in every thread of every workgroup
+        __syncthreads();           // the scratch becomes the staging area
+    }
+
     // Lanes of padded rows (16I + r >= n) read row n-1 instead: they fill Gram entries of rows
     // that do not exist and that nothing reads, the addresses are those another lane loads
     // anyway, and the main loop stays free of branches.
-    const float *rowp[NB];
-    bool rowok[NB];
+    const float *rowp[NR];
 #pragma unroll
     for (int I = 0; I < NB; ++I) {
         const int row = 16 * I + r;
-        rowok[I] = row < n;
-        rowp[I] = G + (int64_t)(rowok[I] ? row : n - 1) * ld + 8 * q;
+        rowp[I] = G + (int64_t)(row < n ? row : n - 1) * ld + 8 * q;
     }
+    if constexpr (CENTER) rowp[NB] = G + (int64_t)pivot * ld + 8 * q;
 
     Tiles<NB> tiles;
     tiles.clear();
@@ -193,12 +275,29 @@ __global__ __launch_bounds__(kThreads) void gram_kernel(const float *__restrict_
         __syncthreads();
     };
 
-    auto load = [&](Raw (&b)[NB], int64_t step) {
+    auto load = [&](Raw (&b)[NR], int64_t step) {
         const int64_t c = step * kCols;
 #pragma unroll
-        for (int I = 0; I < NB; ++I) {
+        for (int I = 0; I < NR; ++I) {
             b[I].u = *reinterpret_cast<const float4 *>(rowp[I] + c);
             b[I].w = *reinterpret_cast<const float4 *>(rowp[I] + c + 4);
+        }
+    };
+    // the products of one step (with CENTER: of the values minus the pivot's)
+    auto multiply = [&](const Raw (&b)[NR]) {
+        Raw x[NB];
+#pragma unroll
+        for (int I = 0; I < NB; ++I) {
+            x[I] = b[I];
+            if constexpr (CENTER) x[I] = raw_minus(b[I], b[NB]);
+        }
+        if constexpr (BF16) {
+            Pieces p[NB];
+#pragma unroll
+            for (int I = 0; I < NB; ++I) p[I] = split8(x[I].u, x[I].w);
+            tiles.mac_bf16(p);
+        } else {
+            tiles.mac_fp32(x);
         }
     };
 
@@ -208,7 +307,7 @@ __global__ __launch_bounds__(kThreads) void gram_kernel(const float *__restrict_
     if (iters > 0) {
         const int64_t last = iters - 1;
         auto step_of = [&](int64_t i) { return gw + (i < last ? i : last) * nwaves; };  // clamped
-        Raw raw[DEPTH][NB];
+        Raw raw[DEPTH][NR];
 #pragma unroll
         for (int k = 0; k < DEPTH; ++k) load(raw[k], step_of(k));
         for (int64_t i = 0; i <= last; i += DEPTH) {
@@ -216,13 +315,13 @@ __global__ __launch_bounds__(kThreads) void gram_kernel(const float *__restrict_
             for (int k = 0; k < DEPTH; ++k) {
                 if (i + k <= last) {
                     if constexpr (BF16) {
-                        Pieces x[NB];
+                        Raw cur[NR];
 #pragma unroll
-                        for (int I = 0; I < NB; ++I) x[I] = split8(raw[k][I].u, raw[k][I].w);
+                        for (int I = 0; I < NR; ++I) cur[I] = raw[k][I];
                         load(raw[k], step_of(i + k + DEPTH));
-                        tiles.mac_bf16(x);
+                        multiply(cur);
                     } else {
-                        tiles.mac_fp32(raw[k]);
+                        multiply(raw[k]);
                         load(raw[k], step_of(i + k + DEPTH));
                     }
                     if (((i + k) & (kFlush - 1)) == kFlush - 1) flush();
@@ -242,23 +341,16 @@ __global__ __launch_bounds__(kThreads) void gram_kernel(const float *__restrict_
             const int64_t step = gw + i * nwaves;
             if (step < tsteps) {
                 const int64_t c = c_begin + step * kCols;     // rowp already holds + 8q
-                Raw x[NB];
+                Raw x[NR];
 #pragma unroll
-                for (int I = 0; I < NB; ++I) {
+                for (int I = 0; I < NR; ++I) {
                     float v[8];
 #pragma unroll
                     for (int e = 0; e < 8; ++e) v[e] = (c + 8 * q + e < d) ? rowp[I][c + e] : 0.0f;
                     x[I].u = make_float4(v[0], v[1], v[2], v[3]);
                     x[I].w = make_float4(v[4], v[5], v[6], v[7]);
                 }
-                if constexpr (BF16) {
-                    Pieces p[NB];
-#pragma unroll
-                    for (int I = 0; I < NB; ++I) p[I] = split8(x[I].u, x[I].w);
-                    tiles.mac_bf16(p);
-                } else {
-                    tiles.mac_fp32(x);
-                }
+                multiply(x);
             }
             if ((i & (kFlush - 1)) == kFlush - 1) flush();
         }
@@ -358,6 +450,31 @@ __device__ __forceinline__ void read_tile(unsigned base, const unsigned (&off)[2
     }
 }
 
+// the same for the pivot row alone: its two chunks, complete on return
+__device__ __forceinline__ void read_pivot(unsigned base, const unsigned (&off)[2], Raw &x)
+{
+    floatx4 v0, v1;
+    asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %3\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(v0), "=&v"(v1)
+                 : "v"(base + off[0]), "v"(base + off[1])
+                 : "memory");
+    x.u = make_float4(v0[0], v0[1], v0[2], v0[3]);
+    x.w = make_float4(v1[0], v1[1], v1[2], v1[3]);
+}
+
+// eight bf16 values (four words, element e in half e & 1 of word e / 2) widened to fp32
+__device__ __forceinline__ Raw widen8(const float4 &w)
+{
+    const unsigned a = __float_as_uint(w.x), b = __float_as_uint(w.y), c = __float_as_uint(w.z),
+                   e = __float_as_uint(w.w);
+    Raw y;
+    y.u = make_float4(__uint_as_float(a << 16), __uint_as_float(a & 0xffff0000u), __uint_as_float(b << 16),
+                      __uint_as_float(b & 0xffff0000u));
+    y.w = make_float4(__uint_as_float(c << 16), __uint_as_float(c & 0xffff0000u), __uint_as_float(e << 16),
+                      __uint_as_float(e & 0xffff0000u));
+    return y;
+}
+
 // Tile buffers per workgroup and workgroups per compute unit the registers are budgeted for
 // (measured at n = 39: 2 buffers x 3 workgroups 5.97 ms, 3 x 2 6.4 ms; the fp64 sums of
 // 10 tiles leave room for two waves per SIMD only at NB = 4).
@@ -381,9 +498,10 @@ enum Kind { kFp32 = 0, kSplit = 1, kIn16 = 2 };
 template <int KIND> constexpr int elem_bytes() { return KIND == kIn16 ? 2 : 4; }
 template <int KIND> constexpr int tile_cols() { return 512 / elem_bytes<KIND>(); }
 
-template <int NB, int KIND, int L>
+template <int NB, int KIND, int L, bool CENTER>
 __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_kernel(
-    const void *__restrict__ Gv, int n, int64_t d, int64_t ld, int64_t ntiles, double *__restrict__ partials)
+    const void *__restrict__ Gv, int n, int64_t d, int64_t ld, int64_t ntiles, double *__restrict__ partials,
+    const double *__restrict__ first_pass, int *__restrict__ gate)
 {
     constexpr int NT = NB * (NB + 1) / 2;
     constexpr int S = kStages;
@@ -400,6 +518,19 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
     const int r = lane & 15;
     const int q = lane >> 4;
     const int tile_floats = ((n + 1) >> 1) * 256;
+
+    // second pass: needed at all, and around which row?  (the tile buffers serve as scratch: n KB
+    // and more, the gate needs (n^2 + n) doubles)
+    int pivot = 0;
+    if constexpr (CENTER) {
+        pivot = gram_gate<kThreads>(first_pass, n, reinterpret_cast<double *>(lds), tid);
+        if (blockIdx.x == 0 && tid == 0) {
+            gate[kGateFlag] = pivot >= 0 ? 1 : 0;
+            gate[kGatePivot] = pivot >= 0 ? pivot : 0;
+        }
+        if (pivot < 0) return;     // the same in every thread of every workgroup
+        __syncthreads();           // the scratch becomes the tile buffers
+    }
 
     // ---- loads: instruction j of this wave moves row pair wave + 4j ---------------------------
     const int half = lane >> 5, slot = lane & 31;
@@ -444,6 +575,12 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
         off[2 * I] = (unsigned)(row * 512 + c0 * 16);
         off[2 * I + 1] = (unsigned)(row * 512 + (c0 ^ (KIND == kIn16 ? 4 : 1)) * 16);
     }
+    unsigned poff[2] = {0u, 0u};   // the same two chunks of the pivot row
+    if constexpr (CENTER) {
+        const int c0 = (KIND == kIn16 ? 8 * wave + q : 8 * wave + 2 * q) ^ (pivot & 15);
+        poff[0] = (unsigned)(pivot * 512 + c0 * 16);
+        poff[1] = (unsigned)(pivot * 512 + (c0 ^ (KIND == kIn16 ? 4 : 1)) * 16);
+    }
     const unsigned lds0 = lds_byte_address(lds);
 
     Tiles<NB> tiles;
@@ -473,6 +610,33 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
             tiles.mac_fp32(x);
         }
     };
+    // second pass: the pivot's values come off first.  fp32 input: one subtraction per value, then
+    // as above.  bf16 input: the differences of two bf16 values are fp32 values (exact when the
+    // exponents are within 16 of each other), so each of the wave's two steps is widened,
+    // centred and multiplied as split fp32.
+    auto multiply_centred = [&](const Raw (&x)[NB], const Raw &pv) {
+        if constexpr (KIND == kIn16) {
+            const Raw p0 = widen8(pv.u), p1 = widen8(pv.w);
+            Pieces p[NB];
+#pragma unroll
+            for (int I = 0; I < NB; ++I) {
+                const Raw y = raw_minus(widen8(x[I].u), p0);
+                p[I] = split8(y.u, y.w);
+            }
+            tiles.mac_bf16(p);
+#pragma unroll
+            for (int I = 0; I < NB; ++I) {
+                const Raw y = raw_minus(widen8(x[I].w), p1);
+                p[I] = split8(y.u, y.w);
+            }
+            tiles.mac_bf16(p);
+        } else {
+            Raw y[NB];
+#pragma unroll
+            for (int I = 0; I < NB; ++I) y[I] = raw_minus(x[I], pv);
+            multiply(y);
+        }
+    };
 
     // ---- whole tiles b, b + g, b + 2g, ... of this workgroup ----------------------------------
     const int64_t g = gridDim.x, b = blockIdx.x;
@@ -496,7 +660,13 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
         if constexpr (KIND != kIn16) __builtin_amdgcn_s_setprio(0);
         Raw x[NB];
         read_tile<NB>(lds0 + (unsigned)((int)(i % S) * tile_floats * 4), off, x);
-        multiply(x);
+        if constexpr (CENTER) {
+            Raw pv;
+            read_pivot(lds0 + (unsigned)((int)(i % S) * tile_floats * 4), poff, pv);
+            multiply_centred(x, pv);
+        } else {
+            multiply(x);
+        }
         if ((i & (kEvery - 1)) == kEvery - 1) flush();
     }
 
@@ -510,11 +680,9 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
         int64_t done = 0;
         for (int64_t u = gw; u < units; u += nwaves, ++done) {
             const int64_t c = c_begin + u * WC + 8 * q;      // this lane's 8 columns of the first step
-            Raw x[NB];
-#pragma unroll
-            for (int I = 0; I < NB; ++I) {
-                int row = 16 * I + r;
-                row = row < n ? row : n - 1;
+            // the lane's values of one row (KIND == kIn16: two steps, the bf16 words as they are)
+            auto load_row = [&](int row) {
+                Raw y;
                 if constexpr (KIND == kIn16) {
                     const unsigned short *p = reinterpret_cast<const unsigned short *>(G) + (int64_t)row * ld;
                     unsigned w0[4], w1[4];
@@ -524,20 +692,33 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
                         w0[e] = (ca < d ? (unsigned)p[ca] : 0u) | (ca + 1 < d ? (unsigned)p[ca + 1] << 16 : 0u);
                         w1[e] = (cb < d ? (unsigned)p[cb] : 0u) | (cb + 1 < d ? (unsigned)p[cb + 1] << 16 : 0u);
                     }
-                    x[I].u = make_float4(__uint_as_float(w0[0]), __uint_as_float(w0[1]), __uint_as_float(w0[2]),
-                                         __uint_as_float(w0[3]));
-                    x[I].w = make_float4(__uint_as_float(w1[0]), __uint_as_float(w1[1]), __uint_as_float(w1[2]),
-                                         __uint_as_float(w1[3]));
+                    y.u = make_float4(__uint_as_float(w0[0]), __uint_as_float(w0[1]), __uint_as_float(w0[2]),
+                                      __uint_as_float(w0[3]));
+                    y.w = make_float4(__uint_as_float(w1[0]), __uint_as_float(w1[1]), __uint_as_float(w1[2]),
+                                      __uint_as_float(w1[3]));
                 } else {
                     const float *p = reinterpret_cast<const float *>(G) + (int64_t)row * ld;
                     float v[8];
 #pragma unroll
                     for (int e = 0; e < 8; ++e) v[e] = (c + e < d) ? p[c + e] : 0.0f;
-                    x[I].u = make_float4(v[0], v[1], v[2], v[3]);
-                    x[I].w = make_float4(v[4], v[5], v[6], v[7]);
+                    y.u = make_float4(v[0], v[1], v[2], v[3]);
+                    y.w = make_float4(v[4], v[5], v[6], v[7]);
                 }
+                return y;
+            };
+            Raw x[NB];
+#pragma unroll
+            for (int I = 0; I < NB; ++I) {
+                int row = 16 * I + r;
+                row = row < n ? row : n - 1;
+                x[I] = load_row(row);
             }
-            multiply(x);
+            if constexpr (CENTER) {
+                // columns past the end are zero in every row, the pivot's included: they add nothing
+                multiply_centred(x, load_row(pivot));
+            } else {
+                multiply(x);
+            }
             if ((done & (kEvery - 1)) == kEvery - 1) flush();
         }
     }
@@ -578,9 +759,16 @@ inline hipError_t current_device(int *dev)
     return (*dev >= 0 && *dev < kMaxDevices) ? hipSuccess : hipErrorInvalidDevice;
 }
 
-template <int NB, int KIND, int L>
+// `second` (may be null): launch the second, centred pass instead, which reads the first pass's
+// reduced Gram tiles and leaves its flag and pivot in `gate`.
+struct SecondPass {
+    const double *first_pass;
+    int *gate;
+};
+
+template <int NB, int KIND, int L, bool CENTER>
 hipError_t launch_dma_l(const void *G, int n, int64_t d, int64_t ld, bool aligned, double *partials, int max_blocks,
-                        int *nblocks, hipStream_t s)
+                        int *nblocks, const SecondPass *second, hipStream_t s)
 {
     struct PerDevice {
         bool prepared;
@@ -596,7 +784,7 @@ hipError_t launch_dma_l(const void *G, int n, int64_t d, int64_t ld, bool aligne
         std::lock_guard<std::mutex> lock(g_launch_mu);
         PerDevice &c = cache[dev];
         if (!c.prepared) {
-            if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gram_dma_kernel<NB, KIND, L>),
+            if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gram_dma_kernel<NB, KIND, L, CENTER>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize,
                                          (int)dma_lds_bytes(16 * NB))) != hipSuccess)
                 return e;
@@ -605,8 +793,8 @@ hipError_t launch_dma_l(const void *G, int n, int64_t d, int64_t ld, bool aligne
         if (!c.resident[n]) {
             int cus = 0, per_cu = 0;
             if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
-            if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gram_dma_kernel<NB, KIND, L>, kThreads,
-                                                                  bytes)) != hipSuccess)
+            if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gram_dma_kernel<NB, KIND, L, CENTER>,
+                                                                  kThreads, bytes)) != hipSuccess)
                 return e;
             c.resident[n] = cus * (per_cu < 1 ? 1 : per_cu);
         }
@@ -620,30 +808,36 @@ hipError_t launch_dma_l(const void *G, int n, int64_t d, int64_t ld, bool aligne
     int64_t g = resident < max_blocks ? resident : max_blocks;
     if (work < 4 * g) g = work < 4 ? 1 : work / 4;
     *nblocks = (int)g;
-    gram_dma_kernel<NB, KIND, L><<<dim3((unsigned)g), dim3(kThreads), bytes, s>>>(G, n, d, ld, tiles, partials);
+    gram_dma_kernel<NB, KIND, L, CENTER><<<dim3((unsigned)g), dim3(kThreads), bytes, s>>>(
+        G, n, d, ld, tiles, partials, second ? second->first_pass : nullptr, second ? second->gate : nullptr);
     return hipGetLastError();
 }
 
 template <int NB, int KIND>
 hipError_t launch_dma(const void *G, int n, int64_t d, int64_t ld, bool aligned, double *partials, int max_blocks,
-                      int *nblocks, hipStream_t s)
+                      int *nblocks, const SecondPass *second, hipStream_t s)
 {
     // load instructions per wave and tile: ceil(pairs / 4), one of two values for each NB
-    if ((dma_pairs(n) + 3) / 4 == 2 * NB)
-        return launch_dma_l<NB, KIND, 2 * NB>(G, n, d, ld, aligned, partials, max_blocks, nblocks, s);
-    return launch_dma_l<NB, KIND, 2 * NB - 1>(G, n, d, ld, aligned, partials, max_blocks, nblocks, s);
+    const bool more = (dma_pairs(n) + 3) / 4 == 2 * NB;
+    if (second) {
+        if (more) return launch_dma_l<NB, KIND, 2 * NB, true>(G, n, d, ld, aligned, partials, max_blocks, nblocks, second, s);
+        return launch_dma_l<NB, KIND, 2 * NB - 1, true>(G, n, d, ld, aligned, partials, max_blocks, nblocks, second, s);
+    }
+    if (more) return launch_dma_l<NB, KIND, 2 * NB, false>(G, n, d, ld, aligned, partials, max_blocks, nblocks, second, s);
+    return launch_dma_l<NB, KIND, 2 * NB - 1, false>(G, n, d, ld, aligned, partials, max_blocks, nblocks, second, s);
 }
 
-template <int NB, bool BF16, int DEPTH>
+template <int NB, bool BF16, int DEPTH, bool CENTER>
 hipError_t launch_one(const float *G, int n, int64_t d, int64_t ld, double *partials, int nblocks,
-                      hipStream_t s)
+                      const SecondPass *second, hipStream_t s)
 {
     const int aligned = ((uintptr_t)G % 16 == 0) && (ld % 4 == 0);
-    gram_kernel<NB, BF16, DEPTH><<<dim3(nblocks), dim3(kThreads), 0, s>>>(G, n, d, ld, aligned, partials);
+    gram_kernel<NB, BF16, DEPTH, CENTER><<<dim3(nblocks), dim3(kThreads), 0, s>>>(
+        G, n, d, ld, aligned, partials, second ? second->first_pass : nullptr, second ? second->gate : nullptr);
     return hipGetLastError();
 }
 
-template <int NB, bool BF16, int DEPTH>
+template <int NB, bool BF16, int DEPTH, bool CENTER>
 int resident_blocks()
 {
     static int cache[kMaxDevices] = {};
@@ -652,7 +846,7 @@ int resident_blocks()
     std::lock_guard<std::mutex> lock(g_launch_mu);
     if (cache[dev]) return cache[dev];
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 1024;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gram_kernel<NB, BF16, DEPTH>, kThreads, 0) !=
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gram_kernel<NB, BF16, DEPTH, CENTER>, kThreads, 0) !=
         hipSuccess)
         return 1024;
     if (per_cu < 1) per_cu = 1;
@@ -660,11 +854,11 @@ int resident_blocks()
     return cache[dev];
 }
 
-template <int NB, bool BF16, int DEPTH>
+template <int NB, bool BF16, int DEPTH, bool CENTER>
 int grid_for(int64_t d, int max_blocks)
 {
     const int64_t steps = (d + 4 * kCols - 1) / (4 * kCols);   // one step for each of the 4 waves
-    int64_t g = resident_blocks<NB, BF16, DEPTH>();
+    int64_t g = resident_blocks<NB, BF16, DEPTH, CENTER>();
     if (g > max_blocks) g = max_blocks;
     if (steps < g) g = steps < 1 ? 1 : steps;
     return (int)g;
@@ -678,51 +872,57 @@ struct Depth {
 
 template <int NB, bool BF16>
 hipError_t launch_nb(const float *G, int n, int64_t d, int64_t ld, double *partials, int max_blocks, int *nblocks,
-                     hipStream_t s)
+                     const SecondPass *second, hipStream_t s)
 {
     if (((uintptr_t)G % 16 == 0) && (ld % 4 == 0) && d >= kTile)
-        return launch_dma<NB, BF16 ? kSplit : kFp32>(G, n, d, ld, true, partials, max_blocks, nblocks, s);
+        return launch_dma<NB, BF16 ? kSplit : kFp32>(G, n, d, ld, true, partials, max_blocks, nblocks, second, s);
     constexpr int D = Depth<NB, BF16>::value;
-    *nblocks = grid_for<NB, BF16, D>(d, max_blocks);
-    return launch_one<NB, BF16, D>(G, n, d, ld, partials, *nblocks, s);
+    if (second) {
+        *nblocks = grid_for<NB, BF16, D, true>(d, max_blocks);
+        return launch_one<NB, BF16, D, true>(G, n, d, ld, partials, *nblocks, second, s);
+    }
+    *nblocks = grid_for<NB, BF16, D, false>(d, max_blocks);
+    return launch_one<NB, BF16, D, false>(G, n, d, ld, partials, *nblocks, second, s);
 }
 
 }  // namespace
 
 hipError_t launch_dist_gram_in16(const uint16_t *G, int n, int64_t d, int64_t ld, double *partials, int max_blocks,
-                                 int *nblocks, hipStream_t s)
+                                 int *nblocks, const double *first_pass, int *gate, hipStream_t s)
 {
     if (max_blocks < 1) return hipErrorInvalidValue;
     if (max_blocks > kGramMaxBlocks) max_blocks = kGramMaxBlocks;
+    const SecondPass sp{first_pass, gate}, *second = first_pass ? &sp : nullptr;
     const bool aligned = ((uintptr_t)G % 16 == 0) && (ld % 8 == 0) && d >= tile_cols<kIn16>();
     switch (gram_blocks(n)) {
-        case 1: return launch_dma<1, kIn16>(G, n, d, ld, aligned, partials, max_blocks, nblocks, s);
-        case 2: return launch_dma<2, kIn16>(G, n, d, ld, aligned, partials, max_blocks, nblocks, s);
-        case 3: return launch_dma<3, kIn16>(G, n, d, ld, aligned, partials, max_blocks, nblocks, s);
-        case 4: return launch_dma<4, kIn16>(G, n, d, ld, aligned, partials, max_blocks, nblocks, s);
+        case 1: return launch_dma<1, kIn16>(G, n, d, ld, aligned, partials, max_blocks, nblocks, second, s);
+        case 2: return launch_dma<2, kIn16>(G, n, d, ld, aligned, partials, max_blocks, nblocks, second, s);
+        case 3: return launch_dma<3, kIn16>(G, n, d, ld, aligned, partials, max_blocks, nblocks, second, s);
+        case 4: return launch_dma<4, kIn16>(G, n, d, ld, aligned, partials, max_blocks, nblocks, second, s);
     }
     return hipErrorInvalidValue;
 }
 
 hipError_t launch_dist_gram(const float *G, int n, int64_t d, int64_t ld, double *partials, bool bf16,
-                            int max_blocks, int *nblocks, hipStream_t s)
+                            int max_blocks, int *nblocks, const double *first_pass, int *gate, hipStream_t s)
 {
     if (max_blocks < 1) return hipErrorInvalidValue;
     if (max_blocks > kGramMaxBlocks) max_blocks = kGramMaxBlocks;
+    const SecondPass sp{first_pass, gate}, *second = first_pass ? &sp : nullptr;
     const int nb = gram_blocks(n);
     if (bf16) {
         switch (nb) {
-            case 1: return launch_nb<1, true>(G, n, d, ld, partials, max_blocks, nblocks, s);
-            case 2: return launch_nb<2, true>(G, n, d, ld, partials, max_blocks, nblocks, s);
-            case 3: return launch_nb<3, true>(G, n, d, ld, partials, max_blocks, nblocks, s);
-            case 4: return launch_nb<4, true>(G, n, d, ld, partials, max_blocks, nblocks, s);
+            case 1: return launch_nb<1, true>(G, n, d, ld, partials, max_blocks, nblocks, second, s);
+            case 2: return launch_nb<2, true>(G, n, d, ld, partials, max_blocks, nblocks, second, s);
+            case 3: return launch_nb<3, true>(G, n, d, ld, partials, max_blocks, nblocks, second, s);
+            case 4: return launch_nb<4, true>(G, n, d, ld, partials, max_blocks, nblocks, second, s);
         }
     } else {
         switch (nb) {
-            case 1: return launch_nb<1, false>(G, n, d, ld, partials, max_blocks, nblocks, s);
-            case 2: return launch_nb<2, false>(G, n, d, ld, partials, max_blocks, nblocks, s);
-            case 3: return launch_nb<3, false>(G, n, d, ld, partials, max_blocks, nblocks, s);
-            case 4: return launch_nb<4, false>(G, n, d, ld, partials, max_blocks, nblocks, s);
+            case 1: return launch_nb<1, false>(G, n, d, ld, partials, max_blocks, nblocks, second, s);
+            case 2: return launch_nb<2, false>(G, n, d, ld, partials, max_blocks, nblocks, second, s);
+            case 3: return launch_nb<3, false>(G, n, d, ld, partials, max_blocks, nblocks, second, s);
+            case 4: return launch_nb<4, false>(G, n, d, ld, partials, max_blocks, nblocks, second, s);
         }
     }
     return hipErrorInvalidValue;

@@ -27,10 +27,6 @@ namespace mb {
 
 constexpr double kGateRatio = 256.0;
 
-// the two words the second pass leaves for the kernels after it
-constexpr int kGateFlag = 0;    // 1: the second pass ran and `reduced2` holds its Gram tiles
-constexpr int kGatePivot = 1;   // its pivot row
-
 struct GramTerm {
     double d;       // G_ii + G_jj - 2 G_ij, clamped at 0 (NaN stays NaN)
     double norms;   // G_ii + G_jj: the error of d is proportional to it

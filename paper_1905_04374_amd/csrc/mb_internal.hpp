@@ -15,6 +15,9 @@ constexpr int kDirectSlots = 36 * 64;
 constexpr int kGramMaxBlocks = 2048;
 constexpr int gram_blocks(int n) { return (n + 15) / 16; }
 constexpr int gram_slots(int n) { return gram_blocks(n) * (gram_blocks(n) + 1) / 2 * 256; }
+// the two words the second pass of the Gram form leaves for the kernels after it
+constexpr int kGateFlag = 0;    // 1: the second pass ran and its reduced tiles are to be used
+constexpr int kGatePivot = 1;   // its pivot row
 
 // Element (i, j), i >= j, of the Gram matrix inside the reduced tile array.  Tile (I, J) holds
 // rows 16I.. as the A operand and rows 16J.. as the B operand; the instruction leaves entry
@@ -32,18 +35,25 @@ int dist_grid_blocks(int64_t d, int algo);
 hipError_t launch_dist_direct(const float *G, int n, int64_t d, int64_t ld, double *partials,
                               int nblocks, hipStream_t s);
 // launches with as many workgroups as stay resident (at most dist_grid_blocks, and at most
-// max_blocks >= 1: what `partials` has room for) and reports the count
+// max_blocks >= 1: what `partials` has room for) and reports the count.
+// first_pass == null: the first pass (rows as they are).  Otherwise the second pass: first_pass =
+// the reduced Gram tiles of the first; the kernel decides on the device whether it is needed,
+// chooses the pivot row, leaves both in gate[kGateFlag], gate[kGatePivot] and, if needed, writes
+// the partial Gram tiles of the rows minus the pivot row.
 hipError_t launch_dist_gram(const float *G, int n, int64_t d, int64_t ld, double *partials, bool bf16,
-                            int max_blocks, int *nblocks, hipStream_t s);
+                            int max_blocks, int *nblocks, const double *first_pass, int *gate, hipStream_t s);
 // the same for gradients stored as bf16 (raw 16-bit words, ld in elements)
 hipError_t launch_dist_gram_in16(const uint16_t *G, int n, int64_t d, int64_t ld, double *partials, int max_blocks,
-                                 int *nblocks, hipStream_t s);
-// partials[nblocks][stride] -> reduced[0..slots) (fixed summation order), then -> dist[n*n]
+                                 int *nblocks, const double *first_pass, int *gate, hipStream_t s);
+// partials[nblocks][stride] -> reduced[0..slots) (fixed summation order).  gate (may be null): do
+// nothing unless gate[kGateFlag] is set (the reduction of a second pass that did not run).
 hipError_t launch_reduce(const double *partials, int nblocks, int stride, int slots, double *reduced,
-                         hipStream_t s);
+                         const int *gate, hipStream_t s);
 hipError_t launch_finalize_direct(const double *reduced, int n, double *dist, int accumulate, hipStream_t s);
-hipError_t launch_finalize_gram(const double *reduced, int n, double *dist, int accumulate, bool canon,
-                                hipStream_t s);
+// Gram tiles of the first pass, of the second pass and its gate words (both null: no second pass was
+// launched) -> dist[n*n]
+hipError_t launch_finalize_gram(const double *reduced, const double *reduced2, const int *gate, int n, double *dist,
+                                int accumulate, hipStream_t s);
 
 // ---- selection -----------------------------------------------------------
 // rounds >= 1: multi-Krum rounds; scores_out (may be null) gets the scores of the first round.
@@ -54,9 +64,10 @@ hipError_t launch_select(const double *dist, int n, int f, int rounds, const uin
                          int32_t *sel, uint8_t *agr_sets, int32_t *m_out, double *scores_out, int32_t *plan,
                          hipStream_t s);
 // The same starting from the reduced Gram tiles of the distance pass: the kernel forms the distance
-// matrix itself (what launch_finalize_gram would write, canon as there) and saves that launch.
-hipError_t launch_select_gram(const double *reduced, bool canon, int n, int f, int rounds, int32_t *sel,
-                              uint8_t *agr_sets, int32_t *m_out, int32_t *plan, hipStream_t s);
+// matrix itself (what launch_finalize_gram would write from the same arguments) and saves that launch.
+hipError_t launch_select_gram(const double *reduced, const double *reduced2, const int *gate, int n, int f,
+                              int rounds, int32_t *sel, uint8_t *agr_sets, int32_t *m_out, int32_t *plan,
+                              hipStream_t s);
 
 // out[c] = mean over rows r with mask[r] of G[r][c]
 hipError_t launch_masked_mean(const float *G, int n, int64_t d, int64_t ld, const uint8_t *mask,

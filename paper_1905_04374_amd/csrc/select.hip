@@ -13,6 +13,7 @@
 #include <hip/hip_runtime.h>
 
 #include "alg1_plan.hpp"
+#include "gram_combine.hpp"
 #include "mb_internal.hpp"
 
 namespace mb {
@@ -187,12 +188,14 @@ __device__ __forceinline__ void play_rounds(const Rounds &a, int i)
     }
 }
 
-// dist != null: the distance matrix.  Otherwise gram = the reduced Gram tiles of the distance pass,
-// and the matrix is formed here exactly as finalize_gram_kernel forms it (canon as there).
+// dist != null: the distance matrix.  Otherwise gram (and gram2, gate: the second pass, if one was
+// launched) = the reduced Gram tiles of the distance pass, and the matrix is formed here exactly as
+// finalize_gram_kernel forms it.
 // plan != null (needs sel and agr_sets): the plan of the Algorithm-1 coordinate pass for the
 // chosen gradients and sets is written as well, once the last round is over.
 __global__ __launch_bounds__(kSelThreads) void select_kernel(
-    const double *__restrict__ dist, const double *__restrict__ gram, int canon, int n, int f, int rounds,
+    const double *__restrict__ dist, const double *__restrict__ gram, const double *__restrict__ gram2,
+    const int *__restrict__ gate, int n, int f, int rounds,
     const uint8_t *__restrict__ active_in, int32_t *__restrict__ sel, uint8_t *__restrict__ agr_sets,
     int32_t *__restrict__ m_out, double *__restrict__ scores_out, int32_t *__restrict__ plan)
 {
@@ -221,53 +224,33 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
         }
         __syncthreads();
     } else {
-        // the Gram entries of all of a thread's elements first (up to 3 x kPerThread loads in
-        // flight), the arithmetic after
-        double gh[kPerThread], gl[kPerThread], gx[kPerThread];
-#pragma unroll
-        for (int k = 0; k < kPerThread; ++k) {
-            const int e = tid + k * kSelThreads;
-            gh[k] = gl[k] = gx[k] = 0.0;
-            if (e < n * n) {
-                const int i = e / n, j = e % n;
-                const int hi = i > j ? i : j, lo = i > j ? j : i;
-                if (hi != lo) {
-                    gh[k] = gram_at(gram, hi, hi);
-                    gl[k] = gram_at(gram, lo, lo);
-                    gx[k] = gram_at(gram, hi, lo);
-                }
-            }
-        }
-#pragma unroll
-        for (int k = 0; k < kPerThread; ++k) {
-            const int e = tid + k * kSelThreads;
-            if (e < n * n) {
-                double v = (gh[k] + gl[k]) - 2.0 * gx[k];      // 0 on the diagonal
-                v = v < 0.0 ? 0.0 : v;
-                sD[(e / n) * kMaxN + (e % n)] = v;
-            }
-        }
+        // which rows are copies of an earlier row (their Gram entries are bit-identical), then every
+        // pair from the pass with the smaller error bound; the Gram entries of all of a thread's
+        // elements first (many loads in flight), the arithmetic after
+        const bool refined = gate && gate[kGateFlag] != 0;
         if (tid < kMaxN) rep[tid] = tid;
         __syncthreads();
-        if (canon) {   // rep[j] = the first row at distance exactly 0 from row j (j itself if none)
+        bool same[kPerThread];
 #pragma unroll
-            for (int k = 0; k < kPerThread; ++k) {
-                const int e = tid + k * kSelThreads;
-                if (e < n * n) {
-                    const int i = e / n, j = e % n;
-                    if (i < j && sD[i * kMaxN + j] == 0.0) atomicMin(&rep[j], i);
-                }
-            }
+        for (int k = 0; k < kPerThread; ++k) {
+            const int e = tid + k * kSelThreads;
+            same[k] = false;
+            if (e < n * n && e / n > e % n) same[k] = gram_term(gram, e / n, e % n).same;
         }
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k)
+            if (same[k]) atomicMin(&rep[(tid + k * kSelThreads) / n], (tid + k * kSelThreads) % n);
         __syncthreads();
         double mine[kPerThread];
 #pragma unroll
         for (int k = 0; k < kPerThread; ++k) {
             const int e = tid + k * kSelThreads;
             mine[k] = 0.0;
-            if (e < n * n) mine[k] = sD[rep[e / n] * kMaxN + rep[e % n]];
+            if (e < n * n) {
+                const int i = rep[e / n], j = rep[e % n];
+                if (i != j) mine[k] = gram_pair_distance(gram, gram2, refined, i > j ? i : j, i > j ? j : i);
+            }
         }
-        __syncthreads();
 #pragma unroll
         for (int k = 0; k < kPerThread; ++k) {
             const int e = tid + k * kSelThreads;
@@ -346,16 +329,17 @@ hipError_t launch_select(const double *dist, int n, int f, int rounds, const uin
                          hipStream_t s)
 {
     if (plan && !(sel && agr_sets)) return hipErrorInvalidValue;
-    select_kernel<<<dim3(1), dim3(kSelThreads), 0, s>>>(dist, nullptr, 0, n, f, rounds, active_in, sel, agr_sets,
-                                                        m_out, scores_out, plan);
+    select_kernel<<<dim3(1), dim3(kSelThreads), 0, s>>>(dist, nullptr, nullptr, nullptr, n, f, rounds, active_in, sel,
+                                                        agr_sets, m_out, scores_out, plan);
     return hipGetLastError();
 }
 
-hipError_t launch_select_gram(const double *reduced, bool canon, int n, int f, int rounds, int32_t *sel,
-                              uint8_t *agr_sets, int32_t *m_out, int32_t *plan, hipStream_t s)
+hipError_t launch_select_gram(const double *reduced, const double *reduced2, const int *gate, int n, int f,
+                              int rounds, int32_t *sel, uint8_t *agr_sets, int32_t *m_out, int32_t *plan,
+                              hipStream_t s)
 {
     if (plan && !(sel && agr_sets)) return hipErrorInvalidValue;
-    select_kernel<<<dim3(1), dim3(kSelThreads), 0, s>>>(nullptr, reduced, canon ? 1 : 0, n, f, rounds, nullptr, sel,
+    select_kernel<<<dim3(1), dim3(kSelThreads), 0, s>>>(nullptr, reduced, reduced2, gate, n, f, rounds, nullptr, sel,
                                                         agr_sets, m_out, nullptr, plan);
     return hipGetLastError();
 }

@@ -31,7 +31,7 @@ def to_bf16(G):
 def assert_dist_close(got, G, ref):
     got = got.cpu().numpy()
     sq = (G.astype(np.float64) ** 2).sum(1)
-    tol = 1e-6 * (sq[:, None] + sq[None, :]) + 1e-30
+    tol = max(1e-7, 1e-5 / np.sqrt(G.shape[1])) * (sq[:, None] + sq[None, :]) + 1e-30
     err = np.abs(got - ref)
     assert np.all(err <= tol), f"dist: worst err/tol {np.max(err / tol):.3g}"
     assert np.array_equal(got, got.T) and np.all(np.diag(got) == 0.0)
@@ -214,7 +214,12 @@ def test_coordwise_median_bf16():
 
 def alg1_compare(got, ref, scale, margin, alt):
     """Accept the reference, or, where the decision margin is below the rounding noise of an fp32
-    evaluation of the multi-Krum averages, the other candidate."""
+    evaluation of the multi-Krum averages, the other candidate.  Returns how often the other
+    candidate was taken.  With bf16 gradients this is not rare: values of 8 significant bits make
+    averages that are *exactly* equidistant from the median (in exact arithmetic) about once in a
+    thousand coordinates, and which of the two an evaluation takes then hangs on the last bit of
+    the average (the oracle divides an fp64 sum, the kernel multiplies an fp32 sum by 1/m).  Measured:
+    1e-4 d to 1e-3 d on the workloads below; the tests fail above 2e-3 d."""
     got = got.cpu().numpy()
     tol = 1e-5 * np.maximum(np.abs(ref), scale) + 1e-37
     ok = np.abs(got - ref) <= tol
@@ -239,7 +244,7 @@ def test_coordwise_alg1_bf16(n, f, d):
     ref, scale, margin, alt = O.coordwise_alg1(G, ext, sets, beta, want_extra=True)
     got = mb.coordwise_trimmed_avg(Gt, torch.as_tensor(ext).to(DEV), beta, agr_sets=torch.as_tensor(sets).to(DEV))
     flips = alg1_compare(got, ref, scale, margin, alt)
-    assert flips <= max(4, d // 200)
+    assert flips <= max(4, d // 500)
 
 
 @pytest.mark.parametrize("cfg,d", [(1, None), (2, 400_000), (4, 100_004), (4, 5_000_001)])
@@ -257,4 +262,4 @@ def test_aggregate_alg1_mode_bf16(cfg, d):
     out, sel = mb.mbulyan_aggregate_ex(Gt, s["f"], mode=mb.MODE_ALG1)
     assert sel.cpu().numpy().tolist() == ext.tolist()
     flips = alg1_compare(out, ref, scale, margin, alt)
-    assert flips <= max(4, G.shape[1] // 200)
+    assert flips <= max(4, G.shape[1] // 500)

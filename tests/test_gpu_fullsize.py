@@ -81,7 +81,7 @@ def test_full_size_single_buffer(cfg, dtype):
     gap = check_separation(D, f, theta, ext)
     assert sel.tolist() == ext.tolist()
     sq = np.array([float(np.dot(G[r, :1 << 20].astype(np.float64), G[r, :1 << 20])) for r in range(n)]) * (d / (1 << 20))
-    assert np.all(np.abs(Dg - D) <= 1e-6 * (sq[:, None] + sq[None, :]))
+    assert np.all(np.abs(Dg - D) <= 1e-7 * (sq[:, None] + sq[None, :]))
     rel = np.abs(Dg - D)[D > 0] / D[D > 0]
     t0 = time.time()
     worst = 0.0
@@ -132,7 +132,7 @@ def test_full_size_alg1_mode(cfg):
         assert np.all(ok | ok_alt), f"block {b}: {int(np.sum(~(ok | ok_alt)))} coordinates off"
         flips += int(np.sum(~ok & ok_alt))
         worst = max(worst, float(np.max(np.where(ok, np.abs(g - ref) / tol, 0.0))))
-    assert flips <= (1 << 24) // 1000
+    assert flips <= (1 << 24) // 10_000
     say(f"cfg {cfg} alg1: selected {ext.tolist()}, worst err/tol {worst:.3g}, ambiguous choices {flips} of {1 << 24}")
 
 

@@ -1,0 +1,134 @@
+"""Parity on the paper's own benchmark inputs (Section V-A): n = 7, 9, .., 39 gradients drawn from
+U(0,1)^d, f = floor((n-3)/4), here at d = 1e5 (the oracle does all 17 cells in seconds), for the four
+aggregation rules the sweep times: multi-Bulyan in both readings, multi-Krum, the median.
+
+These gradients are i.i.d.: nothing separates their Krum scores but chance, so this is the workload
+on which an fp32/fp64 difference in the distances could change the extracted list.  The check is
+therefore made through the scores.  With tau = the relative error the distance pass may commit on
+this input, (a) the list the GPU extracts must be *valid*: replaying its choices on the oracle's
+distances, every winner's score is within tau of the smallest score of its round, and every averaged
+set is, within tau, a set of smallest scores; (b) where the oracle's own decisions are all clearer
+than tau (winner against runner-up, and for the averaged sets the q-th score against the next),
+the lists and sets must be identical.  Cells where (b) does not apply are counted and reported.
+The outputs are then compared with the oracle's coordinate phase on the GPU's own lists.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_1905_04374_amd as mb
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+D_SWEEP = 100_000
+# U(0,1): |x|^2 = d/3, D = d/6, so 1e-7 (|x_i|^2 + |x_j|^2) = 4e-7 D is what the Gram form may be off by
+TAU = 4e-7
+
+
+def say(*a):
+    print("[case]", *a, flush=True)
+    sys.stdout.flush()
+
+
+def replay(D, f, sel, sets, tau):
+    """Validity of an extracted list (and, if given, of the averaged sets) on the distances D.
+    Returns the smallest relative gap the oracle itself saw at a decision (winner / runner-up, and
+    with sets the q-th / (q+1)-th score)."""
+    n = D.shape[0]
+    active = np.ones(n, np.uint8)
+    clear = np.inf
+    for t, w in enumerate(sel):
+        assert active[w], f"round {t}: gradient {w} extracted twice"
+        S = O.krum_scores(D, f, active)
+        k = int(active.sum())
+        q = max(k - f - 2, 0)
+        order = sorted(np.flatnonzero(active), key=lambda i: (S[i], i))
+        best = S[order[0]]
+        assert S[w] <= best + tau * max(best, 1e-300), f"round {t}: winner {w} has score {S[w]}, best {best}"
+        # (scores that tie exactly - no neighbours left, or two gradients that are each other's only
+        # neighbour - tie on both sides and go to the smaller index on both)
+        if len(order) > 1 and S[order[1]] != best:
+            clear = min(clear, (S[order[1]] - best) / max(S[order[1]], 1e-300))
+        if sets is not None:
+            members = np.flatnonzero(sets[t])
+            assert len(members) == min(q, k) and all(active[i] for i in members)
+            if 0 < q < k:
+                worst_in = max(S[i] for i in members)
+                others = [S[i] for i in order if i not in set(members.tolist())]
+                assert worst_in <= min(others) + tau * max(worst_in, 1e-300), f"round {t}: averaged set"
+                if S[order[q]] != S[order[q - 1]]:
+                    clear = min(clear, (S[order[q]] - S[order[q - 1]]) / max(S[order[q]], 1e-300))
+        active[w] = 0
+    return clear
+
+
+def out_close(got, ref, scale, what):
+    err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+    tol = 1e-5 * np.maximum(np.abs(ref), scale).astype(np.float64) + 1e-37
+    assert np.all(err <= tol), f"{what}: worst err/tol {np.max(err / tol):.3g}"
+
+
+def test_paper_sweep_grid_against_oracle():
+    ambiguous = []
+    for n in range(7, 40, 2):
+        f = (n - 3) // 4
+        Gt = W.uniform(n, D_SWEEP, DEV)
+        G = Gt.cpu().numpy()
+        D = O.pairwise_sqdist(G)
+        say("sweep cell", n, f)
+        # ---- distances
+        Dg = mb.pairwise_sqdist(Gt).cpu().numpy()
+        off = ~np.eye(n, dtype=bool)
+        assert np.max(np.abs(Dg - D)[off] / D[off]) <= TAU
+        for mode, omode in ((mb.MODE_SELECTED, O.MODE_SELECTED), (mb.MODE_ALG1, O.MODE_ALG1)):
+            theta, beta = O.params(n, f, omode)
+            out, sel = mb.mbulyan_aggregate_ex(Gt, f, mode=mode)
+            sel = sel.cpu().numpy()
+            out = out.cpu().numpy()
+            ext, sets_o, _ = O.multikrum_select(D, f, theta)
+            if omode == O.MODE_ALG1:
+                # the sets the library averaged: the selection on the library's own distances
+                sel2, sets_g, _ = mb.multikrum_select(torch.as_tensor(Dg).to(DEV), f, theta)
+                assert sel2.cpu().numpy().tolist() == sel.tolist()
+                sets_g = sets_g.cpu().numpy()
+                clear = replay(D, f, sel, sets_g, TAU)
+            else:
+                sets_g = None
+                clear = replay(D, f, sel, None, TAU)
+            if clear > TAU:
+                assert sel.tolist() == ext.tolist(), (n, mode)
+                if sets_g is not None:
+                    assert np.array_equal(sets_g, sets_o), (n, mode)
+            else:
+                ambiguous.append((n, "alg1" if omode else "selected", float(clear)))
+            if omode == O.MODE_SELECTED:
+                ref, scale = O.coordwise_selected(G, sel, beta, want_scale=True)
+                out_close(out, ref, scale, f"multi-Bulyan n={n}")
+            else:
+                ref, scale, margin, alt = O.coordwise_alg1(G, sel, sets_g, beta, want_extra=True)
+                tol = 1e-5 * np.maximum(np.abs(ref), scale) + 1e-37
+                ok = np.abs(out - ref) <= tol
+                ok_alt = (margin <= 4e-6 * scale) & (np.abs(out - alt) <= 1e-5 * np.maximum(np.abs(alt), scale) + 1e-37)
+                assert np.all(ok | ok_alt), (n, int(np.sum(~(ok | ok_alt))))
+                assert int(np.sum(~ok & ok_alt)) <= max(2, D_SWEEP // 10_000)
+        # ---- multi-Krum as a rule of its own, and the median
+        if n >= 2 * f + 3:
+            ref, mask = O.multikrum_aggregate(G, f)
+            out, mask_g = mb.multikrum_aggregate(Gt, f)
+            mask_g = mask_g.cpu().numpy()
+            clear = replay(D, f, [int(np.argmin(np.where(mask_g > 0, O.krum_scores(D, f), np.inf)))], mask_g[None, :], TAU)
+            if clear > TAU:
+                assert np.array_equal(mask_g, mask), n
+            else:
+                ambiguous.append((n, "multi-krum", float(clear)))
+            rows = G[mask_g.astype(bool)].astype(np.float64)
+            out_close(out.cpu().numpy(), rows.mean(0).astype(np.float32), np.abs(rows).mean(0), f"multi-Krum n={n}")
+        med = mb.coordwise_median(Gt).cpu().numpy()
+        assert np.array_equal(med, O.coordwise_median(G)), n          # n is odd: the median is an input value
+    say(f"sweep grid at d = {D_SWEEP}: {len(ambiguous)} of {17 * 3} (n, rule) cells had an oracle decision closer than "
+        f"{TAU:g}: {ambiguous}")
+    assert len(ambiguous) <= 3

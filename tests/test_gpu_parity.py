@@ -2,7 +2,7 @@
 to end, on seeded inputs that span several tiles and a ragged tail.
 
 Bars: indices, masks and counts bit-exact; scores bit-exact when fed the oracle's distances;
-distances within 1e-6 of the squared norms involved (Gram form) or 2e-6 relative (direct
+distances within 1e-7 of the squared norms involved (Gram form) or 2e-6 relative (direct
 form); outputs within 1e-5 of max(|reference|, mean |averaged values|), the conditioning scale of an
 average evaluated in fp32.
 """
@@ -42,13 +42,19 @@ def assert_out_close(got, ref, scale, rtol=1e-5, what="out"):
 
 
 def assert_dist_close(got, G, ref, algo):
-    """|D - ref| <= 1e-6 (|x_i|^2 + |x_j|^2) for the Gram form, 2e-6 D for the direct form."""
+    """|D - ref| <= 1e-7 (|x_i|^2 + |x_j|^2) for the Gram form (where that exceeds 2.6e-5 D the library
+    runs its second pass and the bound is on the centred norms: tests/test_gpu_conditioning.py), 2e-6 D for
+    the direct form.  1e-7 holds from ten thousand coordinates on; below, max(1e-7, 1e-5 / sqrt(d))."""
     got = got.cpu().numpy()
     sq = (G.astype(np.float64) ** 2).sum(1)
     if algo == mb.DIST_DIRECT:
         tol = 2e-6 * ref + 1e-30
     else:
-        tol = 1e-6 * (sq[:, None] + sq[None, :]) + 1e-30
+        # rounding errors of independent signs: the bound falls with the square root of the number of
+        # coordinates down to 1e-7 (measured: about 5e-6 / sqrt(d); 1e-8 at d >= 1e5); the fp32
+        # matrix-core variant also rounds its products
+        c = 1e-5 if algo == mb.DIST_GRAM_BF16 else 2e-5
+        tol = max(1e-7, c / np.sqrt(G.shape[1])) * (sq[:, None] + sq[None, :]) + 1e-30
     err = np.abs(got - ref)
     assert np.all(err <= tol), f"dist: worst err/tol {np.max(err / tol):.3g}"
     assert np.array_equal(got, got.T) and np.all(np.diag(got) == 0.0)
@@ -238,7 +244,9 @@ def test_coordwise_median():
 
 def alg1_compare(got, ref, scale, margin, alt):
     """Accept the reference, or, where the decision margin is below the rounding noise of
-    an fp32 evaluation of the multi-Krum averages, the other candidate."""
+    an fp32 evaluation of the multi-Krum averages, the other candidate.  Returns how often the
+    other candidate was taken: on fp32 gradients a few per million coordinates (measured 10 and 80
+    of 2^24 at full size); the tests fail above 1e-4 d."""
     got = got.cpu().numpy()
     tol = 1e-5 * np.maximum(np.abs(ref), scale) + 1e-37
     ok = np.abs(got - ref) <= tol
@@ -260,7 +268,7 @@ def test_coordwise_alg1(n, f, d):
     ref, scale, margin, alt = O.coordwise_alg1(G, ext, sets, beta, want_extra=True)
     got = mb.coordwise_trimmed_avg(gpu(G), gpu(ext), beta, agr_sets=gpu(sets))
     flips = alg1_compare(got, ref, scale, margin, alt)
-    assert flips <= max(2, d // 1000)
+    assert flips <= max(2, d // 10_000)
 
 
 @pytest.mark.parametrize("n,theta,beta,d", [(9, 4, 1, 3001), (20, 7, 3, 5000), (39, 19, 1, 20_000), (64, 30, 2, 2000)])
@@ -277,7 +285,7 @@ def test_coordwise_alg1_arbitrary_sets(n, theta, beta, d):
     ref, scale, margin, alt = O.coordwise_alg1(G, ext, sets, beta, want_extra=True)
     got = mb.coordwise_trimmed_avg(gpu(G), gpu(ext), beta, agr_sets=gpu(sets))
     flips = alg1_compare(got, ref, scale, margin, alt)
-    assert flips <= max(2, d // 500)
+    assert flips <= max(2, d // 10_000)
 
 
 def test_coordwise_alg1_regular_sets_take_the_register_path():
@@ -297,7 +305,7 @@ def test_coordwise_alg1_regular_sets_take_the_register_path():
     ref, scale, margin, alt = O.coordwise_alg1(G, ext, sets, beta, want_extra=True)
     got = mb.coordwise_trimmed_avg(gpu(G), gpu(ext), beta, agr_sets=gpu(sets))
     flips = alg1_compare(got, ref, scale, margin, alt)
-    assert flips <= 20
+    assert flips <= 2
 
 
 # ------------------------------------------------------------------ whole GAR
@@ -340,7 +348,7 @@ def test_aggregate_alg1_mode(cfg, d):
     out, sel = mb.mbulyan_aggregate_ex(Gt, f, mode=mb.MODE_ALG1, workspace=ws)
     assert sel.cpu().numpy().tolist() == ext.tolist()
     flips = alg1_compare(out, ref, scale, margin, alt)
-    assert flips <= max(2, G.shape[1] // 1000)
+    assert flips <= max(2, G.shape[1] // 10_000)
 
 
 def test_aggregate_chunked_equals_whole():
@@ -380,7 +388,7 @@ def test_aggregate_chunked_alg1_mode(in16):
     chunks = [Gt[:, a:b].contiguous() for a, b in zip(cuts[:-1], cuts[1:])]
     outs, sel = mb.mbulyan_aggregate_chunked(chunks, f, mode=mb.MODE_ALG1)
     assert sel.cpu().numpy().tolist() == ext.tolist()
-    assert alg1_compare(torch.cat(outs), ref, scale, margin, alt) <= max(2, d // 1000)
+    assert alg1_compare(torch.cat(outs), ref, scale, margin, alt) <= max(2, d // 10_000)
     outs2, sel2 = mb.mbulyan_aggregate_chunked(chunks, f, mode=mb.MODE_ALG1)
     assert torch.equal(sel, sel2) and torch.equal(torch.cat(outs), torch.cat(outs2))
 
@@ -455,7 +463,7 @@ def test_non_finite_byzantine_rows_are_never_chosen(algo, mode):
     assert torch.isfinite(out).all()
     if mode == "alg1":
         ref, scale, margin, alt = O.coordwise_alg1(G, ext, sets, beta, want_extra=True)
-        assert alg1_compare(out, ref, scale, margin, alt) <= max(2, d // 1000)
+        assert alg1_compare(out, ref, scale, margin, alt) <= max(2, d // 10_000)
     else:
         ref, scale = O.coordwise_selected(G, ext, beta, want_scale=True)
         assert_out_close(out, ref, scale)

@@ -110,6 +110,40 @@ def make(cfg: int, device="cpu", d: int | None = None, col0: int = 0,
     return fill(cfg, out, col0, placement, seed)
 
 
+def offset(n: int, f: int, d: int, kappa: float, device="cpu", byzantine_first: bool = False,
+           sigma: float = 0.05, seed: int = 0) -> torch.Tensor:
+    """Gradients that share a large common component, the regime the paper's convergence argument
+    assumes (Lemma 1: the gradient dominates its noise): correct worker w = g + N(0, (sigma (1 +
+    LADDER w))^2) with |g|^2 / d = (2 kappa - 1) sigma^2, so that squared norm : squared distance
+    between two correct workers is about kappa : 1.  The f Byzantine rows: the first half identical
+    copies of -2 g, the rest g + N(0, (20 sigma)^2) each.  They come last, or first when
+    byzantine_first is set (row 0 is then a Byzantine one)."""
+    gen = torch.Generator(device=device)
+    gen.manual_seed(BASE_SEED * 7 + 1009 * n + 31 * int(kappa) + seed)
+    nc = n - f
+
+    def randn(*shape):
+        return torch.randn(*shape, generator=gen, device=device, dtype=torch.float32)
+
+    out = torch.empty(n, d, device=device, dtype=torch.float32)
+    gamma = sigma * (2.0 * kappa - 1.0) ** 0.5
+    lo = 0
+    while lo < d:                                   # in blocks: no n x d temporaries on top of the result
+        w = min(BLOCK, d - lo)
+        g = randn(w).mul_(gamma)
+        blk = torch.empty(n, w, device=device, dtype=torch.float32)
+        ladder = sigma * (1.0 + LADDER * torch.arange(nc, device=device, dtype=torch.float32))
+        blk[:nc] = randn(nc, w).mul_(ladder[:, None]).add_(g[None, :])
+        h = f // 2
+        blk[nc:nc + h] = (-2.0 * g)[None, :]
+        blk[nc + h:] = randn(f - h, w).mul_(20.0 * sigma).add_(g[None, :])
+        if byzantine_first:
+            blk = torch.cat([blk[nc:], blk[:nc]], dim=0)
+        out[:, lo:lo + w] = blk
+        lo += w
+    return out
+
+
 def uniform(n: int, d: int, device="cpu", seed: int = 0) -> torch.Tensor:
     """n gradients drawn independently from U(0,1)^d: the input of the paper's
     aggregation-time benchmark (Section V-A)."""
