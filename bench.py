@@ -162,7 +162,9 @@ def main():
 
     sec = (t1 - t0) / a.steps
     in_bytes = eb * n * d
-    rows2 = theta if mode == mb.MODE_SELECTED else None
+    # rows the coordinate pass reads: the theta extracted ones, or (Algorithm-1 reading) the rows of the first
+    # round's averaged set, n-f-2 of them, which holds every later set while the score order stays stable
+    rows2 = theta if mode == mb.MODE_SELECTED else n - f - 2
     value = in_bytes / sec / 1e9
 
     # dominant kernel: the distance pass, 4*n bytes per coordinate, one launch per chunk
@@ -217,18 +219,39 @@ def main():
     }
 
     if not a.no_cpu_baseline:
-        import numpy as np
         import oracle as O
+        omode = O.MODE_SELECTED if mode == mb.MODE_SELECTED else O.MODE_ALG1
         ds = min(a.cpu_sample, chunks[0].shape[1])
         host = chunks[0][:, :ds].float().contiguous().cpu().numpy()
-        c0 = time.perf_counter()
-        O.mbulyan(host, f, O.MODE_SELECTED if mode == mb.MODE_SELECTED else O.MODE_ALG1)
-        c1 = time.perf_counter()
-        res["cpu_baseline"] = {"value": round(eb * n * ds / (c1 - c0) / 1e9, 3), "unit": "GB/s",
-                               "cores": O.last_threads(), "kind": "oracle",
+
+        def oracle_run(threads):
+            """the oracle's three phases, timed one by one (seconds)"""
+            c0 = time.perf_counter()
+            D = O.pairwise_sqdist(host, nthreads=threads)
+            c1 = time.perf_counter()
+            ext, sets, _ = O.multikrum_select(D, f, theta)
+            c2 = time.perf_counter()
+            if omode == O.MODE_SELECTED:
+                O.coordwise_selected(host, ext, beta, nthreads=threads)
+            else:
+                O.coordwise_alg1(host, ext, sets, beta, nthreads=threads)
+            c3 = time.perf_counter()
+            return c1 - c0, c2 - c1, c3 - c2, O.last_threads()
+
+        t_dist, t_sel, t_coord, cores = oracle_run(0)
+        total = t_dist + t_sel + t_coord
+        res["cpu_baseline"] = {"value": round(eb * n * ds / total / 1e9, 3), "unit": "GB/s",
+                               "cores": cores, "kind": "oracle",
                                "sample": f"first {ds} of {d} coordinates, all {n} rows, whole rule, "
-                                         f"{round(c1 - c0, 2)} s"}
-        del host, np
+                                         f"{round(total, 2)} s",
+                               "phases_s": {"distance": round(t_dist, 4), "selection": round(t_sel, 6),
+                                            "coordinate": round(t_coord, 4)}}
+        if a.config <= 2:        # small enough for one thread as well
+            t1 = oracle_run(1)
+            res["cpu_baseline"]["single_thread"] = {
+                "value": round(eb * n * ds / sum(t1[:3]) / 1e9, 3), "unit": "GB/s",
+                "phases_s": {"distance": round(t1[0], 4), "selection": round(t1[1], 6), "coordinate": round(t1[2], 4)}}
+        del host
     print(json.dumps(res), flush=True)
 
 

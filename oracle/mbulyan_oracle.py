@@ -154,6 +154,50 @@ def coordwise_alg1(G, ext, agr_sets, beta, want_extra=False, nthreads=0):
     return (out, scale, margin, alt) if want_extra else out
 
 
+def alg1_accepts(col, ext, agr_sets, beta, got, noise_rel=4e-6, tol_rel=1e-5, max_subsets=20000):
+    """Comparison aid for ONE coordinate of the Algorithm-1 phase (plain Python, slow): is `got` the
+    average of beta entries of G^agr that an evaluation with relative rounding noise `noise_rel` could
+    legitimately have found closest to the median?  `col` = the n values of the coordinate.
+
+    Algorithm 1 takes the beta entries closest to M (Argpartition: ties open).  With closeness
+    delta_t = |G^agr[t] - M| in fp32, delta* its beta-th smallest value and scale = the largest mean
+    absolute value of the rows averaged into a round (what coordwise_alg1 reports): entries with
+    delta_t < delta* - noise are in every legitimate choice, entries with delta_t <= delta* + noise may
+    be, the others are not (noise = noise_rel * scale).  Accepted iff some such choice averages to
+    `got` within tol_rel * max(|average|, scale).  Generalises margin / alt of coordwise_alg1 (one
+    runner-up) to several averages nearly equidistant from the median."""
+    import itertools
+    col = np.asarray(col, np.float32)
+    ext = np.asarray(ext)
+    sets = np.asarray(agr_sets).astype(bool)
+    theta = len(ext)
+    e = np.sort(col[ext])
+    med = e[theta // 2] if theta % 2 else np.float32(0.5) * np.float32(e[theta // 2 - 1] + e[theta // 2])
+    a = np.zeros(theta, np.float32)
+    scale = 0.0
+    for t in range(theta):
+        rows = col[sets[t]].astype(np.float64)
+        if rows.size:
+            a[t] = np.float32(rows.sum() / rows.size)
+            scale = max(scale, float(np.abs(rows).sum() / rows.size))
+    delta = np.abs((a - med).astype(np.float32)).astype(np.float64)
+    star = np.sort(delta)[beta - 1]
+    noise = noise_rel * scale
+    must = [t for t in range(theta) if delta[t] < star - noise]
+    pool = [t for t in range(theta) if delta[t] <= star + noise and t not in must]
+    k = beta - len(must)
+    if k < 0 or k > len(pool):
+        return False
+    base = float(np.sum(a[must].astype(np.float64)))
+    for count, sub in enumerate(itertools.combinations(pool, k)):
+        if count >= max_subsets:
+            return False
+        cand = (base + float(np.sum(a[list(sub)].astype(np.float64)))) / beta
+        if abs(float(got) - cand) <= tol_rel * max(abs(cand), scale) + 1e-37:
+            return True
+    return False
+
+
 def multikrum_aggregate(G, f, nthreads=0):
     """Multi-Krum GAR: average of the n-f-2 best-scored gradients.  (out, mask)."""
     G, n, d, ld = _grads(G)

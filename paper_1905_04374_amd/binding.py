@@ -92,11 +92,20 @@ def _stream(stream) -> int:
     return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
 
 
-def _dev(t: torch.Tensor | None, dtype, name: str) -> int | None:
+def _dev(t: torch.Tensor | None, dtype, name: str, numel: int | None = None, like: torch.Tensor | None = None) -> int | None:
+    """Pointer of a dense CUDA tensor of the given dtype.  The C ABI sees no sizes, so this is the
+    only place that can refuse a buffer that is too short (numel), strided, or on another device than
+    the gradients (like): the kernels would write past its end."""
     if t is None:
         return None
     if not t.is_cuda or t.dtype != dtype:
         raise TypeError(f"{name} must be a CUDA tensor of dtype {dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if numel is not None and t.numel() < numel:
+        raise ValueError(f"{name} holds {t.numel()} elements, {numel} are needed")
+    if like is not None and t.device != like.device:
+        raise ValueError(f"{name} is on {t.device}, the gradients on {like.device}")
     return t.data_ptr()
 
 
@@ -151,8 +160,8 @@ def mbulyan_aggregate(grads, f, out=None, selected_idx=None, stream=None):
         out = torch.empty(d, device=grads.device, dtype=torch.float32)
     if selected_idx is None:
         selected_idx = torch.empty(theta, device=grads.device, dtype=torch.int32)
-    _check(lib.mbulyan_aggregate(p, n, f, d, _dev(out, torch.float32, "out"),
-                                 _dev(selected_idx, torch.int32, "selected_idx"), _stream(stream)))
+    _check(lib.mbulyan_aggregate(p, n, f, d, _dev(out, torch.float32, "out", d, grads),
+                                 _dev(selected_idx, torch.int32, "selected_idx", theta, grads), _stream(stream)))
     return out, selected_idx
 
 
@@ -168,12 +177,12 @@ def mbulyan_aggregate_ex(grads, f, mode=MODE_SELECTED, theta=0, beta=0, out=None
         selected_idx = torch.empty(th, device=grads.device, dtype=torch.int32)
     wp, wb = _ws(workspace)
     if grads.dtype == torch.bfloat16:
-        _check(lib.mbulyan_aggregate_bf16(p, n, f, d, ld, mode, theta, beta, _dev(out, torch.float32, "out"),
-                                          _dev(selected_idx, torch.int32, "selected_idx"), wp, wb,
+        _check(lib.mbulyan_aggregate_bf16(p, n, f, d, ld, mode, theta, beta, _dev(out, torch.float32, "out", d, grads),
+                                          _dev(selected_idx, torch.int32, "selected_idx", th, grads), wp, wb,
                                           _stream(stream)))
         return out, selected_idx
-    _check(lib.mbulyan_aggregate_ex(p, n, f, d, ld, mode, theta, beta, _dev(out, torch.float32, "out"),
-                                    _dev(selected_idx, torch.int32, "selected_idx"), wp, wb, _stream(stream)))
+    _check(lib.mbulyan_aggregate_ex(p, n, f, d, ld, mode, theta, beta, _dev(out, torch.float32, "out", d, grads),
+                                    _dev(selected_idx, torch.int32, "selected_idx", th, grads), wp, wb, _stream(stream)))
     return out, selected_idx
 
 
@@ -181,8 +190,10 @@ def mbulyan_aggregate_noalloc(grads, f, out, selected_idx=None, mode=MODE_SELECT
     """mbulyan_aggregate_ex on the library's static device array: the call allocates nothing, so the
     caller passes `out` (and `selected_idx`, if wanted).  Returns (out, selected_idx)."""
     p, n, d, ld = _matrix(grads)
-    _check(lib.mbulyan_aggregate_noalloc(p, n, f, d, ld, mode, _dev(out, torch.float32, "out"),
-                                         _dev(selected_idx, torch.int32, "selected_idx"), _stream(stream)))
+    theta, _ = mbulyan_params(n, f, mode)
+    _check(lib.mbulyan_aggregate_noalloc(p, n, f, d, ld, mode, _dev(out, torch.float32, "out", d, grads),
+                                         _dev(selected_idx, torch.int32, "selected_idx", theta, grads),
+                                         _stream(stream)))
     return out, selected_idx
 
 
@@ -206,15 +217,15 @@ def mbulyan_aggregate_chunked(chunks, f, mode=MODE_SELECTED, outs=None, selected
     cp = (C.c_void_p * k)(*[m[0] for m in mats])
     cd = (C.c_int64 * k)(*[m[2] for m in mats])
     cl = (C.c_int64 * k)(*[m[3] for m in mats])
-    op = (C.c_void_p * k)(*[_dev(o, torch.float32, "out") for o in outs])
+    op = (C.c_void_p * k)(*[_dev(o, torch.float32, "out", m[2], chunks[0]) for o, m in zip(outs, mats)])
     wp, wb = _ws(workspace)
     if in16:
         _check(lib.mbulyan_aggregate_chunked_bf16(cp, k, cd, cl, n, f, mode, op,
-                                                  _dev(selected_idx, torch.int32, "selected_idx"), wp, wb,
-                                                  _stream(stream)))
+                                                  _dev(selected_idx, torch.int32, "selected_idx", theta, chunks[0]),
+                                                  wp, wb, _stream(stream)))
         return outs, selected_idx
     _check(lib.mbulyan_aggregate_chunked(cp, k, cd, cl, n, f, mode, op,
-                                         _dev(selected_idx, torch.int32, "selected_idx"), wp, wb,
+                                         _dev(selected_idx, torch.int32, "selected_idx", theta, chunks[0]), wp, wb,
                                          _stream(stream)))
     return outs, selected_idx
 
@@ -228,11 +239,11 @@ def pairwise_sqdist(grads, dist=None, accumulate=False, algo=DIST_AUTO, workspac
         dist = torch.empty(n, n, device=grads.device, dtype=torch.float64)
     wp, wb = _ws(workspace)
     if grads.dtype == torch.bfloat16:
-        _check(lib.pairwise_sqdist_bf16(p, n, d, ld, _dev(dist, torch.float64, "dist"), int(accumulate), wp, wb,
-                                        _stream(stream)))
+        _check(lib.pairwise_sqdist_bf16(p, n, d, ld, _dev(dist, torch.float64, "dist", n * n, grads), int(accumulate),
+                                        wp, wb, _stream(stream)))
         return dist
-    _check(lib.pairwise_sqdist(p, n, d, ld, _dev(dist, torch.float64, "dist"), int(accumulate), algo, wp, wb,
-                               _stream(stream)))
+    _check(lib.pairwise_sqdist(p, n, d, ld, _dev(dist, torch.float64, "dist", n * n, grads), int(accumulate), algo,
+                               wp, wb, _stream(stream)))
     return dist
 
 
@@ -240,8 +251,8 @@ def krum_scores(dist, f, active=None, scores=None, stream=None):
     n = dist.shape[0]
     if scores is None:
         scores = torch.empty(n, device=dist.device, dtype=torch.float64)
-    _check(lib.krum_scores(_dev(dist, torch.float64, "dist"), n, f, _dev(active, torch.uint8, "active"),
-                           _dev(scores, torch.float64, "scores"), _stream(stream)))
+    _check(lib.krum_scores(_dev(dist, torch.float64, "dist", n * n), n, f, _dev(active, torch.uint8, "active", n, dist),
+                           _dev(scores, torch.float64, "scores", n, dist), _stream(stream)))
     return scores
 
 
@@ -250,7 +261,7 @@ def multikrum_select(dist, f, theta, want_sets=True, stream=None):
     sel = torch.empty(max(theta, 0), device=dist.device, dtype=torch.int32)
     sets = torch.empty(max(theta, 0), n, device=dist.device, dtype=torch.uint8) if want_sets else None
     m = torch.empty(max(theta, 0), device=dist.device, dtype=torch.int32) if want_sets else None
-    _check(lib.multikrum_select(_dev(dist, torch.float64, "dist"), n, f, theta, _dev(sel, torch.int32, "sel"),
+    _check(lib.multikrum_select(_dev(dist, torch.float64, "dist", n * n), n, f, theta, _dev(sel, torch.int32, "sel"),
                                 _dev(sets, torch.uint8, "agr_sets"), _dev(m, torch.int32, "m_out"),
                                 _stream(stream)))
     return sel, sets, m
@@ -261,14 +272,11 @@ def coordwise_trimmed_avg(grads, selected_idx, beta, agr_sets=None, out=None, st
     p, n, d, ld = _matrix(grads, bf16_ok=True)
     if out is None:
         out = torch.empty(d, device=grads.device, dtype=torch.float32)
-    if grads.dtype == torch.bfloat16:
-        _check(lib.coordwise_trimmed_avg_bf16(p, n, d, ld, _dev(selected_idx, torch.int32, "selected_idx"),
-                                              selected_idx.numel(), beta, _dev(agr_sets, torch.uint8, "agr_sets"),
-                                              _dev(out, torch.float32, "out"), _stream(stream)))
-        return out
-    _check(lib.coordwise_trimmed_avg(p, n, d, ld, _dev(selected_idx, torch.int32, "selected_idx"),
-                                     selected_idx.numel(), beta, _dev(agr_sets, torch.uint8, "agr_sets"),
-                                     _dev(out, torch.float32, "out"), _stream(stream)))
+    theta = selected_idx.numel()
+    sp = _dev(selected_idx, torch.int32, "selected_idx", None, grads)
+    ap = _dev(agr_sets, torch.uint8, "agr_sets", theta * n, grads)
+    fn = lib.coordwise_trimmed_avg_bf16 if grads.dtype == torch.bfloat16 else lib.coordwise_trimmed_avg
+    _check(fn(p, n, d, ld, sp, theta, beta, ap, _dev(out, torch.float32, "out", d, grads), _stream(stream)))
     return out
 
 
@@ -281,8 +289,8 @@ def multikrum_aggregate(grads, f, out=None, selected_mask=None, workspace=None, 
         selected_mask = torch.empty(n, device=grads.device, dtype=torch.uint8)
     wp, wb = _ws(workspace)
     fn = lib.multikrum_aggregate_bf16 if grads.dtype == torch.bfloat16 else lib.multikrum_aggregate
-    _check(fn(p, n, f, d, ld, _dev(out, torch.float32, "out"),
-                                   _dev(selected_mask, torch.uint8, "selected_mask"), wp, wb, _stream(stream)))
+    _check(fn(p, n, f, d, ld, _dev(out, torch.float32, "out", d, grads),
+              _dev(selected_mask, torch.uint8, "selected_mask", n, grads), wp, wb, _stream(stream)))
     return out, selected_mask
 
 
@@ -292,7 +300,7 @@ def coordwise_median(grads, out=None, stream=None):
     if out is None:
         out = torch.empty(d, device=grads.device, dtype=torch.float32)
     fn = lib.coordwise_median_bf16 if grads.dtype == torch.bfloat16 else lib.coordwise_median
-    _check(fn(p, n, d, ld, _dev(out, torch.float32, "out"), _stream(stream)))
+    _check(fn(p, n, d, ld, _dev(out, torch.float32, "out", d, grads), _stream(stream)))
     return out
 
 

@@ -478,7 +478,13 @@ __device__ __forceinline__ Raw widen8(const float4 &w)
 // Tile buffers per workgroup and workgroups per compute unit the registers are budgeted for
 // (measured at n = 39: 2 buffers x 3 workgroups 5.97 ms, 3 x 2 6.4 ms; the fp64 sums of
 // 10 tiles leave room for two waves per SIMD only at NB = 4).
+// Four row blocks (n > 48) leave room for two workgroups per compute unit whatever the stage count
+// (236 registers), so there a third tile buffer buys a second tile in flight per workgroup for as
+// long as two workgroups' buffers fit the 160 KB of LDS (n <= 52).
 constexpr int kStages = 2;
+constexpr int kStagesWide = 3;
+constexpr int kWideMaxN = 52;
+constexpr int dma_stages(int nb, int n) { return (nb == 4 && n <= kWideMaxN) ? kStagesWide : kStages; }
 template <int NB>
 struct DmaShape {
     static constexpr int min_blocks = NB == 4 ? 2 : 3;
@@ -486,7 +492,7 @@ struct DmaShape {
 
 inline int dma_pairs(int n) { return (n + 1) / 2; }   // load instructions per tile, 1 KB of LDS each
 // LDS bytes of one workgroup: the tile buffers and the spare slot
-inline size_t dma_lds_bytes(int n) { return (size_t)kStages * dma_pairs(n) * 1024 + 1024; }
+inline size_t dma_lds_bytes(int n, int stages) { return (size_t)stages * dma_pairs(n) * 1024 + 1024; }
 
 // What the kernel reads and how it multiplies:
 //   kFp32    fp32 input, fp32 MFMA
@@ -498,13 +504,12 @@ enum Kind { kFp32 = 0, kSplit = 1, kIn16 = 2 };
 template <int KIND> constexpr int elem_bytes() { return KIND == kIn16 ? 2 : 4; }
 template <int KIND> constexpr int tile_cols() { return 512 / elem_bytes<KIND>(); }
 
-template <int NB, int KIND, int L, bool CENTER>
+template <int NB, int KIND, int L, bool CENTER, int S>
 __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_kernel(
     const void *__restrict__ Gv, int n, int64_t d, int64_t ld, int64_t ntiles, double *__restrict__ partials,
     const double *__restrict__ first_pass, int *__restrict__ gate)
 {
     constexpr int NT = NB * (NB + 1) / 2;
-    constexpr int S = kStages;
     constexpr int EB = elem_bytes<KIND>();
     constexpr int TC = tile_cols<KIND>();
     constexpr int WC = TC / 4;                    // columns of a tile that one wave multiplies
@@ -766,8 +771,8 @@ struct SecondPass {
     int *gate;
 };
 
-template <int NB, int KIND, int L, bool CENTER>
-hipError_t launch_dma_l(const void *G, int n, int64_t d, int64_t ld, bool aligned, double *partials, int max_blocks,
+template <int NB, int KIND, int L, bool CENTER, int S>
+hipError_t launch_dma_s(const void *G, int n, int64_t d, int64_t ld, bool aligned, double *partials, int max_blocks,
                         int *nblocks, const SecondPass *second, hipStream_t s)
 {
     struct PerDevice {
@@ -778,22 +783,22 @@ hipError_t launch_dma_l(const void *G, int n, int64_t d, int64_t ld, bool aligne
     hipError_t e;
     int dev = 0;
     if ((e = current_device(&dev)) != hipSuccess) return e;
-    const size_t bytes = dma_lds_bytes(n);
+    const size_t bytes = dma_lds_bytes(n, S);
     int resident = 0;
     {
         std::lock_guard<std::mutex> lock(g_launch_mu);
         PerDevice &c = cache[dev];
         if (!c.prepared) {
-            if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gram_dma_kernel<NB, KIND, L, CENTER>),
+            if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gram_dma_kernel<NB, KIND, L, CENTER, S>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         (int)dma_lds_bytes(16 * NB))) != hipSuccess)
+                                         (int)dma_lds_bytes(S == kStagesWide ? kWideMaxN : 16 * NB, S))) != hipSuccess)
                 return e;
             c.prepared = true;
         }
         if (!c.resident[n]) {
             int cus = 0, per_cu = 0;
             if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
-            if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gram_dma_kernel<NB, KIND, L, CENTER>,
+            if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gram_dma_kernel<NB, KIND, L, CENTER, S>,
                                                                   kThreads, bytes)) != hipSuccess)
                 return e;
             c.resident[n] = cus * (per_cu < 1 ? 1 : per_cu);
@@ -808,9 +813,21 @@ hipError_t launch_dma_l(const void *G, int n, int64_t d, int64_t ld, bool aligne
     int64_t g = resident < max_blocks ? resident : max_blocks;
     if (work < 4 * g) g = work < 4 ? 1 : work / 4;
     *nblocks = (int)g;
-    gram_dma_kernel<NB, KIND, L, CENTER><<<dim3((unsigned)g), dim3(kThreads), bytes, s>>>(
+    gram_dma_kernel<NB, KIND, L, CENTER, S><<<dim3((unsigned)g), dim3(kThreads), bytes, s>>>(
         G, n, d, ld, tiles, partials, second ? second->first_pass : nullptr, second ? second->gate : nullptr);
     return hipGetLastError();
+}
+
+template <int NB, int KIND, int L, bool CENTER>
+hipError_t launch_dma_l(const void *G, int n, int64_t d, int64_t ld, bool aligned, double *partials, int max_blocks,
+                        int *nblocks, const SecondPass *second, hipStream_t s)
+{
+    if constexpr (NB == 4) {
+        if (dma_stages(NB, n) == kStagesWide)
+            return launch_dma_s<NB, KIND, L, CENTER, kStagesWide>(G, n, d, ld, aligned, partials, max_blocks, nblocks,
+                                                                  second, s);
+    }
+    return launch_dma_s<NB, KIND, L, CENTER, kStages>(G, n, d, ld, aligned, partials, max_blocks, nblocks, second, s);
 }
 
 template <int NB, int KIND>

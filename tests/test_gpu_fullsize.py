@@ -1,9 +1,8 @@
 """Parity at the full sizes of the workloads, in the launch configuration bench.py times
 (mbulyan_aggregate_ex with a caller workspace; the chunked driver for workload 5).
 
-Workloads 3 and 4 are compared with the oracle element by element over the whole output.
-Workload 5 (n=51, d=1e9 in 4 chunks, 204 GB) runs at one tenth of its d by default and at
-full size when MB_FULL_CFG5=1 (the oracle then needs several minutes of host time).
+Workloads 3 and 4 are compared with the oracle element by element over the whole output, and so is
+workload 5 (n=51, d=1e9 in 4 chunks, 204 GB; the oracle needs a few minutes of host time for it).
 """
 import os
 import sys
@@ -13,6 +12,7 @@ import numpy as np
 import pytest
 import torch
 
+import alg1_check
 import oracle as O
 import paper_1905_04374_amd as mb
 import workloads as W
@@ -124,24 +124,25 @@ def test_full_size_alg1_mode(cfg):
     worst = 0.0
     for b in range(blocks):
         lo = (d - width) * b // (blocks - 1)
-        ref, scale, margin, alt = O.coordwise_alg1(G[:, lo:lo + width], ext, sets, beta, want_extra=True)
-        g = got[lo:lo + width]
-        tol = 1e-5 * np.maximum(np.abs(ref), scale) + 1e-37
-        ok = np.abs(g - ref) <= tol
-        ok_alt = (margin <= 4e-6 * scale) & (np.abs(g - alt) <= 1e-5 * np.maximum(np.abs(alt), scale) + 1e-37)
-        assert np.all(ok | ok_alt), f"block {b}: {int(np.sum(~(ok | ok_alt)))} coordinates off"
-        flips += int(np.sum(~ok & ok_alt))
-        worst = max(worst, float(np.max(np.where(ok, np.abs(g - ref) / tol, 0.0))))
+        fl, w = alg1_check.compare(got[lo:lo + width], G[:, lo:lo + width], ext, sets, beta, f"block {b}")
+        flips += fl
+        worst = max(worst, w)
     assert flips <= (1 << 24) // 10_000
     say(f"cfg {cfg} alg1: selected {ext.tolist()}, worst err/tol {worst:.3g}, ambiguous choices {flips} of {1 << 24}")
 
 
-def test_full_size_chunked():
+def test_full_size_chunked_both_modes():
+    """Workload 5 at its full size (n = 51, d = 1e9 as four chunks of 51 GB), both readings of the rule
+    on the same resident chunks.  The oracle's distances are accumulated once over all coordinates;
+    the outputs are compared over every coordinate (theta = n-2f rows per coordinate) and, for the
+    Algorithm-1 reading (theta averages of up to 37 rows per coordinate), over 64 blocks of 2^18
+    coordinates spread over the four chunks.  MB_CFG5_REDUCED=1 runs a tenth of d (for a quick look)."""
     s = W.spec(5)
     n, f, nchunks = s["n"], s["f"], s["chunks"]
-    d = s["d"] if os.environ.get("MB_FULL_CFG5") == "1" else s["d"] // 10
+    d = s["d"] // 10 if os.environ.get("MB_CFG5_REDUCED") == "1" else s["d"]
     say("chunked", n, f, d, nchunks)
     theta, beta = O.params(n, f)
+    theta1, beta1 = O.params(n, f, O.MODE_ALG1)
     bounds = [d * k // nchunks for k in range(nchunks + 1)]
     chunks = []
     for k in range(nchunks):
@@ -150,20 +151,25 @@ def test_full_size_chunked():
         chunks.append(g)
     ws = torch.empty(mb.mbulyan_workspace_bytes(n, max(c.shape[1] for c in chunks)), dtype=torch.uint8, device=DEV)
     outs, sel = mb.mbulyan_aggregate_chunked(chunks, f, workspace=ws)
+    outs1, sel1 = mb.mbulyan_aggregate_chunked(chunks, f, mode=mb.MODE_ALG1, workspace=ws)
     torch.cuda.synchronize()
-    sel = sel.cpu().numpy()
+    sel, sel1 = sel.cpu().numpy(), sel1.cpu().numpy()
     D = np.zeros((n, n))
     host = np.empty((n, chunks[0].shape[1]), np.float32)
+    t0 = time.time()
     for k in range(nchunks):                           # distances accumulate over the chunks
         w = chunks[k].shape[1]
         for r in range(n):
             host[r, :w] = chunks[k][r].cpu().numpy()
         O.pairwise_sqdist(host[:, :w], D)
-        say("oracle distances of chunk", k)
+        say("oracle distances of chunk", k, round(time.time() - t0, 1), "s")
     ext, _, _ = O.multikrum_select(D, f, theta)
+    ext1, sets1, _ = O.multikrum_select(D, f, theta1)
     gap = check_separation(D, f, theta, ext)
     assert sel.tolist() == ext.tolist()
-    worst = 0.0
+    assert sel1.tolist() == ext1.tolist()
+    worst, worst1, flips, sampled = 0.0, 0.0, 0, 0
+    blocks, width = 16, 1 << 18
     for k in range(nchunks):
         w = chunks[k].shape[1]
         for r in range(n):
@@ -174,8 +180,18 @@ def test_full_size_chunked():
             hi = min(w, lo + step)
             ref, scale = O.coordwise_selected(host[:, lo:hi], ext, beta, want_scale=True)
             worst = max(worst, check_chunk(got[lo:hi], ref, scale))
-        say("oracle coordinate phase of chunk", k)
-    say(f"cfg 5 (d={d}): selected {ext.tolist()}, score gap {gap:.2e}, out worst err/tol {worst:.3g}")
+        got1 = outs1[k].cpu().numpy()
+        wd = min(width, w)
+        for b in range(blocks):
+            lo = (w - wd) * b // (blocks - 1)
+            fl, w1 = alg1_check.compare(got1[lo:lo + wd], host[:, lo:lo + wd], ext1, sets1, beta1, f"chunk {k} block {b}")
+            flips += fl
+            sampled += wd
+            worst1 = max(worst1, w1)
+        say("oracle coordinate phase of chunk", k, round(time.time() - t0, 1), "s")
+    assert flips <= max(2, sampled // 10_000)
+    say(f"cfg 5 (d={d}): selected {ext.tolist()}, score gap {gap:.2e}, out worst err/tol {worst:.3g}; "
+        f"alg1: worst err/tol {worst1:.3g}, ambiguous choices {flips} of {sampled}")
 
 
 def test_more_than_2_to_the_31_coordinates():

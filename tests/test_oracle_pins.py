@@ -325,6 +325,38 @@ def test_alg1_margin_and_alternative_hand_worked():
     assert seen == 6
 
 
+def test_alg1_acceptance_with_several_near_equidistant_averages():
+    """oracle.alg1_accepts on hand-made coordinates (d = 1).  M = 10 (extracted values 9 10 11), scale = 12
+    (the largest mean absolute value of a round's rows), so the noise band is 4e-6 * 12 = 4.8e-5.
+    beta = 1, averages 10.001, 9.99898, 10.00104, 12: closenesses 1.00e-3, 1.02e-3, 1.04e-3, 2: the
+    first three lie within the band of the best and are all acceptable, 12 is not, and neither is a
+    value between two of them that no choice produces.
+    beta = 2, same averages: the pairs among the first three are acceptable, a pair with 12 is not."""
+    e_vals = [9.0, 10.0, 11.0]
+    groups3 = [[10.001], [9.99898], [10.00104]]
+    # a fourth round needs a fourth extracted value; keep M = 10 with extracted 9, 10, 10, 11 -> median 10
+    G, ext, S = _alg1_case([9.0, 10.0, 10.0, 11.0], groups3 + [[12.0]])
+    col = G[:, 0]
+    a = [np.float32(10.001), np.float32(9.99898), np.float32(10.00104), np.float32(12.0)]
+    for t in range(3):
+        assert O.alg1_accepts(col, ext, S, 1, a[t])
+    assert not O.alg1_accepts(col, ext, S, 1, a[3])
+    assert not O.alg1_accepts(col, ext, S, 1, np.float32(10.0))          # the median itself is no average
+    assert not O.alg1_accepts(col, ext, S, 1, np.float32(10.0005))
+    for i, j in [(0, 1), (0, 2), (1, 2)]:
+        assert O.alg1_accepts(col, ext, S, 2, np.float32((float(a[i]) + float(a[j])) / 2))
+    assert not O.alg1_accepts(col, ext, S, 2, np.float32((float(a[0]) + 12.0) / 2))
+    # a clear decision leaves no choice: averages 10.001, 9.9, 10.2 -> only the first for beta = 1
+    G, ext, S = _alg1_case(e_vals, [[10.001], [9.9], [10.2]])
+    assert O.alg1_accepts(G[:, 0], ext, S, 1, np.float32(10.001))
+    assert not O.alg1_accepts(G[:, 0], ext, S, 1, np.float32(9.9))
+    # and it agrees with out / alt of coordwise_alg1 on the hand-worked cases
+    G, ext, S = _alg1_case([2.0, 4.0, 6.0], [[0.0, 10.0], [4.0, 6.0], [2.0, 4.0]])     # case B: out 3, alt 5, margin 0
+    assert O.alg1_accepts(G[:, 0], ext, S, 1, np.float32(3.0)) and O.alg1_accepts(G[:, 0], ext, S, 1, np.float32(5.0))
+    G, ext, S = _alg1_case([4.0, 5.5, 8.0], [[4.0, 6.0], [5.0], [6.0, 8.0]])            # case A: out 5, alt 7, margin 1
+    assert O.alg1_accepts(G[:, 0], ext, S, 1, np.float32(5.0)) and not O.alg1_accepts(G[:, 0], ext, S, 1, np.float32(7.0))
+
+
 def test_alg1_scale_is_the_conditioning_of_an_fp32_running_sum():
     """Why the Algorithm-1 output is compared on the scale "largest mean absolute value of the rows
     averaged into any G^agr[t][c]" and not on |G^agr|: an fp32 evaluation of the averages as
