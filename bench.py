@@ -80,9 +80,9 @@ def main():
     ap.add_argument("--d", type=int, default=None, help="override the number of coordinates")
     ap.add_argument("--mode", choices=["selected", "alg1"], default="selected")
     ap.add_argument("--dist-algo", choices=["auto", "direct", "gram", "gram_bf16"], default="auto")
-    ap.add_argument("--input-dtype", choices=["f32", "bf16"], default="f32",
-                    help="bf16: the workload rounded to bf16 once, aggregated by the bf16 entry points "
-                         "(half the bytes; a second workload, not the headline)")
+    ap.add_argument("--input-dtype", choices=["f32", "bf16", "fp16"], default="f32",
+                    help="bf16 / fp16: the workload rounded to that format once, aggregated by the entry points "
+                         "for 16-bit storage (half the bytes; a second workload, not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run one plain device copy of this many MiB before the timed region "
@@ -112,7 +112,8 @@ def main():
     nchunks = spec["chunks"] if a.d is None else 1
     mode = mb.MODE_SELECTED if a.mode == "selected" else mb.MODE_ALG1
     theta, beta = mb.mbulyan_params(n, f, mode)
-    in16 = a.input_dtype == "bf16"
+    in16 = a.input_dtype in ("bf16", "fp16")
+    dt16 = torch.bfloat16 if a.input_dtype == "bf16" else torch.float16
     eb = 2.0 if in16 else 4.0
 
     # ---- inputs resident in HBM before the timed region ----------------------
@@ -122,7 +123,7 @@ def main():
         g = torch.empty(n, bounds[k + 1] - bounds[k], device=dev, dtype=torch.float32)
         W.fill(a.config, g, bounds[k])
         if in16:
-            g16 = torch.empty(g.shape, device=dev, dtype=torch.bfloat16)
+            g16 = torch.empty(g.shape, device=dev, dtype=dt16)
             for r in range(n):                     # row by row: no second fp32-sized temporary
                 g16[r].copy_(g[r])
             g = g16
@@ -179,10 +180,10 @@ def main():
     kname = {"direct": "dist_direct_kernel", "gram": f"{gram}<{nb}, fp32>"}.get(
         a.dist_algo, f"{gram}<{nb}, bf16>")
     if in16:
-        kname = f"gram_dma_kernel<{nb}, bf16 input>"
+        kname = f"gram_dma_kernel<{nb}, {a.input_dtype} input>"
     roofline = {"kernel": kname, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get((a.config, "in16" if in16 else "gram_bf16"))
+                "traffic": MEASURED_TRAFFIC_BYTES.get((a.config, {"f32": "gram_bf16", "bf16": "in16"}.get(a.input_dtype)))
                 if (bf16 and a.d is None) else None,
                 "algorithmic_bytes": dist_bytes,
                 "avg_launch_ms": round(dist_avg_s * 1e3, 4), "launches": dist_launches}
@@ -191,8 +192,8 @@ def main():
         # (split bf16) products per tile and coordinate
         tiles = nb * (nb + 1) // 2
         flops = tiles * 256 * 2 * (1 if in16 else 6 if bf16 else 1) * (d / nchunks)
-        peak = MFMA_BF16_PEAK_TFLOPS if (bf16 or in16) else MFMA_FP32_PEAK_TFLOPS
-        roofline["matrix_cores"] = {"dtype": "bf16" if (bf16 or in16) else "f32", "tflops": round(flops / dist_avg_s / 1e12, 1),
+        peak = MFMA_BF16_PEAK_TFLOPS if (bf16 or in16) else MFMA_FP32_PEAK_TFLOPS   # bf16 and fp16: the same dense peak
+        roofline["matrix_cores"] = {"dtype": a.input_dtype if in16 else "bf16" if bf16 else "f32", "tflops": round(flops / dist_avg_s / 1e12, 1),
                                     "peak": peak, "frac": round(flops / dist_avg_s / 1e12 / peak, 4)}
 
     per_stage = {k: round(v[0] / a.steps, 4) for k, v in stages.items()}
@@ -205,11 +206,11 @@ def main():
 
     res = {
         "metric": "multi-Bulyan aggregation GB/s of gradient input (n*d*4B/s), 1 GPU" if not in16 else
-                  "multi-Bulyan aggregation GB/s of gradient input (n*d*2B/s, bf16 gradients), 1 GPU",
+                  f"multi-Bulyan aggregation GB/s of gradient input (n*d*2B/s, {a.input_dtype} gradients), 1 GPU",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": round(sec * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"configs[{a.config - 1}]: n={n} f={f} d={d} {'bf16 gradients' if in16 else 'fp32'}, "
+        "config": {"workload": f"configs[{a.config - 1}]: n={n} f={f} d={d} {a.input_dtype + ' gradients' if in16 else 'fp32'}, "
                                f"mode={a.mode}, "
                                f"theta={theta} beta={beta}, chunks={nchunks}"},
         "hbm_frac_input_bytes": round(value / HBM_PEAK_GBS, 4),

@@ -235,22 +235,27 @@ int coordwise_trimmed_avg(const float *grads, int n, int64_t d, int64_t ld,
                           const uint8_t *agr_sets, float *out, void *stream);
 
 /*
- * Gradients stored as bf16 (raw 16-bit words, the upper half of the fp32 bit
- * pattern; ld in elements): the same operations of Algorithm 1 on half the
- * bytes.  Every bf16 value is an fp32 value, so the results are those of the
- * fp32 entry points on the widened matrix, to the same tolerances; distances
- * and out stay fp64 / fp32.  The fast paths need rows that start on 16-byte
- * boundaries (distance pass: grads % 16 == 0 and ld % 8 == 0) and 4-byte
- * boundaries (coordinate pass: grads % 4 == 0, ld % 2 == 0, out % 8 == 0);
- * anything else takes element loads.  Arguments as for the fp32 entry point
- * of the same name:
- *   pairwise_sqdist_bf16            pairwise_sqdist (Gram form; there is one
- *                                   exact product per pair and coordinate)
- *   coordwise_trimmed_avg_bf16      coordwise_trimmed_avg
- *   mbulyan_aggregate_bf16          mbulyan_aggregate_ex
- *   mbulyan_aggregate_chunked_bf16  mbulyan_aggregate_chunked
- *   multikrum_aggregate_bf16        multikrum_aggregate
- *   coordwise_median_bf16           coordwise_median
+ * Gradients stored in 16 bits (NEXT to the fp32 path: the same operations of
+ * Algorithm 1 on half the bytes).  Two formats, raw 16-bit words, ld in
+ * elements:
+ *   *_bf16  bfloat16: the upper half of the fp32 bit pattern
+ *   *_fp16  IEEE half precision (subnormals included)
+ * Every value of either format is an fp32 value, so the results are those of
+ * the fp32 entry points on the widened matrix, to the same tolerances;
+ * distances and out stay fp64 / fp32.  The distance pass needs no splitting:
+ * a product of two such values is exact in fp32 (one matrix-core product per
+ * pair and coordinate); its second, centred pass works on the fp32
+ * differences.  The fast paths need rows that start on 16-byte boundaries
+ * (distance pass: grads % 16 == 0 and ld % 8 == 0) and 4-byte boundaries
+ * (coordinate pass: grads % 4 == 0, ld % 2 == 0, out % 8 == 0); anything else
+ * takes element loads.  Arguments as for the fp32 entry point of the same
+ * name:
+ *   pairwise_sqdist_*            pairwise_sqdist (Gram form)
+ *   coordwise_trimmed_avg_*      coordwise_trimmed_avg
+ *   mbulyan_aggregate_*          mbulyan_aggregate_ex
+ *   mbulyan_aggregate_chunked_*  mbulyan_aggregate_chunked
+ *   multikrum_aggregate_*        multikrum_aggregate
+ *   coordwise_median_*           coordwise_median
  */
 int pairwise_sqdist_bf16(const uint16_t *grads, int n, int64_t d, int64_t ld,
                          double *dist, int accumulate, void *workspace,
@@ -275,6 +280,60 @@ int mbulyan_aggregate_chunked_bf16(const uint16_t *const *chunks, int nchunks,
                                    int32_t *selected_idx,
                                    void *workspace, size_t ws_bytes,
                                    void *stream);
+int pairwise_sqdist_fp16(const uint16_t *grads, int n, int64_t d, int64_t ld,
+                         double *dist, int accumulate, void *workspace,
+                         size_t ws_bytes, void *stream);
+int coordwise_trimmed_avg_fp16(const uint16_t *grads, int n, int64_t d,
+                               int64_t ld, const int32_t *selected_idx,
+                               int theta, int beta, const uint8_t *agr_sets,
+                               float *out, void *stream);
+int mbulyan_aggregate_fp16(const uint16_t *grads, int n, int f, int64_t d,
+                           int64_t ld, int mode, int theta, int beta,
+                           float *out, int32_t *selected_idx, void *workspace,
+                           size_t ws_bytes, void *stream);
+int multikrum_aggregate_fp16(const uint16_t *grads, int n, int f, int64_t d,
+                             int64_t ld, float *out, uint8_t *selected_mask,
+                             void *workspace, size_t ws_bytes, void *stream);
+int coordwise_median_fp16(const uint16_t *grads, int n, int64_t d, int64_t ld,
+                          float *out, void *stream);
+int mbulyan_aggregate_chunked_fp16(const uint16_t *const *chunks, int nchunks,
+                                   const int64_t *chunk_d,
+                                   const int64_t *chunk_ld, int n, int f,
+                                   int mode, float *const *outs,
+                                   int32_t *selected_idx,
+                                   void *workspace, size_t ws_bytes,
+                                   void *stream);
+
+/*
+ * The same rule for gradients that stay in HOST memory (d beyond what the device
+ * holds; Section I speaks of d up to 10^9 .. 10^11).  Column chunks of chunk_d
+ * coordinates are uploaded into two device buffers in turn, the upload of one
+ * chunk overlapping the kernels of the one before, in two sweeps over the
+ * matrix: distances (Algorithm 1 computes them over whole gradients), then the
+ * selection, then the coordinate pass per chunk with its part of the result
+ * copied back.
+ *   host_grads   host, n rows of d values, row stride ld elements; pinned memory
+ *                (hipHostMalloc) if the copies are to overlap the kernels,
+ *                pageable memory works but serialises them
+ *   storage      MB_STORE_FP32 (float), MB_STORE_BF16 / MB_STORE_FP16 (16-bit words)
+ *   chunk_d      coordinates per chunk (the last chunk may be shorter); the call
+ *                holds 2 n chunk_d values plus 2 chunk_d floats of device memory
+ *   host_out     host, d floats
+ *   host_selected_idx  host, theta int32, may be NULL
+ *   stream       the kernels' stream (copies use a stream of the call's own); work
+ *                queued on it before the call is waited for
+ * theta and beta are the mode's defaults.  Unlike the other entry points this one
+ * allocates and frees device memory (its chunk buffers) and RETURNS ONLY WHEN THE
+ * RESULT IS IN host_out.  The rate is that of the host link, twice over: the
+ * device-resident entry points are the ones to time.
+ */
+#define MB_STORE_FP32 0
+#define MB_STORE_BF16 1
+#define MB_STORE_FP16 2
+int mbulyan_aggregate_host(const void *host_grads, int storage, int n, int f,
+                           int64_t d, int64_t ld, int mode, int64_t chunk_d,
+                           float *host_out, int32_t *host_selected_idx,
+                           void *stream);
 
 /*
  * Multi-Krum as a GAR (Algorithm 1, function multi-Krum, G^output): the

@@ -29,6 +29,9 @@ EXPORTS = [
     "pairwise_sqdist_bf16", "coordwise_trimmed_avg_bf16", "mbulyan_aggregate_bf16",
     "mbulyan_aggregate_chunked_bf16", "multikrum_aggregate_bf16", "coordwise_median_bf16",
     "mbulyan_aggregate_noalloc",
+    "pairwise_sqdist_fp16", "coordwise_trimmed_avg_fp16", "mbulyan_aggregate_fp16",
+    "mbulyan_aggregate_chunked_fp16", "multikrum_aggregate_fp16", "coordwise_median_fp16",
+    "mbulyan_aggregate_host",
 ]
 
 
@@ -54,6 +57,7 @@ def _load() -> C.CDLL:
     lib.mbulyan_set_dist_algo.argtypes = [ci]
     lib.mbulyan_aggregate.argtypes = [vp, ci, ci, i64, vp, vp, vp]
     lib.mbulyan_aggregate_ex.argtypes = [vp, ci, ci, i64, i64, ci, ci, ci, vp, vp, vp, sz, vp]
+    lib.mbulyan_aggregate_host.argtypes = [vp, ci, ci, ci, i64, i64, ci, i64, vp, vp, vp]
     lib.mbulyan_aggregate_noalloc.argtypes = [vp, ci, ci, i64, i64, ci, vp, vp, vp]
     lib.mbulyan_aggregate_chunked.argtypes = [C.POINTER(vp), ci, C.POINTER(i64), C.POINTER(i64), ci, ci, ci,
                                               C.POINTER(vp), vp, vp, sz, vp]
@@ -63,13 +67,14 @@ def _load() -> C.CDLL:
     lib.coordwise_trimmed_avg.argtypes = [vp, ci, i64, i64, vp, ci, ci, vp, vp, vp]
     lib.multikrum_aggregate.argtypes = [vp, ci, ci, i64, i64, vp, vp, vp, sz, vp]
     lib.coordwise_median.argtypes = [vp, ci, i64, i64, vp, vp]
-    lib.pairwise_sqdist_bf16.argtypes = [vp, ci, i64, i64, vp, ci, vp, sz, vp]
-    lib.coordwise_trimmed_avg_bf16.argtypes = [vp, ci, i64, i64, vp, ci, ci, vp, vp, vp]
-    lib.mbulyan_aggregate_bf16.argtypes = [vp, ci, ci, i64, i64, ci, ci, ci, vp, vp, vp, sz, vp]
-    lib.mbulyan_aggregate_chunked_bf16.argtypes = [C.POINTER(vp), ci, C.POINTER(i64), C.POINTER(i64), ci, ci, ci,
-                                                   C.POINTER(vp), vp, vp, sz, vp]
-    lib.multikrum_aggregate_bf16.argtypes = [vp, ci, ci, i64, i64, vp, vp, vp, sz, vp]
-    lib.coordwise_median_bf16.argtypes = [vp, ci, i64, i64, vp, vp]
+    for sfx in ("bf16", "fp16"):
+        getattr(lib, "pairwise_sqdist_" + sfx).argtypes = [vp, ci, i64, i64, vp, ci, vp, sz, vp]
+        getattr(lib, "coordwise_trimmed_avg_" + sfx).argtypes = [vp, ci, i64, i64, vp, ci, ci, vp, vp, vp]
+        getattr(lib, "mbulyan_aggregate_" + sfx).argtypes = [vp, ci, ci, i64, i64, ci, ci, ci, vp, vp, vp, sz, vp]
+        getattr(lib, "mbulyan_aggregate_chunked_" + sfx).argtypes = [C.POINTER(vp), ci, C.POINTER(i64), C.POINTER(i64),
+                                                                     ci, ci, ci, C.POINTER(vp), vp, vp, sz, vp]
+        getattr(lib, "multikrum_aggregate_" + sfx).argtypes = [vp, ci, ci, i64, i64, vp, vp, vp, sz, vp]
+        getattr(lib, "coordwise_median_" + sfx).argtypes = [vp, ci, i64, i64, vp, vp]
     lib.mbulyan_timing_enable.argtypes = [ci]
     lib.mbulyan_timing_read.argtypes = [C.POINTER(C.c_double), C.POINTER(i64)]
     return lib
@@ -109,10 +114,19 @@ def _dev(t: torch.Tensor | None, dtype, name: str, numel: int | None = None, lik
     return t.data_ptr()
 
 
+_SUFFIX = {torch.bfloat16: "bf16", torch.float16: "fp16"}
+
+
+def _entry(name: str, grads: torch.Tensor):
+    """The entry point for the storage format of grads: `name` itself for float32, its _bf16 / _fp16 form else."""
+    sfx = _SUFFIX.get(grads.dtype)
+    return getattr(lib, name + "_" + sfx) if sfx else getattr(lib, name)
+
+
 def _matrix(grads: torch.Tensor, bf16_ok: bool = False):
-    """(pointer, n, d, ld) of an (n, d) float32 CUDA tensor with unit column stride (bfloat16 where
-    the entry point has a bf16 form; ld is in elements)."""
-    ok = (torch.float32, torch.bfloat16) if bf16_ok else (torch.float32,)
+    """(pointer, n, d, ld) of an (n, d) float32 CUDA tensor with unit column stride (bfloat16 or float16 where
+    the entry point has 16-bit forms; ld is in elements)."""
+    ok = (torch.float32, torch.bfloat16, torch.float16) if bf16_ok else (torch.float32,)
     if not grads.is_cuda or grads.dtype not in ok or grads.dim() != 2:
         raise TypeError("grads must be a 2-D CUDA tensor of " + " or ".join(str(t) for t in ok))
     n, d = grads.shape
@@ -167,7 +181,7 @@ def mbulyan_aggregate(grads, f, out=None, selected_idx=None, stream=None):
 
 def mbulyan_aggregate_ex(grads, f, mode=MODE_SELECTED, theta=0, beta=0, out=None, selected_idx=None,
                          workspace=None, stream=None):
-    """grads may be bfloat16: the bf16 entry point runs, out stays float32."""
+    """grads may be bfloat16 or float16: the entry point for that storage runs, out stays float32."""
     p, n, d, ld = _matrix(grads, bf16_ok=True)
     th_def, _ = mbulyan_params(n, f, mode)
     th = theta or th_def
@@ -176,10 +190,11 @@ def mbulyan_aggregate_ex(grads, f, mode=MODE_SELECTED, theta=0, beta=0, out=None
     if selected_idx is None:
         selected_idx = torch.empty(th, device=grads.device, dtype=torch.int32)
     wp, wb = _ws(workspace)
-    if grads.dtype == torch.bfloat16:
-        _check(lib.mbulyan_aggregate_bf16(p, n, f, d, ld, mode, theta, beta, _dev(out, torch.float32, "out", d, grads),
-                                          _dev(selected_idx, torch.int32, "selected_idx", th, grads), wp, wb,
-                                          _stream(stream)))
+    if grads.dtype != torch.float32:
+        _check(_entry("mbulyan_aggregate", grads)(p, n, f, d, ld, mode, theta, beta,
+                                                  _dev(out, torch.float32, "out", d, grads),
+                                                  _dev(selected_idx, torch.int32, "selected_idx", th, grads), wp, wb,
+                                                  _stream(stream)))
         return out, selected_idx
     _check(lib.mbulyan_aggregate_ex(p, n, f, d, ld, mode, theta, beta, _dev(out, torch.float32, "out", d, grads),
                                     _dev(selected_idx, torch.int32, "selected_idx", th, grads), wp, wb, _stream(stream)))
@@ -197,13 +212,35 @@ def mbulyan_aggregate_noalloc(grads, f, out, selected_idx=None, mode=MODE_SELECT
     return out, selected_idx
 
 
+def mbulyan_aggregate_host(host_grads, f, chunk_d, mode=MODE_SELECTED, host_out=None, stream=None):
+    """GAR(f, host_grads) for an (n, d) HOST tensor (float32, bfloat16 or float16; pinned memory lets the
+    uploads overlap the kernels): uploaded in column chunks of chunk_d coordinates, twice.  Blocks until the
+    result is in host_out.  Returns (host_out, selected_idx), both host tensors."""
+    if host_grads.is_cuda or host_grads.dim() != 2 or host_grads.dtype not in (torch.float32, torch.bfloat16, torch.float16):
+        raise TypeError("host_grads must be a 2-D host tensor of float32, bfloat16 or float16")
+    n, d = host_grads.shape
+    if d > 1 and host_grads.stride(1) != 1:
+        raise ValueError("host_grads must have unit stride along the coordinates")
+    ld = host_grads.stride(0) if n > 1 else max(d, 1)
+    storage = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}[host_grads.dtype]
+    theta, _ = mbulyan_params(n, f, mode)
+    if host_out is None:
+        host_out = torch.empty(d, dtype=torch.float32, pin_memory=host_grads.is_pinned())
+    if host_out.is_cuda or host_out.dtype != torch.float32 or not host_out.is_contiguous() or host_out.numel() < d:
+        raise ValueError("host_out must be a contiguous host float32 tensor of d elements")
+    sel = torch.empty(theta, dtype=torch.int32)
+    _check(lib.mbulyan_aggregate_host(host_grads.data_ptr(), storage, n, f, d, ld, mode, int(chunk_d),
+                                      host_out.data_ptr(), sel.data_ptr(), _stream(stream)))
+    return host_out, sel
+
+
 def mbulyan_aggregate_chunked(chunks, f, mode=MODE_SELECTED, outs=None, selected_idx=None, workspace=None,
                               stream=None):
     """chunks: list of (n, d_c) float32 CUDA tensors, the column chunks of one matrix (all bfloat16
-    instead: the bf16 entry point)."""
+    or all float16 instead: the entry point for that storage)."""
     k = len(chunks)
     mats = [_matrix(c, bf16_ok=True) for c in chunks]
-    in16 = chunks[0].dtype == torch.bfloat16
+    in16 = chunks[0].dtype != torch.float32
     if any(c.dtype != chunks[0].dtype for c in chunks):
         raise TypeError("all chunks must have the same dtype")
     n = mats[0][1]
@@ -220,7 +257,7 @@ def mbulyan_aggregate_chunked(chunks, f, mode=MODE_SELECTED, outs=None, selected
     op = (C.c_void_p * k)(*[_dev(o, torch.float32, "out", m[2], chunks[0]) for o, m in zip(outs, mats)])
     wp, wb = _ws(workspace)
     if in16:
-        _check(lib.mbulyan_aggregate_chunked_bf16(cp, k, cd, cl, n, f, mode, op,
+        _check(_entry("mbulyan_aggregate_chunked", chunks[0])(cp, k, cd, cl, n, f, mode, op,
                                                   _dev(selected_idx, torch.int32, "selected_idx", theta, chunks[0]),
                                                   wp, wb, _stream(stream)))
         return outs, selected_idx
@@ -231,16 +268,16 @@ def mbulyan_aggregate_chunked(chunks, f, mode=MODE_SELECTED, outs=None, selected
 
 
 def pairwise_sqdist(grads, dist=None, accumulate=False, algo=DIST_AUTO, workspace=None, stream=None):
-    """grads may be bfloat16: the bf16 entry point runs (Gram form, algo is not used)."""
+    """grads may be bfloat16 or float16: the entry point for that storage runs (Gram form, algo is not used)."""
     p, n, d, ld = _matrix(grads, bf16_ok=True)
     if dist is None:
         if accumulate:
             raise ValueError("accumulate needs an existing dist")
         dist = torch.empty(n, n, device=grads.device, dtype=torch.float64)
     wp, wb = _ws(workspace)
-    if grads.dtype == torch.bfloat16:
-        _check(lib.pairwise_sqdist_bf16(p, n, d, ld, _dev(dist, torch.float64, "dist", n * n, grads), int(accumulate),
-                                        wp, wb, _stream(stream)))
+    if grads.dtype != torch.float32:
+        _check(_entry("pairwise_sqdist", grads)(p, n, d, ld, _dev(dist, torch.float64, "dist", n * n, grads),
+                                                int(accumulate), wp, wb, _stream(stream)))
         return dist
     _check(lib.pairwise_sqdist(p, n, d, ld, _dev(dist, torch.float64, "dist", n * n, grads), int(accumulate), algo,
                                wp, wb, _stream(stream)))
@@ -268,38 +305,38 @@ def multikrum_select(dist, f, theta, want_sets=True, stream=None):
 
 
 def coordwise_trimmed_avg(grads, selected_idx, beta, agr_sets=None, out=None, stream=None):
-    """grads may be bfloat16."""
+    """grads may be bfloat16 or float16."""
     p, n, d, ld = _matrix(grads, bf16_ok=True)
     if out is None:
         out = torch.empty(d, device=grads.device, dtype=torch.float32)
     theta = selected_idx.numel()
     sp = _dev(selected_idx, torch.int32, "selected_idx", None, grads)
     ap = _dev(agr_sets, torch.uint8, "agr_sets", theta * n, grads)
-    fn = lib.coordwise_trimmed_avg_bf16 if grads.dtype == torch.bfloat16 else lib.coordwise_trimmed_avg
+    fn = _entry("coordwise_trimmed_avg", grads)
     _check(fn(p, n, d, ld, sp, theta, beta, ap, _dev(out, torch.float32, "out", d, grads), _stream(stream)))
     return out
 
 
 def multikrum_aggregate(grads, f, out=None, selected_mask=None, workspace=None, stream=None):
-    """grads may be bfloat16."""
+    """grads may be bfloat16 or float16."""
     p, n, d, ld = _matrix(grads, bf16_ok=True)
     if out is None:
         out = torch.empty(d, device=grads.device, dtype=torch.float32)
     if selected_mask is None:
         selected_mask = torch.empty(n, device=grads.device, dtype=torch.uint8)
     wp, wb = _ws(workspace)
-    fn = lib.multikrum_aggregate_bf16 if grads.dtype == torch.bfloat16 else lib.multikrum_aggregate
+    fn = _entry("multikrum_aggregate", grads)
     _check(fn(p, n, f, d, ld, _dev(out, torch.float32, "out", d, grads),
               _dev(selected_mask, torch.uint8, "selected_mask", n, grads), wp, wb, _stream(stream)))
     return out, selected_mask
 
 
 def coordwise_median(grads, out=None, stream=None):
-    """grads may be bfloat16."""
+    """grads may be bfloat16 or float16."""
     p, n, d, ld = _matrix(grads, bf16_ok=True)
     if out is None:
         out = torch.empty(d, device=grads.device, dtype=torch.float32)
-    fn = lib.coordwise_median_bf16 if grads.dtype == torch.bfloat16 else lib.coordwise_median
+    fn = _entry("coordwise_median", grads)
     _check(fn(p, n, d, ld, _dev(out, torch.float32, "out", d, grads), _stream(stream)))
     return out
 

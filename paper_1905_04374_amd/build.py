@@ -47,13 +47,18 @@ def units():
          ("dist.o", "dist.hip", []),
          ("dist_gram.o", "dist_gram.hip", []),
          ("select.o", "select.hip", []),
-         ("rowops.o", "rowops.hip", [])]
+         ("rowops.o", "rowops.hip", []),
+         ("host_chunks.o", "host_chunks.hip", [])]
+    # the coordinate kernels: per group of theta values, and per storage format of the gradients
+    # (fp32, bf16 = -DMB_IN16=1, fp16 = -DMB_IN16=2)
     for g in range(8):
         u.append((f"coordwise_g{g}.o", "coordwise.hip", NO_NANS + [f"-DMB_GROUP={g}"]))
         u.append((f"coordwise16_g{g}.o", "coordwise.hip", NO_NANS + [f"-DMB_GROUP={g}", "-DMB_IN16=1"]))
+        u.append((f"coordwiseh_g{g}.o", "coordwise.hip", NO_NANS + [f"-DMB_GROUP={g}", "-DMB_IN16=2"]))
     for g in range(8):
         u.append((f"coordwise_alg1_g{g}.o", "coordwise_alg1.hip", NO_NANS + [f"-DMB_GROUP={g}"]))
         u.append((f"coordwise_alg1_16_g{g}.o", "coordwise_alg1.hip", NO_NANS + [f"-DMB_GROUP={g}", "-DMB_IN16=1"]))
+        u.append((f"coordwise_alg1_h_g{g}.o", "coordwise_alg1.hip", NO_NANS + [f"-DMB_GROUP={g}", "-DMB_IN16=2"]))
     return u
 
 
@@ -75,7 +80,7 @@ def _deps_newer(obj: str, src: str) -> bool:
     t = os.path.getmtime(obj)
     deps = [os.path.join(CSRC, src), __file__]
     deps += sorted(_local_includes(os.path.join(CSRC, src), set()))
-    if src == "api.hip":
+    if src in ("api.hip", "host_chunks.hip"):
         deps += [os.path.join(INCLUDE, name) for name in os.listdir(INCLUDE)]
     return any(os.path.getmtime(dep) > t for dep in deps)
 

@@ -40,6 +40,8 @@ constexpr size_t kOffPlan = kOffSets + 4096;                     // plan of the 
 constexpr size_t kPlanBytes = 18 * 1024;
 constexpr size_t kOffPartials = kOffPlan + kPlanBytes;
 static_assert(mb::kPlanWords * sizeof(int32_t) <= kPlanBytes, "plan segment");
+static_assert(MB_STORE_FP32 == mb::kStoreFp32 && MB_STORE_BF16 == mb::kStoreBf16 && MB_STORE_FP16 == mb::kStoreFp16,
+              "the public storage codes are the kernels' own");
 
 struct Workspace {
     char *base;
@@ -180,7 +182,8 @@ int check_matrix(const void *grads, int n, int64_t d, int64_t ld)
 // which find out on the device whether they are needed (gram_combine.hpp) and return at once if not.
 // `defer` (may be null): leave the last step, Gram tiles -> distance matrix, to the selection kernel
 // (it forms the matrix itself from ws.reduced(), ws.reduced2(), ws.gate()); set to 1 when that was possible.
-// gradients stored as bf16: Gram form only (one exact bf16 product per pair and coordinate)
+// in16: mb::kStoreFp32, or gradients stored as 16-bit words (kStoreBf16 / kStoreFp16): Gram form only
+// (one exact product per pair and coordinate)
 int run_dist_gram(const void *grads, int in16, bool bf16, int n, int64_t d, int64_t ld, double *dist, int accumulate,
                   const Workspace &ws, hipStream_t s, int *defer)
 {
@@ -194,7 +197,7 @@ int run_dist_gram(const void *grads, int in16, bool bf16, int n, int64_t d, int6
         {
             StageTimer t(pass ? MB_STAGE_REFINE : MB_STAGE_DIST, s);
             if (in16)
-                MB_HIP(mb::launch_dist_gram_in16(static_cast<const uint16_t *>(grads), n, d, ld, ws.partials(), room,
+                MB_HIP(mb::launch_dist_gram_in16(static_cast<const uint16_t *>(grads), in16, n, d, ld, ws.partials(), room,
                                                  &nblocks, first, gate, s));
             else
                 MB_HIP(mb::launch_dist_gram(static_cast<const float *>(grads), n, d, ld, ws.partials(), bf16, room,
@@ -212,10 +215,10 @@ int run_dist_gram(const void *grads, int in16, bool bf16, int n, int64_t d, int6
     return MB_OK;
 }
 
-int run_dist_in16(const uint16_t *grads, int n, int64_t d, int64_t ld, double *dist, int accumulate,
+int run_dist_in16(const uint16_t *grads, int fmt, int n, int64_t d, int64_t ld, double *dist, int accumulate,
                   const Workspace &ws, hipStream_t s, int *defer = nullptr)
 {
-    return run_dist_gram(grads, 1, true, n, d, ld, dist, accumulate, ws, s, defer);
+    return run_dist_gram(grads, fmt, true, n, d, ld, dist, accumulate, ws, s, defer);
 }
 
 int run_dist(const float *grads, int n, int64_t d, int64_t ld, double *dist, int accumulate, int algo,
@@ -272,58 +275,32 @@ int resolve_params(int n, int f, int mode, int *theta, int *beta)
 }  // namespace
 
 namespace mb {
+#define MB_BY_GROUP(PREFIX)                             \
+    switch ((a.theta - 1) / 8) {                        \
+        case 0: return PREFIX##0(a, s);                 \
+        case 1: return PREFIX##1(a, s);                 \
+        case 2: return PREFIX##2(a, s);                 \
+        case 3: return PREFIX##3(a, s);                 \
+        case 4: return PREFIX##4(a, s);                 \
+        case 5: return PREFIX##5(a, s);                 \
+        case 6: return PREFIX##6(a, s);                 \
+        default: return PREFIX##7(a, s);                \
+    }
 hipError_t launch_coord_selected(const CoordArgs &a, hipStream_t s)
 {
     if (a.theta < 1 || a.theta > kMaxN) return hipErrorInvalidValue;
-    if (a.in16) {
-        switch ((a.theta - 1) / 8) {
-            case 0: return launch_coord16_group0(a, s);
-            case 1: return launch_coord16_group1(a, s);
-            case 2: return launch_coord16_group2(a, s);
-            case 3: return launch_coord16_group3(a, s);
-            case 4: return launch_coord16_group4(a, s);
-            case 5: return launch_coord16_group5(a, s);
-            case 6: return launch_coord16_group6(a, s);
-            default: return launch_coord16_group7(a, s);
-        }
-    }
-    switch ((a.theta - 1) / 8) {
-        case 0: return launch_coord_group0(a, s);
-        case 1: return launch_coord_group1(a, s);
-        case 2: return launch_coord_group2(a, s);
-        case 3: return launch_coord_group3(a, s);
-        case 4: return launch_coord_group4(a, s);
-        case 5: return launch_coord_group5(a, s);
-        case 6: return launch_coord_group6(a, s);
-        default: return launch_coord_group7(a, s);
-    }
+    if (a.in16 == kStoreBf16) { MB_BY_GROUP(launch_coord16_group) }
+    if (a.in16 == kStoreFp16) { MB_BY_GROUP(launch_coordh_group) }
+    MB_BY_GROUP(launch_coord_group)
 }
 hipError_t launch_coord_alg1(const CoordAlg1Args &a, hipStream_t s)
 {
     if (a.theta < 1 || a.theta > kMaxN) return hipErrorInvalidValue;
-    if (a.in16) {
-        switch ((a.theta - 1) / 8) {
-            case 0: return launch_coord_alg1_16_group0(a, s);
-            case 1: return launch_coord_alg1_16_group1(a, s);
-            case 2: return launch_coord_alg1_16_group2(a, s);
-            case 3: return launch_coord_alg1_16_group3(a, s);
-            case 4: return launch_coord_alg1_16_group4(a, s);
-            case 5: return launch_coord_alg1_16_group5(a, s);
-            case 6: return launch_coord_alg1_16_group6(a, s);
-            default: return launch_coord_alg1_16_group7(a, s);
-        }
-    }
-    switch ((a.theta - 1) / 8) {
-        case 0: return launch_coord_alg1_group0(a, s);
-        case 1: return launch_coord_alg1_group1(a, s);
-        case 2: return launch_coord_alg1_group2(a, s);
-        case 3: return launch_coord_alg1_group3(a, s);
-        case 4: return launch_coord_alg1_group4(a, s);
-        case 5: return launch_coord_alg1_group5(a, s);
-        case 6: return launch_coord_alg1_group6(a, s);
-        default: return launch_coord_alg1_group7(a, s);
-    }
+    if (a.in16 == kStoreBf16) { MB_BY_GROUP(launch_coord_alg1_16_group) }
+    if (a.in16 == kStoreFp16) { MB_BY_GROUP(launch_coord_alg1_h_group) }
+    MB_BY_GROUP(launch_coord_alg1_group)
 }
+#undef MB_BY_GROUP
 }  // namespace mb
 
 extern "C" {
@@ -439,7 +416,7 @@ static int aggregate_chunked(const void *const *chunks, int in16, int nchunks, c
     if (rc != MB_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
     for (int c = 0; c < nchunks; ++c) {
-        rc = in16 ? run_dist_in16(static_cast<const uint16_t *>(chunks[c]), n, chunk_d[c], chunk_ld[c], ws.dist(), c > 0,
+        rc = in16 ? run_dist_in16(static_cast<const uint16_t *>(chunks[c]), in16, n, chunk_d[c], chunk_ld[c], ws.dist(), c > 0,
                                   ws, s)
                   : run_dist(static_cast<const float *>(chunks[c]), n, chunk_d[c], chunk_ld[c], ws.dist(), c > 0,
                              MB_DIST_AUTO, ws, s);
@@ -472,8 +449,16 @@ int mbulyan_aggregate_chunked_bf16(const uint16_t *const *chunks, int nchunks, c
                                    const int64_t *chunk_ld, int n, int f, int mode, float *const *outs,
                                    int32_t *selected_idx, void *workspace, size_t ws_bytes, void *stream)
 {
-    return aggregate_chunked(reinterpret_cast<const void *const *>(chunks), 1, nchunks, chunk_d, chunk_ld, n, f,
-                             mode, outs, selected_idx, workspace, ws_bytes, stream);
+    return aggregate_chunked(reinterpret_cast<const void *const *>(chunks), mb::kStoreBf16, nchunks, chunk_d, chunk_ld,
+                             n, f, mode, outs, selected_idx, workspace, ws_bytes, stream);
+}
+
+int mbulyan_aggregate_chunked_fp16(const uint16_t *const *chunks, int nchunks, const int64_t *chunk_d,
+                                   const int64_t *chunk_ld, int n, int f, int mode, float *const *outs,
+                                   int32_t *selected_idx, void *workspace, size_t ws_bytes, void *stream)
+{
+    return aggregate_chunked(reinterpret_cast<const void *const *>(chunks), mb::kStoreFp16, nchunks, chunk_d, chunk_ld,
+                             n, f, mode, outs, selected_idx, workspace, ws_bytes, stream);
 }
 
 // distance pass, reduction, selection, coordinate pass of one fp32 matrix on the workspace `ws`
@@ -609,9 +594,9 @@ int coordwise_median(const float *grads, int n, int64_t d, int64_t ld, float *ou
     return MB_OK;
 }
 
-// ---- gradients stored as bf16 ----------------------------------------------
-int pairwise_sqdist_bf16(const uint16_t *grads, int n, int64_t d, int64_t ld, double *dist, int accumulate,
-                         void *workspace, size_t ws_bytes, void *stream)
+// ---- gradients stored as 16-bit words (fmt = mb::kStoreBf16 / mb::kStoreFp16) ----------------
+static int pairwise_sqdist_16(const uint16_t *grads, int fmt, int n, int64_t d, int64_t ld, double *dist,
+                              int accumulate, void *workspace, size_t ws_bytes, void *stream)
 {
     int rc = check_matrix(grads, n, d, ld);
     if (rc != MB_OK) return rc;
@@ -619,11 +604,12 @@ int pairwise_sqdist_bf16(const uint16_t *grads, int n, int64_t d, int64_t ld, do
     Workspace ws;
     rc = get_workspace(workspace, ws_bytes, n, d, &ws);
     if (rc != MB_OK) return rc;
-    return run_dist_in16(grads, n, d, ld, dist, accumulate ? 1 : 0, ws, (hipStream_t)stream);
+    return run_dist_in16(grads, fmt, n, d, ld, dist, accumulate ? 1 : 0, ws, (hipStream_t)stream);
 }
 
-int coordwise_trimmed_avg_bf16(const uint16_t *grads, int n, int64_t d, int64_t ld, const int32_t *selected_idx,
-                               int theta, int beta, const uint8_t *agr_sets, float *out, void *stream)
+static int coordwise_trimmed_avg_16(const uint16_t *grads, int fmt, int n, int64_t d, int64_t ld,
+                                    const int32_t *selected_idx, int theta, int beta, const uint8_t *agr_sets,
+                                    float *out, void *stream)
 {
     const int rc = check_matrix(grads, n, d, ld);
     if (rc != MB_OK) return rc;
@@ -633,12 +619,12 @@ int coordwise_trimmed_avg_bf16(const uint16_t *grads, int n, int64_t d, int64_t 
         const int wrc = own_workspace(kOffPartials, &ws);
         if (wrc != MB_OK) return wrc;
     }
-    return run_coord(grads, 1, n, d, ld, agr_sets ? MB_MODE_ALG1 : MB_MODE_SELECTED, theta, beta, selected_idx,
+    return run_coord(grads, fmt, n, d, ld, agr_sets ? MB_MODE_ALG1 : MB_MODE_SELECTED, theta, beta, selected_idx,
                      agr_sets, agr_sets ? ws.plan() : nullptr, false, out, (hipStream_t)stream);
 }
 
-int multikrum_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d, int64_t ld, float *out,
-                             uint8_t *selected_mask, void *workspace, size_t ws_bytes, void *stream)
+static int multikrum_aggregate_16(const uint16_t *grads, int fmt, int n, int f, int64_t d, int64_t ld, float *out,
+                                  uint8_t *selected_mask, void *workspace, size_t ws_bytes, void *stream)
 {
     int rc = check_matrix(grads, n, d, ld);
     if (rc != MB_OK) return rc;
@@ -649,7 +635,7 @@ int multikrum_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d, int
     if (rc != MB_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
     int deferred = 0;
-    rc = run_dist_in16(grads, n, d, ld, ws.dist(), 0, ws, s, &deferred);
+    rc = run_dist_in16(grads, fmt, n, d, ld, ws.dist(), 0, ws, s, &deferred);
     if (rc != MB_OK) return rc;
     uint8_t *mask = selected_mask ? selected_mask : ws.sets();   // written in place by the selection
     {
@@ -661,25 +647,25 @@ int multikrum_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d, int
     }
     {
         StageTimer t(MB_STAGE_COORD, s);
-        MB_HIP(mb::launch_masked_mean_in16(grads, n, d, ld, mask, out, s));
+        MB_HIP(mb::launch_masked_mean_in16(grads, fmt, n, d, ld, mask, out, s));
     }
     return MB_OK;
 }
 
-int coordwise_median_bf16(const uint16_t *grads, int n, int64_t d, int64_t ld, float *out, void *stream)
+static int coordwise_median_16(const uint16_t *grads, int fmt, int n, int64_t d, int64_t ld, float *out, void *stream)
 {
     const int rc = check_matrix(grads, n, d, ld);
     if (rc != MB_OK) return rc;
     if (!out) return MB_EINVAL;
     StageTimer t(MB_STAGE_COORD, (hipStream_t)stream);
-    mb::CoordArgs a{grads, n, d, ld, nullptr, n, 1, 1, out, 1};
+    mb::CoordArgs a{grads, n, d, ld, nullptr, n, 1, 1, out, fmt};
     MB_HIP(mb::launch_coord_selected(a, (hipStream_t)stream));
     return MB_OK;
 }
 
-int mbulyan_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d, int64_t ld, int mode, int theta,
-                           int beta, float *out, int32_t *selected_idx, void *workspace, size_t ws_bytes,
-                           void *stream)
+static int mbulyan_aggregate_16(const uint16_t *grads, int fmt, int n, int f, int64_t d, int64_t ld, int mode,
+                                int theta, int beta, float *out, int32_t *selected_idx, void *workspace,
+                                size_t ws_bytes, void *stream)
 {
     int rc = check_matrix(grads, n, d, ld);
     if (rc != MB_OK) return rc;
@@ -693,7 +679,7 @@ int mbulyan_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d, int64
     if (rc != MB_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
     int deferred = 0;
-    rc = run_dist_in16(grads, n, d, ld, ws.dist(), 0, ws, s, &deferred);
+    rc = run_dist_in16(grads, fmt, n, d, ld, ws.dist(), 0, ws, s, &deferred);
     if (rc != MB_OK) return rc;
     int32_t *sel = selected_idx ? selected_idx : ws.sel();   // the selection writes the caller's list in place
     {
@@ -705,8 +691,40 @@ int mbulyan_aggregate_bf16(const uint16_t *grads, int n, int f, int64_t d, int64
         else
             MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, sel, sets, ws.m(), nullptr, plan, s));
     }
-    return run_coord(grads, 1, n, d, ld, mode, theta, beta, sel, ws.sets(), ws.plan(), true, out, s);
+    return run_coord(grads, fmt, n, d, ld, mode, theta, beta, sel, ws.sets(), ws.plan(), true, out, s);
 }
+
+#define MB_16BIT_ENTRY_POINTS(SUFFIX, FMT)                                                                           \
+    int pairwise_sqdist_##SUFFIX(const uint16_t *grads, int n, int64_t d, int64_t ld, double *dist, int accumulate,  \
+                                 void *workspace, size_t ws_bytes, void *stream)                                     \
+    {                                                                                                                \
+        return pairwise_sqdist_16(grads, FMT, n, d, ld, dist, accumulate, workspace, ws_bytes, stream);              \
+    }                                                                                                                \
+    int coordwise_trimmed_avg_##SUFFIX(const uint16_t *grads, int n, int64_t d, int64_t ld,                          \
+                                       const int32_t *selected_idx, int theta, int beta, const uint8_t *agr_sets,    \
+                                       float *out, void *stream)                                                     \
+    {                                                                                                                \
+        return coordwise_trimmed_avg_16(grads, FMT, n, d, ld, selected_idx, theta, beta, agr_sets, out, stream);     \
+    }                                                                                                                \
+    int multikrum_aggregate_##SUFFIX(const uint16_t *grads, int n, int f, int64_t d, int64_t ld, float *out,         \
+                                     uint8_t *selected_mask, void *workspace, size_t ws_bytes, void *stream)         \
+    {                                                                                                                \
+        return multikrum_aggregate_16(grads, FMT, n, f, d, ld, out, selected_mask, workspace, ws_bytes, stream);     \
+    }                                                                                                                \
+    int coordwise_median_##SUFFIX(const uint16_t *grads, int n, int64_t d, int64_t ld, float *out, void *stream)     \
+    {                                                                                                                \
+        return coordwise_median_16(grads, FMT, n, d, ld, out, stream);                                               \
+    }                                                                                                                \
+    int mbulyan_aggregate_##SUFFIX(const uint16_t *grads, int n, int f, int64_t d, int64_t ld, int mode, int theta,  \
+                                   int beta, float *out, int32_t *selected_idx, void *workspace, size_t ws_bytes,    \
+                                   void *stream)                                                                     \
+    {                                                                                                                \
+        return mbulyan_aggregate_16(grads, FMT, n, f, d, ld, mode, theta, beta, out, selected_idx, workspace,        \
+                                    ws_bytes, stream);                                                               \
+    }
+MB_16BIT_ENTRY_POINTS(bf16, mb::kStoreBf16)
+MB_16BIT_ENTRY_POINTS(fp16, mb::kStoreFp16)
+#undef MB_16BIT_ENTRY_POINTS
 
 int mbulyan_timing_enable(int on)
 {

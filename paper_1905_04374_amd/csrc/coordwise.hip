@@ -8,8 +8,8 @@
 // around the median.  Nothing is staged in LDS: the working set is theta
 // floats per coordinate and fits the register file for theta <= 64.
 //
-// This file is compiled once per group of 8 values of theta (-DMB_GROUP=g), and a second time
-// with -DMB_IN16=1 for gradients stored as bf16.
+// This file is compiled once per group of 8 values of theta (-DMB_GROUP=g), and again with
+// -DMB_IN16=1 for gradients stored as bf16 and -DMB_IN16=2 for fp16.
 #include <hip/hip_runtime.h>
 
 #include "mb_coord.hpp"
@@ -96,12 +96,12 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 
 #ifndef MB_IN16
-#define MB_IN16 0   // 1: this unit holds the kernels for gradients stored as bf16
+#define MB_IN16 0   // 1 / 2: this unit holds the kernels for gradients stored as bf16 / fp16
 #endif
 
-// IN16: the gradients are bf16 (raw 16-bit words); they widen exactly to fp32 in registers and the
-// arithmetic and the output stay fp32.
-template <int THETA, int VEC, int WIN, bool IN16>
+// FMT != kStoreFp32: the gradients are raw 16-bit words (bf16 or fp16); they widen exactly to fp32 in
+// registers and the arithmetic and the output stay fp32.
+template <int THETA, int VEC, int WIN, int FMT>
 __global__ __launch_bounds__(256) void coord_selected_kernel(
     const void *__restrict__ Gv, int n, int64_t d, int64_t ld, const int32_t *__restrict__ sel,
     int K, int median_only, float scale, float *__restrict__ out)
@@ -121,21 +121,21 @@ __global__ __launch_bounds__(256) void coord_selected_kernel(
     }
     float v[VEC][THETA];
     const bool full = (c0 + VEC <= d);
-    if constexpr (IN16) {
-        static_assert(VEC <= 2, "bf16 input: one or two coordinates per lane");
+    if constexpr (FMT != kStoreFp32) {
+        static_assert(VEC <= 2, "16-bit input: one or two coordinates per lane");
         if (VEC == 2 && full) {
 #pragma unroll
             for (int t = 0; t < THETA; ++t) {
                 const unsigned x = __builtin_nontemporal_load(reinterpret_cast<const unsigned *>(G16 + roff[t] + c0));
-                v[0][t] = __uint_as_float(x << 16);
-                v[1 % VEC][t] = __uint_as_float(x & 0xffff0000u);
+                v[0][t] = widen16<FMT>(x, false);
+                v[1 % VEC][t] = widen16<FMT>(x, true);
             }
         } else {
 #pragma unroll
             for (int t = 0; t < THETA; ++t)
 #pragma unroll
                 for (int e = 0; e < VEC; ++e)
-                    v[e][t] = (c0 + e < d) ? __uint_as_float((unsigned)G16[roff[t] + c0 + e] << 16) : 0.0f;
+                    v[e][t] = (c0 + e < d) ? widen16<FMT>((unsigned)G16[roff[t] + c0 + e], false) : 0.0f;
         }
     } else if (VEC == 4 && full) {
         // the input is read once and never again: non-temporal loads keep it from displacing
@@ -191,20 +191,20 @@ hipError_t launch_theta(const CoordArgs &a, hipStream_t s)
     const float scale = a.median_only ? 1.0f : 1.0f / (float)a.beta;
     // two coordinates per lane (8-byte loads; 4-byte loads of bf16 pairs) measured faster than four
     // at every theta tried (11, 15, 21, 27): fewer live registers, more waves in flight
-    constexpr bool IN16 = MB_IN16 != 0;
-    const bool aligned = ((uintptr_t)a.G % (IN16 ? 4 : 8) == 0) && ((uintptr_t)a.out % 8 == 0) && (a.ld % 2 == 0);
+    constexpr int FMT = MB_IN16;
+    const bool aligned = ((uintptr_t)a.G % (FMT != kStoreFp32 ? 4 : 8) == 0) && ((uintptr_t)a.out % 8 == 0) && (a.ld % 2 == 0);
     const dim3 block(256);
     if (aligned) {
         const dim3 grid((unsigned)((a.d + 511) / 512));
         if (K <= 2 && H > 2)
-            coord_selected_kernel<THETA, 2, 2, IN16><<<grid, block, 0, s>>>(a.G, a.n, a.d, a.ld, a.sel, K,
+            coord_selected_kernel<THETA, 2, 2, FMT><<<grid, block, 0, s>>>(a.G, a.n, a.d, a.ld, a.sel, K,
                                                                             a.median_only, scale, a.out);
         else
-            coord_selected_kernel<THETA, 2, (H > 0 ? H : 1), IN16><<<grid, block, 0, s>>>(
+            coord_selected_kernel<THETA, 2, (H > 0 ? H : 1), FMT><<<grid, block, 0, s>>>(
                 a.G, a.n, a.d, a.ld, a.sel, K, a.median_only, scale, a.out);
     } else {
         const dim3 grid((unsigned)((a.d + 255) / 256));
-        coord_selected_kernel<THETA, 1, (H > 0 ? H : 1), IN16><<<grid, block, 0, s>>>(
+        coord_selected_kernel<THETA, 1, (H > 0 ? H : 1), FMT><<<grid, block, 0, s>>>(
             a.G, a.n, a.d, a.ld, a.sel, K, a.median_only, scale, a.out);
     }
     return hipGetLastError();
@@ -215,7 +215,9 @@ hipError_t launch_theta(const CoordArgs &a, hipStream_t s)
 #define MB_CAT2(a, b) a##b
 #define MB_CAT(a, b) MB_CAT2(a, b)
 
-#if MB_IN16
+#if MB_IN16 == 2
+hipError_t MB_CAT(launch_coordh_group, MB_GROUP)(const CoordArgs &a, hipStream_t s)
+#elif MB_IN16 == 1
 hipError_t MB_CAT(launch_coord16_group, MB_GROUP)(const CoordArgs &a, hipStream_t s)
 #else
 hipError_t MB_CAT(launch_coord_group, MB_GROUP)(const CoordArgs &a, hipStream_t s)

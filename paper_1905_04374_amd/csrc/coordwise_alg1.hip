@@ -11,8 +11,8 @@
 // kernel (rowops.hip) prepares the row list and the updates; the kernel here
 // reads its plan with scalar loads and keeps everything else in registers.
 //
-// Compiled once per group of 8 values of theta (-DMB_GROUP=0..7), and a second time with
-// -DMB_IN16=1 for gradients stored as bf16.
+// Compiled once per group of 8 values of theta (-DMB_GROUP=0..7), and again with -DMB_IN16=1 for
+// gradients stored as bf16 and -DMB_IN16=2 for fp16.
 #include <hip/hip_runtime.h>
 
 #include "mb_coord.hpp"
@@ -30,7 +30,7 @@ namespace {
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 
 #ifndef MB_IN16
-#define MB_IN16 0   // 1: this unit holds the kernels for gradients stored as bf16 (raw 16-bit words)
+#define MB_IN16 0   // 1 / 2: this unit holds the kernels for gradients stored as bf16 / fp16 (raw 16-bit words)
 #endif
 constexpr bool kIn16 = MB_IN16 != 0;
 typedef typename std::conditional<kIn16, unsigned short, float>::type Elem;
@@ -57,7 +57,7 @@ struct RawOps<floatx2> {   // fp32 gradients
 };
 
 template <>
-struct RawOps<unsigned> {   // bf16 gradients: one word holds both
+struct RawOps<unsigned> {   // 16-bit gradients: one word holds both
     static __device__ __forceinline__ unsigned load(const unsigned short *p, bool pair, bool two)
     {
         if (pair) return __builtin_nontemporal_load(reinterpret_cast<const unsigned *>(p));
@@ -68,7 +68,7 @@ struct RawOps<unsigned> {   // bf16 gradients: one word holds both
     static __device__ __forceinline__ unsigned zero() { return 0u; }
     static __device__ __forceinline__ float widen(unsigned r, int k)
     {
-        return __uint_as_float(k == 0 ? r << 16 : r & 0xffff0000u);
+        return widen16<(MB_IN16 == 2 ? kStoreFp16 : kStoreBf16)>(r, k != 0);
     }
 };
 
@@ -371,7 +371,9 @@ hipError_t launch_theta(const CoordAlg1Args &a, hipStream_t s)
 #define MB_CASE(k) \
     case k: return launch_theta<8 * MB_GROUP + k>(a, s);
 
-#if MB_IN16
+#if MB_IN16 == 2
+hipError_t MB_CAT(launch_coord_alg1_h_group, MB_GROUP)(const CoordAlg1Args &a, hipStream_t s)
+#elif MB_IN16 == 1
 hipError_t MB_CAT(launch_coord_alg1_16_group, MB_GROUP)(const CoordAlg1Args &a, hipStream_t s)
 #else
 hipError_t MB_CAT(launch_coord_alg1_group, MB_GROUP)(const CoordAlg1Args &a, hipStream_t s)

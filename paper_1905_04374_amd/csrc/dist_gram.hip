@@ -43,6 +43,7 @@ namespace {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
 typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;  // 4 waves
@@ -130,6 +131,22 @@ struct Tiles {
             _Pragma("unroll") for (int J = 0; J <= I; ++J, ++t)                                 \
                 acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                               \
                     __builtin_bit_cast(bf16x8, x[I].FIELD), __builtin_bit_cast(bf16x8, x[J].FIELD), \
+                    acc[t], 0, 0, 0);                                                           \
+    }
+        MB_STEP(u) MB_STEP(w)
+#undef MB_STEP
+    }
+
+    // fp16 input: the same with the fp16 instruction (a product of two fp16 values is exact in fp32 too)
+    __device__ __forceinline__ void mac_inf16(const Raw (&x)[NB])
+    {
+#define MB_STEP(FIELD)                                                                          \
+    {                                                                                           \
+        int t = 0;                                                                              \
+        _Pragma("unroll") for (int I = 0; I < NB; ++I)                                          \
+            _Pragma("unroll") for (int J = 0; J <= I; ++J, ++t)                                 \
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(                                \
+                    __builtin_bit_cast(halfx8, x[I].FIELD), __builtin_bit_cast(halfx8, x[J].FIELD), \
                     acc[t], 0, 0, 0);                                                           \
     }
         MB_STEP(u) MB_STEP(w)
@@ -462,16 +479,15 @@ __device__ __forceinline__ void read_pivot(unsigned base, const unsigned (&off)[
     x.w = make_float4(v1[0], v1[1], v1[2], v1[3]);
 }
 
-// eight bf16 values (four words, element e in half e & 1 of word e / 2) widened to fp32
+// eight 16-bit values (four words, element e in half e & 1 of word e / 2) widened to fp32
+template <int FMT>
 __device__ __forceinline__ Raw widen8(const float4 &w)
 {
     const unsigned a = __float_as_uint(w.x), b = __float_as_uint(w.y), c = __float_as_uint(w.z),
                    e = __float_as_uint(w.w);
     Raw y;
-    y.u = make_float4(__uint_as_float(a << 16), __uint_as_float(a & 0xffff0000u), __uint_as_float(b << 16),
-                      __uint_as_float(b & 0xffff0000u));
-    y.w = make_float4(__uint_as_float(c << 16), __uint_as_float(c & 0xffff0000u), __uint_as_float(e << 16),
-                      __uint_as_float(e & 0xffff0000u));
+    y.u = make_float4(widen16<FMT>(a, false), widen16<FMT>(a, true), widen16<FMT>(b, false), widen16<FMT>(b, true));
+    y.w = make_float4(widen16<FMT>(c, false), widen16<FMT>(c, true), widen16<FMT>(e, false), widen16<FMT>(e, true));
     return y;
 }
 
@@ -499,9 +515,12 @@ inline size_t dma_lds_bytes(int n, int stages) { return (size_t)stages * dma_pai
 //   kSplit   fp32 input, every value split into three bf16 pieces (see the top of this file)
 //   kIn16    bf16 input (raw 16-bit words): products of two bf16 values are exact in fp32, one
 //            v_mfma_f32_16x16x32_bf16 per tile and 32 columns, nothing to split
-// A tile is 512 bytes of every row either way: 128 fp32 or 256 bf16 columns.
-enum Kind { kFp32 = 0, kSplit = 1, kIn16 = 2 };
-template <int KIND> constexpr int elem_bytes() { return KIND == kIn16 ? 2 : 4; }
+//   kInF16   fp16 input: the same with v_mfma_f32_16x16x32_f16
+// A tile is 512 bytes of every row either way: 128 fp32 or 256 16-bit columns.
+enum Kind { kFp32 = 0, kSplit = 1, kIn16 = 2, kInF16 = 3 };
+template <int KIND> constexpr bool is_16bit() { return KIND == kIn16 || KIND == kInF16; }
+template <int KIND> constexpr int storage_of() { return KIND == kIn16 ? kStoreBf16 : KIND == kInF16 ? kStoreFp16 : kStoreFp32; }
+template <int KIND> constexpr int elem_bytes() { return is_16bit<KIND>() ? 2 : 4; }
 template <int KIND> constexpr int tile_cols() { return 512 / elem_bytes<KIND>(); }
 
 template <int NB, int KIND, int L, bool CENTER, int S>
@@ -570,21 +589,21 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
 
     // ---- reads: byte offsets of this lane's two chunks per row block (padded rows re-read row n-1)
     // fp32: the 8 values of one 32-column step are chunks 8w+2q and 8w+2q+1;
-    // bf16: a chunk is the 8 values of one step, the wave's two steps are chunks 8w+q and 8w+4+q.
+    // 16-bit input: a chunk is the 8 values of one step, the wave's two steps are chunks 8w+q and 8w+4+q.
     unsigned off[2 * NB];
 #pragma unroll
     for (int I = 0; I < NB; ++I) {
         int row = 16 * I + r;
         row = row < n ? row : n - 1;
-        const int c0 = (KIND == kIn16 ? 8 * wave + q : 8 * wave + 2 * q) ^ (row & 15);
+        const int c0 = (is_16bit<KIND>() ? 8 * wave + q : 8 * wave + 2 * q) ^ (row & 15);
         off[2 * I] = (unsigned)(row * 512 + c0 * 16);
-        off[2 * I + 1] = (unsigned)(row * 512 + (c0 ^ (KIND == kIn16 ? 4 : 1)) * 16);
+        off[2 * I + 1] = (unsigned)(row * 512 + (c0 ^ (is_16bit<KIND>() ? 4 : 1)) * 16);
     }
     unsigned poff[2] = {0u, 0u};   // the same two chunks of the pivot row
     if constexpr (CENTER) {
-        const int c0 = (KIND == kIn16 ? 8 * wave + q : 8 * wave + 2 * q) ^ (pivot & 15);
+        const int c0 = (is_16bit<KIND>() ? 8 * wave + q : 8 * wave + 2 * q) ^ (pivot & 15);
         poff[0] = (unsigned)(pivot * 512 + c0 * 16);
-        poff[1] = (unsigned)(pivot * 512 + (c0 ^ (KIND == kIn16 ? 4 : 1)) * 16);
+        poff[1] = (unsigned)(pivot * 512 + (c0 ^ (is_16bit<KIND>() ? 4 : 1)) * 16);
     }
     const unsigned lds0 = lds_byte_address(lds);
 
@@ -611,6 +630,8 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
             tiles.mac_bf16(p);
         } else if constexpr (KIND == kIn16) {
             tiles.mac_in16(x);
+        } else if constexpr (KIND == kInF16) {
+            tiles.mac_inf16(x);
         } else {
             tiles.mac_fp32(x);
         }
@@ -620,18 +641,19 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
     // exponents are within 16 of each other), so each of the wave's two steps is widened,
     // centred and multiplied as split fp32.
     auto multiply_centred = [&](const Raw (&x)[NB], const Raw &pv) {
-        if constexpr (KIND == kIn16) {
-            const Raw p0 = widen8(pv.u), p1 = widen8(pv.w);
+        if constexpr (is_16bit<KIND>()) {
+            constexpr int FMT = storage_of<KIND>();
+            const Raw p0 = widen8<FMT>(pv.u), p1 = widen8<FMT>(pv.w);
             Pieces p[NB];
 #pragma unroll
             for (int I = 0; I < NB; ++I) {
-                const Raw y = raw_minus(widen8(x[I].u), p0);
+                const Raw y = raw_minus(widen8<FMT>(x[I].u), p0);
                 p[I] = split8(y.u, y.w);
             }
             tiles.mac_bf16(p);
 #pragma unroll
             for (int I = 0; I < NB; ++I) {
-                const Raw y = raw_minus(widen8(x[I].w), p1);
+                const Raw y = raw_minus(widen8<FMT>(x[I].w), p1);
                 p[I] = split8(y.u, y.w);
             }
             tiles.mac_bf16(p);
@@ -654,7 +676,7 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
         // a wave that is ready for the next tile goes first: the sooner all four are through the
         // barrier, the sooner the next loads are on their way (measured: 1 % on the whole pass
         // where there is arithmetic to compete with, nothing with bf16 input)
-        if constexpr (KIND != kIn16) __builtin_amdgcn_s_setprio(3);
+        if constexpr (!is_16bit<KIND>()) __builtin_amdgcn_s_setprio(3);
         if (mine - 1 - i >= S - 2) {
             wait_loads_then_barrier<L * (S - 2)>();
         } else {
@@ -662,7 +684,7 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
         }
         // every wave has left the buffer of tile i - 1: refill it
         if (i + S - 1 < mine) issue((int)((i + S - 1) % S), b + (i + S - 1) * g);
-        if constexpr (KIND != kIn16) __builtin_amdgcn_s_setprio(0);
+        if constexpr (!is_16bit<KIND>()) __builtin_amdgcn_s_setprio(0);
         Raw x[NB];
         read_tile<NB>(lds0 + (unsigned)((int)(i % S) * tile_floats * 4), off, x);
         if constexpr (CENTER) {
@@ -685,10 +707,10 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
         int64_t done = 0;
         for (int64_t u = gw; u < units; u += nwaves, ++done) {
             const int64_t c = c_begin + u * WC + 8 * q;      // this lane's 8 columns of the first step
-            // the lane's values of one row (KIND == kIn16: two steps, the bf16 words as they are)
+            // the lane's values of one row (16-bit input: two steps, the words as they are)
             auto load_row = [&](int row) {
                 Raw y;
-                if constexpr (KIND == kIn16) {
+                if constexpr (is_16bit<KIND>()) {
                     const unsigned short *p = reinterpret_cast<const unsigned short *>(G) + (int64_t)row * ld;
                     unsigned w0[4], w1[4];
 #pragma unroll
@@ -904,19 +926,26 @@ hipError_t launch_nb(const float *G, int n, int64_t d, int64_t ld, double *parti
 
 }  // namespace
 
-hipError_t launch_dist_gram_in16(const uint16_t *G, int n, int64_t d, int64_t ld, double *partials, int max_blocks,
-                                 int *nblocks, const double *first_pass, int *gate, hipStream_t s)
+hipError_t launch_dist_gram_in16(const uint16_t *G, int fmt, int n, int64_t d, int64_t ld, double *partials,
+                                 int max_blocks, int *nblocks, const double *first_pass, int *gate, hipStream_t s)
 {
-    if (max_blocks < 1) return hipErrorInvalidValue;
+    if (max_blocks < 1 || (fmt != kStoreBf16 && fmt != kStoreFp16)) return hipErrorInvalidValue;
     if (max_blocks > kGramMaxBlocks) max_blocks = kGramMaxBlocks;
     const SecondPass sp{first_pass, gate}, *second = first_pass ? &sp : nullptr;
     const bool aligned = ((uintptr_t)G % 16 == 0) && (ld % 8 == 0) && d >= tile_cols<kIn16>();
-    switch (gram_blocks(n)) {
-        case 1: return launch_dma<1, kIn16>(G, n, d, ld, aligned, partials, max_blocks, nblocks, second, s);
-        case 2: return launch_dma<2, kIn16>(G, n, d, ld, aligned, partials, max_blocks, nblocks, second, s);
-        case 3: return launch_dma<3, kIn16>(G, n, d, ld, aligned, partials, max_blocks, nblocks, second, s);
-        case 4: return launch_dma<4, kIn16>(G, n, d, ld, aligned, partials, max_blocks, nblocks, second, s);
+#define MB_NB(K)                                                                                                 \
+    switch (gram_blocks(n)) {                                                                                    \
+        case 1: return launch_dma<1, K>(G, n, d, ld, aligned, partials, max_blocks, nblocks, second, s);         \
+        case 2: return launch_dma<2, K>(G, n, d, ld, aligned, partials, max_blocks, nblocks, second, s);         \
+        case 3: return launch_dma<3, K>(G, n, d, ld, aligned, partials, max_blocks, nblocks, second, s);         \
+        case 4: return launch_dma<4, K>(G, n, d, ld, aligned, partials, max_blocks, nblocks, second, s);         \
     }
+    if (fmt == kStoreBf16) {
+        MB_NB(kIn16)
+    } else {
+        MB_NB(kInF16)
+    }
+#undef MB_NB
     return hipErrorInvalidValue;
 }
 

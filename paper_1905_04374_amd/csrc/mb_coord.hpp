@@ -8,9 +8,27 @@ namespace mb {
 
 constexpr int kMaxN = 64;
 
+// How the gradients are stored: fp32, or 16-bit words (bf16 = the upper half of the fp32 pattern; IEEE
+// fp16).  Both 16-bit formats widen exactly to fp32 in registers; everything computed from them is
+// fp32 / fp64 as for fp32 gradients.
+enum Storage { kStoreFp32 = 0, kStoreBf16 = 1, kStoreFp16 = 2 };
+
+// the 16-bit value in the low (hi = false) or high half of w, as fp32
+template <int FMT>
+__device__ __forceinline__ float widen16(unsigned w, bool hi)
+{
+    static_assert(FMT == kStoreBf16 || FMT == kStoreFp16, "a 16-bit format");
+    if constexpr (FMT == kStoreBf16) {
+        return __uint_as_float(hi ? (w & 0xffff0000u) : (w << 16));
+    } else {
+        const unsigned short h = (unsigned short)(hi ? (w >> 16) : (w & 0xffffu));
+        return (float)__builtin_bit_cast(_Float16, h);
+    }
+}
+
 // ---- coordinate pass -----------------------------------------------------
 struct CoordArgs {
-    const void *G;       // fp32, or bf16 as raw 16-bit words when in16 is set
+    const void *G;       // fp32, or raw 16-bit words when in16 is kStoreBf16 / kStoreFp16
     int n;
     int64_t d;
     int64_t ld;
@@ -23,16 +41,17 @@ struct CoordArgs {
 };
 hipError_t launch_coord_selected(const CoordArgs &a, hipStream_t s);
 // one per translation unit, covering theta in [8g+1, 8g+8]
-#define MB_DECL_GROUP(g)                                                \
-    hipError_t launch_coord_group##g(const CoordArgs &a, hipStream_t s); \
-    hipError_t launch_coord16_group##g(const CoordArgs &a, hipStream_t s);
+#define MB_DECL_GROUP(g)                                                  \
+    hipError_t launch_coord_group##g(const CoordArgs &a, hipStream_t s);   \
+    hipError_t launch_coord16_group##g(const CoordArgs &a, hipStream_t s); \
+    hipError_t launch_coordh_group##g(const CoordArgs &a, hipStream_t s);
 MB_DECL_GROUP(0) MB_DECL_GROUP(1) MB_DECL_GROUP(2) MB_DECL_GROUP(3)
 MB_DECL_GROUP(4) MB_DECL_GROUP(5) MB_DECL_GROUP(6) MB_DECL_GROUP(7)
 #undef MB_DECL_GROUP
 
 // Algorithm-1 mode: values are averages over row sets.
 struct CoordAlg1Args {
-    const void *G;           // fp32, or bf16 as raw 16-bit words when in16 is set
+    const void *G;           // fp32, or raw 16-bit words when in16 is kStoreBf16 / kStoreFp16
     int n;
     int64_t d;
     int64_t ld;
@@ -66,19 +85,27 @@ hipError_t launch_coord_alg1(const CoordAlg1Args &a, hipStream_t s);
 // one per translation unit, covering theta in [8g+1, 8g+8]
 hipError_t launch_coord_alg1_group0(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_16_group0(const CoordAlg1Args &a, hipStream_t s);
+hipError_t launch_coord_alg1_h_group0(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_group1(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_16_group1(const CoordAlg1Args &a, hipStream_t s);
+hipError_t launch_coord_alg1_h_group1(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_group2(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_16_group2(const CoordAlg1Args &a, hipStream_t s);
+hipError_t launch_coord_alg1_h_group2(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_group3(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_16_group3(const CoordAlg1Args &a, hipStream_t s);
+hipError_t launch_coord_alg1_h_group3(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_group4(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_16_group4(const CoordAlg1Args &a, hipStream_t s);
+hipError_t launch_coord_alg1_h_group4(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_group5(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_16_group5(const CoordAlg1Args &a, hipStream_t s);
+hipError_t launch_coord_alg1_h_group5(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_group6(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_16_group6(const CoordAlg1Args &a, hipStream_t s);
+hipError_t launch_coord_alg1_h_group6(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_group7(const CoordAlg1Args &a, hipStream_t s);
 hipError_t launch_coord_alg1_16_group7(const CoordAlg1Args &a, hipStream_t s);
+hipError_t launch_coord_alg1_h_group7(const CoordAlg1Args &a, hipStream_t s);
 
 }  // namespace mb

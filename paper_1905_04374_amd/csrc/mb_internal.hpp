@@ -42,9 +42,9 @@ hipError_t launch_dist_direct(const float *G, int n, int64_t d, int64_t ld, doub
 // the partial Gram tiles of the rows minus the pivot row.
 hipError_t launch_dist_gram(const float *G, int n, int64_t d, int64_t ld, double *partials, bool bf16,
                             int max_blocks, int *nblocks, const double *first_pass, int *gate, hipStream_t s);
-// the same for gradients stored as bf16 (raw 16-bit words, ld in elements)
-hipError_t launch_dist_gram_in16(const uint16_t *G, int n, int64_t d, int64_t ld, double *partials, int max_blocks,
-                                 int *nblocks, const double *first_pass, int *gate, hipStream_t s);
+// the same for gradients stored as 16-bit words (fmt = kStoreBf16 / kStoreFp16, ld in elements)
+hipError_t launch_dist_gram_in16(const uint16_t *G, int fmt, int n, int64_t d, int64_t ld, double *partials,
+                                 int max_blocks, int *nblocks, const double *first_pass, int *gate, hipStream_t s);
 // partials[nblocks][stride] -> reduced[0..slots) (fixed summation order).  gate (may be null): do
 // nothing unless gate[kGateFlag] is set (the reduction of a second pass that did not run).
 hipError_t launch_reduce(const double *partials, int nblocks, int stride, int slots, double *reduced,
@@ -72,7 +72,7 @@ hipError_t launch_select_gram(const double *reduced, const double *reduced2, con
 // out[c] = mean over rows r with mask[r] of G[r][c]
 hipError_t launch_masked_mean(const float *G, int n, int64_t d, int64_t ld, const uint8_t *mask,
                               float *out, hipStream_t s);
-hipError_t launch_masked_mean_in16(const uint16_t *G, int n, int64_t d, int64_t ld, const uint8_t *mask,
+hipError_t launch_masked_mean_in16(const uint16_t *G, int fmt, int n, int64_t d, int64_t ld, const uint8_t *mask,
                                    float *out, hipStream_t s);
 
 }  // namespace mb

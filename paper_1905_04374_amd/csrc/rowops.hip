@@ -16,12 +16,14 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kRows = 8;   // row loads in flight per lane (16 measured no faster)
 
-// IN16: gradients stored as bf16 (raw 16-bit words), widened exactly in registers; VEC is then 1 or 2.
-template <int VEC, bool IN16>
+// FMT != kStoreFp32: gradients stored as raw 16-bit words (bf16 or fp16), widened exactly in registers;
+// VEC is then 1 or 2.
+template <int VEC, int FMT>
 __global__ __launch_bounds__(256) void masked_mean_kernel(const void *__restrict__ Gv, int n, int64_t d,
                                                           int64_t ld, const uint8_t *__restrict__ mask,
                                                           float *__restrict__ out)
 {
+    constexpr bool IN16 = FMT != kStoreFp32;
     const float *G = static_cast<const float *>(Gv);
     const unsigned short *G16 = static_cast<const unsigned short *>(Gv);
     // the membership mask as 64 bits in scalar registers (n <= 64): lane r looks at row r
@@ -74,8 +76,8 @@ __global__ __launch_bounds__(256) void masked_mean_kernel(const void *__restrict
         if constexpr (IN16) {
 #pragma unroll
             for (int j = 0; j < kRows; ++j) {
-                x[j][0] = __uint_as_float(raw[j] << 16);
-                x[j][1 % VEC] = __uint_as_float(VEC == 2 ? raw[j] & 0xffff0000u : raw[j] << 16);
+                x[j][0] = widen16<IN16 ? FMT : kStoreBf16>(raw[j], false);
+                x[j][1 % VEC] = widen16<IN16 ? FMT : kStoreBf16>(raw[j], VEC == 2);
             }
         }
 #pragma unroll
@@ -114,20 +116,26 @@ hipError_t launch_masked_mean(const float *G, int n, int64_t d, int64_t ld, cons
 {
     const bool aligned = ((uintptr_t)G % 16 == 0) && (ld % 4 == 0);
     if (aligned)
-        masked_mean_kernel<4, false><<<dim3((unsigned)((d + 1023) / 1024)), dim3(256), 0, s>>>(G, n, d, ld, mask, out);
+        masked_mean_kernel<4, kStoreFp32><<<dim3((unsigned)((d + 1023) / 1024)), dim3(256), 0, s>>>(G, n, d, ld, mask, out);
     else
-        masked_mean_kernel<1, false><<<dim3((unsigned)((d + 255) / 256)), dim3(256), 0, s>>>(G, n, d, ld, mask, out);
+        masked_mean_kernel<1, kStoreFp32><<<dim3((unsigned)((d + 255) / 256)), dim3(256), 0, s>>>(G, n, d, ld, mask, out);
     return hipGetLastError();
 }
 
-hipError_t launch_masked_mean_in16(const uint16_t *G, int n, int64_t d, int64_t ld, const uint8_t *mask,
+hipError_t launch_masked_mean_in16(const uint16_t *G, int fmt, int n, int64_t d, int64_t ld, const uint8_t *mask,
                                    float *out, hipStream_t s)
 {
     const bool aligned = ((uintptr_t)G % 4 == 0) && (ld % 2 == 0);
-    if (aligned)
-        masked_mean_kernel<2, true><<<dim3((unsigned)((d + 511) / 512)), dim3(256), 0, s>>>(G, n, d, ld, mask, out);
-    else
-        masked_mean_kernel<1, true><<<dim3((unsigned)((d + 255) / 256)), dim3(256), 0, s>>>(G, n, d, ld, mask, out);
+    const dim3 grid2((unsigned)((d + 511) / 512)), grid1((unsigned)((d + 255) / 256));
+    if (fmt == kStoreBf16) {
+        if (aligned) masked_mean_kernel<2, kStoreBf16><<<grid2, dim3(256), 0, s>>>(G, n, d, ld, mask, out);
+        else masked_mean_kernel<1, kStoreBf16><<<grid1, dim3(256), 0, s>>>(G, n, d, ld, mask, out);
+    } else if (fmt == kStoreFp16) {
+        if (aligned) masked_mean_kernel<2, kStoreFp16><<<grid2, dim3(256), 0, s>>>(G, n, d, ld, mask, out);
+        else masked_mean_kernel<1, kStoreFp16><<<grid1, dim3(256), 0, s>>>(G, n, d, ld, mask, out);
+    } else {
+        return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 

@@ -92,5 +92,12 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert lib.mbulyan_aggregate_noalloc(one, 10, 2, 100, 100, 0, one, None, None) == mb.MB_EPRECOND
     assert lib.mbulyan_aggregate_noalloc(one, 11, 2, 100, 99, 0, one, None, None) == mb.MB_EINVAL
     assert lib.mbulyan_aggregate_noalloc(one, 11, 2, 100, 100, 0, None, None, None) == mb.MB_EINVAL
+    # gradients in host memory: the same checks before anything is allocated
+    assert lib.mbulyan_aggregate_host(None, 0, 11, 2, 100, 100, 0, 50, one, None, None) == mb.MB_EINVAL
+    assert lib.mbulyan_aggregate_host(one, 0, 10, 2, 100, 100, 0, 50, one, None, None) == mb.MB_EPRECOND
+    assert lib.mbulyan_aggregate_host(one, 7, 11, 2, 100, 100, 0, 50, one, None, None) == mb.MB_EINVAL
+    assert lib.mbulyan_aggregate_host(one, 0, 11, 2, 100, 100, 0, 0, one, None, None) == mb.MB_EINVAL
+    assert lib.mbulyan_aggregate_fp16(one, 10, 2, 100, 100, 0, 0, 0, one, None, None, 0, None) == mb.MB_EPRECOND
+    assert lib.pairwise_sqdist_fp16(one, 11, 100, 100, None, 0, None, 0, None) == mb.MB_EINVAL
     assert lib.mbulyan_set_dist_algo(5) == mb.MB_EINVAL
     assert lib.mbulyan_set_dist_algo(0) == mb.MB_OK
