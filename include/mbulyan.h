@@ -139,7 +139,7 @@ int mbulyan_aggregate_ex(const float *grads, int n, int f, int64_t d,
  *                              be NULL)
  * Limits: n <= MB_MAX_N (MB_EUNSUPPORTED beyond, nothing launched), any d: the
  * distance pass is launched with no more workgroups than the array has room
- * for (16 MiB hold the partial sums of at least 815 of them at n = 64, more
+ * for (16 MiB hold the partial sums of at least 814 of them at n = 64, more
  * than stay resident on the device).  MB_EWORKSPACE if the array could not
  * hold one workgroup's sums (cannot happen with the sizes above).
  * The first call on a device looks up the address of that device's copy of the

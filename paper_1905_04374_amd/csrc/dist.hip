@@ -117,6 +117,7 @@ __global__ void finalize_direct_kernel(const double *__restrict__ reduced, int n
             const int I = hi / kRB, J = lo / kRB;
             const int bp = I * (I + 1) / 2 + J;
             v = reduced[bp * 64 + (hi % kRB) * kRB + (lo % kRB)];
+            if (!(v == v)) v = __builtin_huge_val();   // a gradient that holds a NaN or an infinity is infinitely far away
         }
         dist[e] = accumulate ? dist[e] + v : v;
     }
@@ -145,7 +146,8 @@ __global__ __launch_bounds__(1024) void finalize_gram_kernel(const double *__res
     __syncthreads();
     for (int e = threadIdx.x; e < n * n; e += blockDim.x) {
         const int i = rep[e / n], j = rep[e % n];
-        const double v = i == j ? 0.0 : gram_pair_distance(reduced, reduced2, refined, i > j ? i : j, i > j ? j : i);
+        double v = i == j ? 0.0 : gram_pair_distance(reduced, reduced2, refined, i > j ? i : j, i > j ? j : i);
+        if (!(v == v)) v = __builtin_huge_val();   // a gradient that holds a NaN or an infinity is infinitely far away
         dist[e] = accumulate ? dist[e] + v : v;
     }
 }

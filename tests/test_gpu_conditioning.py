@@ -131,3 +131,51 @@ def test_a_huge_byzantine_row_harms_only_its_own_distances():
         D = O.pairwise_sqdist(G)
         Dg = mb.pairwise_sqdist(Gh).cpu().numpy()
         assert rel_err(Dg, D) <= 1e-6
+
+
+def test_degenerate_inputs_through_the_two_pass_path():
+    """Edge cases of the check that decides on the second pass: a single gradient, two gradients, all
+    gradients identical (every pair a copy: nothing to flag), all zero, and an ill-conditioned input that
+    also holds a non-finite Byzantine row (which must neither be chosen as the pivot nor break the check)."""
+    say("degenerate inputs")
+    d = 50_000
+    rng = np.random.default_rng(6)
+    # one gradient, two gradients (f = 0)
+    one = (rng.standard_normal((1, d)) + 100.0).astype(np.float32)
+    assert mb.pairwise_sqdist(torch.as_tensor(one).to(DEV)).cpu().numpy().tolist() == [[0.0]]
+    two = np.stack([one[0], one[0] + (rng.standard_normal(d) * 1e-3).astype(np.float32)])
+    D = O.pairwise_sqdist(two)
+    Dg = mb.pairwise_sqdist(torch.as_tensor(two).to(DEV)).cpu().numpy()
+    assert D[0, 1] > 0 and abs(Dg[0, 1] - D[0, 1]) <= 1e-6 * D[0, 1] and Dg[0, 0] == 0.0 and Dg[1, 1] == 0.0
+    # all identical, large norm: every distance exactly 0, the rule returns that gradient
+    same = np.repeat(one, 11, axis=0)
+    assert not mb.pairwise_sqdist(torch.as_tensor(same).to(DEV)).cpu().numpy().any()
+    for mode in (mb.MODE_SELECTED, mb.MODE_ALG1):
+        out, sel = mb.mbulyan_aggregate_ex(torch.as_tensor(same).to(DEV), 2, mode=mode)
+        assert sel.cpu().numpy().tolist() == list(range(sel.numel()))
+        assert np.allclose(out.cpu().numpy(), one[0], rtol=3e-7, atol=0)
+    # all zero
+    zero = torch.zeros(7, d, device=DEV)
+    assert not mb.pairwise_sqdist(zero).cpu().numpy().any()
+    out, sel = mb.mbulyan_aggregate_ex(zero, 1)
+    assert not out.cpu().numpy().any() and sel.cpu().numpy().tolist() == [0, 1, 2, 3, 4]
+    # ill-conditioned and a non-finite row, first or last
+    n, f = 19, 4
+    base = W.offset(n, f, 100_000, 1e5, DEV)
+    for where in (0, n - 1):
+        bad, far = base.clone(), base.clone()
+        bad[where, ::3] = float("nan")
+        bad[where, 1::3] = float("inf")
+        far[where] = 1e12
+        G = far.cpu().numpy()
+        Dref = O.pairwise_sqdist(G)
+        Dg = mb.pairwise_sqdist(bad).cpu().numpy()
+        keep = np.ones(n, bool)
+        keep[where] = False
+        sub, subg = Dref[np.ix_(keep, keep)], Dg[np.ix_(keep, keep)]
+        assert np.max(np.abs(subg - sub)[sub > 0] / sub[sub > 0]) <= 1e-6
+        assert np.all(np.isinf(Dg[where, keep])) and Dg[where, where] == 0.0
+        theta, _ = O.params(n, f)
+        ext, _, _ = O.multikrum_select(Dref, f, theta)
+        _, sel = mb.mbulyan_aggregate_ex(bad, f)
+        assert sel.cpu().numpy().tolist() == ext.tolist()
