@@ -353,7 +353,11 @@ int coordwise_median(const float *grads, int n, int64_t d, int64_t ld,
 
 /*
  * Per-kernel timing of the calls above, with HIP events recorded on the call's
- * own stream.  mbulyan_timing_enable(1) starts collecting, (0) stops.
+ * own stream.  mbulyan_timing_enable(stages) starts collecting for the stages
+ * whose bits (1 << MB_STAGE_x) are set, MB_STAGE_ALL for all of them; (0)
+ * stops.  Every timed stage puts two event records into the stream per call,
+ * a few microseconds each: time one stage alone where a call takes less than
+ * a millisecond.
  * mbulyan_timing_read synchronises the recorded events and returns, per stage,
  * the summed milliseconds and the number of launches since the last
  * mbulyan_timing_reset.  Stages: 0 distance pass (first pass of the Gram
@@ -368,7 +372,8 @@ int coordwise_median(const float *grads, int n, int64_t d, int64_t ld,
 #define MB_STAGE_COORD 3
 #define MB_STAGE_REFINE 4
 #define MB_NUM_STAGES 5
-int mbulyan_timing_enable(int on);
+#define MB_STAGE_ALL ((1 << MB_NUM_STAGES) - 1)
+int mbulyan_timing_enable(int stages);
 int mbulyan_timing_reset(void);
 int mbulyan_timing_read(double *ms_per_stage, int64_t *launches_per_stage);
 

@@ -341,8 +341,10 @@ def coordwise_median(grads, out=None, stream=None):
     return out
 
 
-def mbulyan_timing_enable(on: bool):
-    _check(lib.mbulyan_timing_enable(int(on)))
+def mbulyan_timing_enable(on: bool, stages=None):
+    """stages: names out of STAGES to time (each costs two event records per call); None: all of them."""
+    mask = sum(1 << STAGES.index(s) for s in (STAGES if stages is None else stages)) if on else 0
+    _check(lib.mbulyan_timing_enable(mask))
 
 
 def mbulyan_timing_reset():

@@ -128,7 +128,7 @@ struct Span {
     int stage;
     hipEvent_t a, b;
 };
-bool g_timing = false;
+unsigned g_timing = 0;   // bit k: stage k is being timed
 thread_local bool tl_no_timing = false;   // set while an entry point that must not create events runs
 std::vector<Span> g_spans;
 double g_ms[MB_NUM_STAGES] = {};
@@ -138,7 +138,7 @@ struct StageTimer {
     bool on;
     Span sp;
     hipStream_t s;
-    StageTimer(int stage, hipStream_t stream) : on(g_timing && !tl_no_timing), s(stream)
+    StageTimer(int stage, hipStream_t stream) : on(((g_timing >> stage) & 1u) && !tl_no_timing), s(stream)
     {
         if (!on) return;
         sp.stage = stage;
@@ -726,9 +726,9 @@ MB_16BIT_ENTRY_POINTS(bf16, mb::kStoreBf16)
 MB_16BIT_ENTRY_POINTS(fp16, mb::kStoreFp16)
 #undef MB_16BIT_ENTRY_POINTS
 
-int mbulyan_timing_enable(int on)
+int mbulyan_timing_enable(int stages)
 {
-    g_timing = on != 0;
+    g_timing = static_cast<unsigned>(stages) & ((1u << MB_NUM_STAGES) - 1u);
     return MB_OK;
 }
 
