@@ -110,7 +110,8 @@ int mbulyan_set_dist_algo(int algo);
  *                extraction order
  * Uses a workspace owned by the library (allocated on the first call on a
  * device and grown when a later call needs more; freed by mbulyan_release).
- * Launches: distance pass, its reduction, selection, coordinate pass.
+ * Launches: distance pass, its reduction, the second distance pass (returns at
+ * once unless the first was ill conditioned), selection, coordinate pass.
  */
 int mbulyan_aggregate(const float *grads, int n, int f, int64_t d, float *out,
                       int32_t *selected_idx, void *stream);
@@ -362,8 +363,8 @@ int coordwise_median(const float *grads, int n, int64_t d, int64_t ld,
  * the summed milliseconds and the number of launches since the last
  * mbulyan_timing_reset.  Stages: 0 distance pass (first pass of the Gram
  * forms), 1 distance reduction, 2 selection, 3 coordinate pass, 4 the second
- * pass of the Gram forms and its reduction (launched every time; a few
- * microseconds when the first pass was well conditioned).  Both arrays have
+ * pass of the Gram forms (launched every time; a few microseconds when the
+ * first pass was well conditioned; it reduces its own partial sums).  Both arrays have
  * MB_NUM_STAGES entries.  Host only; not thread safe.
  */
 #define MB_STAGE_DIST 0

@@ -178,8 +178,8 @@ int check_matrix(const void *grads, int n, int64_t d, int64_t ld)
 }
 
 // distances of one matrix into ws.dist()
-// Gram form: first pass, its reduction, then the second (centred) pass and its reduction, both of
-// which find out on the device whether they are needed (gram_combine.hpp) and return at once if not.
+// Gram form: first pass, its reduction, then the second (centred) pass, which finds out on the device
+// whether it is needed (gram_combine.hpp) and returns at once if not.
 // `defer` (may be null): leave the last step, Gram tiles -> distance matrix, to the selection kernel
 // (it forms the matrix itself from ws.reduced(), ws.reduced2(), ws.gate()); set to 1 when that was possible.
 // in16: mb::kStoreFp32, or gradients stored as 16-bit words (kStoreBf16 / kStoreFp16): Gram form only
@@ -191,20 +191,24 @@ int run_dist_gram(const void *grads, int in16, bool bf16, int n, int64_t d, int6
     const int room = ws.max_blocks(slots);
     if (room < 1) return MB_EWORKSPACE;
     for (int pass = 0; pass < 2; ++pass) {
+        // second pass: decides on the device whether it runs; its last workgroup reduces its tiles itself
         const double *first = pass ? ws.reduced() : nullptr;
+        double *second_sums = pass ? ws.reduced2() : nullptr;
         int *gate = pass ? ws.gate() : nullptr;
         int nblocks = 0;
         {
             StageTimer t(pass ? MB_STAGE_REFINE : MB_STAGE_DIST, s);
             if (in16)
                 MB_HIP(mb::launch_dist_gram_in16(static_cast<const uint16_t *>(grads), in16, n, d, ld, ws.partials(), room,
-                                                 &nblocks, first, gate, s));
+                                                 &nblocks, first, second_sums, gate, s));
             else
                 MB_HIP(mb::launch_dist_gram(static_cast<const float *>(grads), n, d, ld, ws.partials(), bf16, room,
-                                            &nblocks, first, gate, s));
+                                            &nblocks, first, second_sums, gate, s));
         }
-        StageTimer t(pass ? MB_STAGE_REFINE : MB_STAGE_REDUCE, s);
-        MB_HIP(mb::launch_reduce(ws.partials(), nblocks, slots, slots, pass ? ws.reduced2() : ws.reduced(), gate, s));
+        if (pass == 0) {
+            StageTimer t(MB_STAGE_REDUCE, s);
+            MB_HIP(mb::launch_reduce(ws.partials(), nblocks, slots, slots, ws.reduced(), ws.gate() + mb::kGateTicket, s));
+        }
     }
     if (defer && !accumulate) {
         *defer = 1;

@@ -164,10 +164,10 @@ constexpr int kRedBatch = 16;
 
 __global__ __launch_bounds__(kRedSegs * kRedSlots) void reduce_partials_kernel(
     const double *__restrict__ partials, int nblocks, int stride, int slots, double *__restrict__ reduced,
-    const int *__restrict__ gate)
+    int *__restrict__ ticket)
 {
     __shared__ double seg_sum[kRedSegs][kRedSlots + 1];
-    if (gate && gate[kGateFlag] == 0) return;   // the pass whose sums these would be did not run
+    if (ticket && blockIdx.x == 0 && threadIdx.x == 0) *ticket = 0;   // for the launch that follows in the stream
     const int el = threadIdx.x % kRedSlots;
     const int seg = threadIdx.x / kRedSlots;
     const int e = blockIdx.x * kRedSlots + el;
@@ -220,10 +220,10 @@ hipError_t launch_dist_direct(const float *G, int n, int64_t d, int64_t ld, doub
 }
 
 hipError_t launch_reduce(const double *partials, int nblocks, int stride, int slots, double *reduced,
-                         const int *gate, hipStream_t s)
+                         int *ticket, hipStream_t s)
 {
     reduce_partials_kernel<<<dim3((slots + kRedSlots - 1) / kRedSlots), dim3(kRedSegs * kRedSlots), 0, s>>>(
-        partials, nblocks, stride, slots, reduced, gate);
+        partials, nblocks, stride, slots, reduced, ticket);
     return hipGetLastError();
 }
 

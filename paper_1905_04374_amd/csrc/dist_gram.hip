@@ -19,10 +19,11 @@
 //  fp32:  v_mfma_f32_16x16x4_f32, eight k-slices per step.  At n = 39 its 1536 MACs per
 //         coordinate take exactly as long as the 156 bytes take from HBM: on the ridge.
 //  bf16:  every fp32 value is split exactly into three bf16 pieces x = hi + mid + lo (8
-//         significand bits each, by truncation, so the remainders are exact).  A product x*y is
-//         the sum of nine piece products, each exact in fp32; the six largest (hi*hi, hi*mid,
-//         mid*hi, hi*lo, lo*hi, mid*mid) are accumulated, the dropped ones are below 2^-24 of
-//         x*y - the size of one fp32 rounding.  v_mfma_f32_16x16x32_bf16 consumes a whole step
+//         significand bits each, each the remainder so far rounded to nearest, so the
+//         remainders are exact).  A product x*y is the sum of nine piece products, each exact
+//         in fp32; the six largest (hi*hi, hi*mid, mid*hi, hi*lo, lo*hi, mid*mid) are
+//         accumulated, the dropped ones (mid*lo, lo*mid, lo*lo) are below 2^-26 of x*y each and
+//         of either sign from one coordinate to the next.  v_mfma_f32_16x16x32_bf16 consumes a whole step
 //         per instruction: six of them at 16 cycles replace eight at 32, so the matrix cores
 //         stop being the limit and the kernel is bound by the HBM stream.
 //
@@ -54,19 +55,32 @@ struct Pieces {
     uintx4 hi, mid, lo;   // 8 bf16 each: element e in half (e & 1) of word e / 2
 };
 
-// two floats -> one packed word of each piece
+// two floats -> one packed bf16 pair, rounded to nearest even (v_cvt_pk_bf16_f32): a in the lower half
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned pack_bf16(float a, float b)
+{
+    const floatx2 v = {a, b};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
+}
+
+// two floats -> one packed word of each piece.  Every piece is the remainder so far rounded to
+// nearest, so the remainders are exact, of either sign, and at most half an ulp of the piece
+// before: |mid| <= 2^-9 |x|, |lo| <= 2^-18 |x|, and lo has at most 7 significant bits left.
+// (Truncation would do as well for exactness, but its remainders all carry the sign of x: the
+// dropped products mid*lo then have the sign of x_i*x_j in every coordinate and add up to a
+// bias of about 6e-8 of |G_ij|, i.e. 1.2e-7 of the norms in the distance of two rows that point in
+// opposite directions.)
 __device__ __forceinline__ void split_pair(float a, float b, unsigned &hi, unsigned &mid, unsigned &lo)
 {
-    constexpr unsigned kTop = 0xffff0000u, kSel = 0x07060302u;   // upper halves of (b, a)
-    const unsigned ua = __float_as_uint(a), ub = __float_as_uint(b);
-    hi = __builtin_amdgcn_perm(ub, ua, kSel);
-    const float ra = a - __uint_as_float(ua & kTop);
-    const float rb = b - __uint_as_float(ub & kTop);
-    const unsigned va = __float_as_uint(ra), vb = __float_as_uint(rb);
-    mid = __builtin_amdgcn_perm(vb, va, kSel);
-    const float sa = ra - __uint_as_float(va & kTop);
-    const float sb = rb - __uint_as_float(vb & kTop);
-    lo = __builtin_amdgcn_perm(__float_as_uint(sb), __float_as_uint(sa), kSel);
+    constexpr unsigned kTop = 0xffff0000u;
+    hi = pack_bf16(a, b);
+    const float ra = a - __uint_as_float(hi << 16);
+    const float rb = b - __uint_as_float(hi & kTop);
+    mid = pack_bf16(ra, rb);
+    const float sa = ra - __uint_as_float(mid << 16);
+    const float sb = rb - __uint_as_float(mid & kTop);
+    lo = pack_bf16(sa, sb);
 }
 
 __device__ __forceinline__ Pieces split8(const float4 &u, const float4 &w)
@@ -228,12 +242,56 @@ __device__ __forceinline__ int gram_gate(const double *__restrict__ R1, int n, d
     return *pick;
 }
 
+// Second pass only: the workgroup that finishes last adds up the tiles of all workgroups, in
+// workgroup order (a function of the data alone), and leaves the sums where the reduction kernel
+// would have put them, so that no reduction launch has to follow a pass that mostly does not run.
+// Nothing waits for anything: a workgroup draws a ticket once its own tile is visible device-wide,
+// and whoever draws the last one finds every tile written.  gate[kGateTicket] is 0 at the start of
+// the launch (the first pass's reduction kernel, which precedes it in the stream, sets it).
+// Every thread of the workgroup calls it, after its stores to `partials`; `last` is a word of LDS
+// no thread still reads.  NT x 256 entries per tile set, kThreads = 256 threads.
+template <int NT>
+__device__ __forceinline__ void sum_tiles_if_last(const double *partials, double *__restrict__ sums, int *gate,
+                                                  int *last, int tid)
+{
+    __threadfence();   // release: this thread's part of the tile
+    __syncthreads();
+    if (tid == 0) *last = (atomicAdd(&gate[kGateTicket], 1) == (int)gridDim.x - 1) ? 1 : 0;
+    __syncthreads();
+    if (*last == 0) return;
+    __threadfence();   // acquire: the other workgroups' tiles
+    const int nb = (int)gridDim.x;
+    double acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = 0.0;
+    constexpr int kAhead = NT <= 3 ? 8 : 4;   // workgroups whose entries are in flight together
+    for (int b = 0; b < nb; b += kAhead) {
+        double x[kAhead][NT];
+#pragma unroll
+        for (int k = 0; k < kAhead; ++k) {
+            const int bb = b + k < nb ? b + k : nb - 1;
+            const double *src = partials + (int64_t)bb * (NT * 256);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) x[k][t] = src[t * 256 + tid];
+        }
+#pragma unroll
+        for (int k = 0; k < kAhead; ++k) {
+            if (b + k < nb) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t) acc[t] += x[k][t];
+            }
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t) sums[t * 256 + tid] = acc[t];
+}
+
 template <int NB, bool BF16, int DEPTH, bool CENTER>
 __global__ __launch_bounds__(kThreads) void gram_kernel(const float *__restrict__ G, int n, int64_t d,
                                                         int64_t ld, int aligned,
                                                         double *__restrict__ partials,
                                                         const double *__restrict__ first_pass,
-                                                        int *__restrict__ gate)
+                                                        double *__restrict__ second_sums, int *__restrict__ gate)
 {
     constexpr int NT = NB * (NB + 1) / 2;
     constexpr int NR = NB + (CENTER ? 1 : 0);   // row blocks a lane loads: with CENTER, the pivot row as one more
@@ -377,6 +435,10 @@ __global__ __launch_bounds__(kThreads) void gram_kernel(const float *__restrict_
     double *dst = partials + (int64_t)blockIdx.x * (NT * 256);
 #pragma unroll
     for (int t = 0; t < NT; ++t) dst[t * 256 + tid] = sums[t];
+    if constexpr (CENTER) {
+        __syncthreads();   // the staging area is free
+        sum_tiles_if_last<NT>(partials, second_sums, gate, reinterpret_cast<int *>(&stage[0][0]), tid);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -526,7 +588,7 @@ template <int KIND> constexpr int tile_cols() { return 512 / elem_bytes<KIND>();
 template <int NB, int KIND, int L, bool CENTER, int S>
 __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_kernel(
     const void *__restrict__ Gv, int n, int64_t d, int64_t ld, int64_t ntiles, double *__restrict__ partials,
-    const double *__restrict__ first_pass, int *__restrict__ gate)
+    const double *__restrict__ first_pass, double *__restrict__ second_sums, int *__restrict__ gate)
 {
     constexpr int NT = NB * (NB + 1) / 2;
     constexpr int EB = elem_bytes<KIND>();
@@ -771,6 +833,10 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
     double *out = partials + (int64_t)blockIdx.x * (NT * 256);
 #pragma unroll
     for (int t = 0; t < NT; ++t) out[t * 256 + tid] = total[t];
+    if constexpr (CENTER) {
+        __syncthreads();   // every thread has read its entries of `red`
+        sum_tiles_if_last<NT>(partials, second_sums, gate, reinterpret_cast<int *>(lds), tid);
+    }
 }
 
 // What the host knows about one kernel on one device: whether the LDS limit has been raised and how
@@ -790,6 +856,7 @@ inline hipError_t current_device(int *dev)
 // reduced Gram tiles and leaves its flag and pivot in `gate`.
 struct SecondPass {
     const double *first_pass;
+    double *sums;   // where its reduced tiles go
     int *gate;
 };
 
@@ -836,7 +903,8 @@ hipError_t launch_dma_s(const void *G, int n, int64_t d, int64_t ld, bool aligne
     if (work < 4 * g) g = work < 4 ? 1 : work / 4;
     *nblocks = (int)g;
     gram_dma_kernel<NB, KIND, L, CENTER, S><<<dim3((unsigned)g), dim3(kThreads), bytes, s>>>(
-        G, n, d, ld, tiles, partials, second ? second->first_pass : nullptr, second ? second->gate : nullptr);
+        G, n, d, ld, tiles, partials, second ? second->first_pass : nullptr, second ? second->sums : nullptr,
+        second ? second->gate : nullptr);
     return hipGetLastError();
 }
 
@@ -872,7 +940,8 @@ hipError_t launch_one(const float *G, int n, int64_t d, int64_t ld, double *part
 {
     const int aligned = ((uintptr_t)G % 16 == 0) && (ld % 4 == 0);
     gram_kernel<NB, BF16, DEPTH, CENTER><<<dim3(nblocks), dim3(kThreads), 0, s>>>(
-        G, n, d, ld, aligned, partials, second ? second->first_pass : nullptr, second ? second->gate : nullptr);
+        G, n, d, ld, aligned, partials, second ? second->first_pass : nullptr, second ? second->sums : nullptr,
+        second ? second->gate : nullptr);
     return hipGetLastError();
 }
 
@@ -927,11 +996,12 @@ hipError_t launch_nb(const float *G, int n, int64_t d, int64_t ld, double *parti
 }  // namespace
 
 hipError_t launch_dist_gram_in16(const uint16_t *G, int fmt, int n, int64_t d, int64_t ld, double *partials,
-                                 int max_blocks, int *nblocks, const double *first_pass, int *gate, hipStream_t s)
+                                 int max_blocks, int *nblocks, const double *first_pass, double *second_sums,
+                                 int *gate, hipStream_t s)
 {
     if (max_blocks < 1 || (fmt != kStoreBf16 && fmt != kStoreFp16)) return hipErrorInvalidValue;
     if (max_blocks > kGramMaxBlocks) max_blocks = kGramMaxBlocks;
-    const SecondPass sp{first_pass, gate}, *second = first_pass ? &sp : nullptr;
+    const SecondPass sp{first_pass, second_sums, gate}, *second = first_pass ? &sp : nullptr;
     const bool aligned = ((uintptr_t)G % 16 == 0) && (ld % 8 == 0) && d >= tile_cols<kIn16>();
 #define MB_NB(K)                                                                                                 \
     switch (gram_blocks(n)) {                                                                                    \
@@ -950,11 +1020,12 @@ hipError_t launch_dist_gram_in16(const uint16_t *G, int fmt, int n, int64_t d, i
 }
 
 hipError_t launch_dist_gram(const float *G, int n, int64_t d, int64_t ld, double *partials, bool bf16,
-                            int max_blocks, int *nblocks, const double *first_pass, int *gate, hipStream_t s)
+                            int max_blocks, int *nblocks, const double *first_pass, double *second_sums, int *gate,
+                            hipStream_t s)
 {
     if (max_blocks < 1) return hipErrorInvalidValue;
     if (max_blocks > kGramMaxBlocks) max_blocks = kGramMaxBlocks;
-    const SecondPass sp{first_pass, gate}, *second = first_pass ? &sp : nullptr;
+    const SecondPass sp{first_pass, second_sums, gate}, *second = first_pass ? &sp : nullptr;
     const int nb = gram_blocks(n);
     if (bf16) {
         switch (nb) {

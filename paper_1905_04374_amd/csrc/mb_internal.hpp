@@ -15,9 +15,10 @@ constexpr int kDirectSlots = 36 * 64;
 constexpr int kGramMaxBlocks = 2048;
 constexpr int gram_blocks(int n) { return (n + 15) / 16; }
 constexpr int gram_slots(int n) { return gram_blocks(n) * (gram_blocks(n) + 1) / 2 * 256; }
-// the two words the second pass of the Gram form leaves for the kernels after it
+// the words the second pass of the Gram form leaves for the kernels after it, and its ticket counter
 constexpr int kGateFlag = 0;    // 1: the second pass ran and its reduced tiles are to be used
 constexpr int kGatePivot = 1;   // its pivot row
+constexpr int kGateTicket = 2;  // workgroups of the second pass that have written their tile (zeroed by launch_reduce)
 
 // Element (i, j), i >= j, of the Gram matrix inside the reduced tile array.  Tile (I, J) holds
 // rows 16I.. as the A operand and rows 16J.. as the B operand; the instruction leaves entry
@@ -38,17 +39,21 @@ hipError_t launch_dist_direct(const float *G, int n, int64_t d, int64_t ld, doub
 // max_blocks >= 1: what `partials` has room for) and reports the count.
 // first_pass == null: the first pass (rows as they are).  Otherwise the second pass: first_pass =
 // the reduced Gram tiles of the first; the kernel decides on the device whether it is needed,
-// chooses the pivot row, leaves both in gate[kGateFlag], gate[kGatePivot] and, if needed, writes
-// the partial Gram tiles of the rows minus the pivot row.
+// chooses the pivot row, leaves both in gate[kGateFlag], gate[kGatePivot] and, if needed, computes
+// the Gram tiles of the rows minus the pivot row: partial tiles into `partials`, and the workgroup
+// that finishes last adds them up into second_sums (so no reduction launch follows this pass).
+// gate[kGateTicket] must be 0 when the second pass starts: launch_reduce of the first pass sees to it.
 hipError_t launch_dist_gram(const float *G, int n, int64_t d, int64_t ld, double *partials, bool bf16,
-                            int max_blocks, int *nblocks, const double *first_pass, int *gate, hipStream_t s);
+                            int max_blocks, int *nblocks, const double *first_pass, double *second_sums, int *gate,
+                            hipStream_t s);
 // the same for gradients stored as 16-bit words (fmt = kStoreBf16 / kStoreFp16, ld in elements)
 hipError_t launch_dist_gram_in16(const uint16_t *G, int fmt, int n, int64_t d, int64_t ld, double *partials,
-                                 int max_blocks, int *nblocks, const double *first_pass, int *gate, hipStream_t s);
-// partials[nblocks][stride] -> reduced[0..slots) (fixed summation order).  gate (may be null): do
-// nothing unless gate[kGateFlag] is set (the reduction of a second pass that did not run).
+                                 int max_blocks, int *nblocks, const double *first_pass, double *second_sums,
+                                 int *gate, hipStream_t s);
+// partials[nblocks][stride] -> reduced[0..slots) (fixed summation order).  ticket (may be null): a
+// word the kernel sets to 0 (the ticket counter of the second pass that follows).
 hipError_t launch_reduce(const double *partials, int nblocks, int stride, int slots, double *reduced,
-                         const int *gate, hipStream_t s);
+                         int *ticket, hipStream_t s);
 hipError_t launch_finalize_direct(const double *reduced, int n, double *dist, int accumulate, hipStream_t s);
 // Gram tiles of the first pass, of the second pass and its gate words (both null: no second pass was
 // launched) -> dist[n*n]

@@ -15,15 +15,12 @@ import torch
 import alg1_check
 import oracle as O
 import paper_1905_04374_amd as mb
+from progress import say
 import workloads as W
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
-
-def say(*a):
-    print("[case]", *a, flush=True)
-    sys.stdout.flush()
 
 
 def check_chunk(got, ref, scale):

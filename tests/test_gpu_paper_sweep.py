@@ -21,6 +21,7 @@ import torch
 import alg1_check
 import oracle as O
 import paper_1905_04374_amd as mb
+from progress import say
 import workloads as W
 
 pytestmark = pytest.mark.gpu
@@ -29,10 +30,6 @@ D_SWEEP = 100_000
 # U(0,1): |x|^2 = d/3, D = d/6, so 1e-7 (|x_i|^2 + |x_j|^2) = 4e-7 D is what the Gram form may be off by
 TAU = 4e-7
 
-
-def say(*a):
-    print("[case]", *a, flush=True)
-    sys.stdout.flush()
 
 
 def replay(D, f, sel, sets, tau):

@@ -15,6 +15,7 @@ import torch
 import alg1_check
 import oracle as O
 import paper_1905_04374_amd as mb
+from progress import say
 import workloads as W
 
 pytestmark = pytest.mark.gpu
@@ -23,10 +24,6 @@ DEV = "cuda:0"
 
 ALGOS = [mb.DIST_DIRECT, mb.DIST_GRAM, mb.DIST_GRAM_BF16]
 
-
-def say(*a):
-    print("[case]", *a, flush=True)
-    sys.stdout.flush()
 
 
 def gpu(x):

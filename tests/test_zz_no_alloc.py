@@ -13,15 +13,12 @@ import pytest
 import torch
 
 import paper_1905_04374_amd as mb
+from progress import say
 import workloads as W
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
-
-def say(*a):
-    print("[case]", *a, flush=True)
-    sys.stdout.flush()
 
 
 def raw_noalloc(G, f, mode, out, sel):
