@@ -18,8 +18,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch of the distance kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
 # scaled by what the same counter reads for a 4 GiB device copy (FETCH_SIZE reads half the bytes
 # of the copy, WRITE_SIZE all of them); see profiles/gram_dma_kernel_cfg4_n39_d250M_hbm_traffic.md
-MEASURED_TRAFFIC_BYTES = {(4, "gram_bf16"): 2 * 19043035 * 1024 + 9216 * 1024,
-                          (4, "in16"): 2 * 9521537 * 1024 + 9216 * 1024}
+MEASURED_TRAFFIC_BYTES = {(4, "f32"): 2 * 19043030 * 1024 + 9216 * 1024,
+                          (4, "bf16"): 2 * 9521538 * 1024 + 9216 * 1024,
+                          (4, "fp16"): 2 * 9521540 * 1024 + 9216 * 1024,
+                          (5, "f32"): 2 * 24924287 * 1024 + 10240 * 1024}
 MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix, published
 
@@ -70,6 +72,33 @@ def sweep():
             print(json.dumps(row), flush=True)
 
 
+def host_resident(a, mb, W, n, f, d, mode, dtype):
+    """Gradients that stay in (pinned) host memory: every step uploads them twice (the selection needs the
+    distances over all coordinates before any coordinate can be aggregated) and downloads the result."""
+    import torch
+    g = torch.empty(n, d, device="cuda:0", dtype=torch.float32)
+    W.fill(a.config, g, 0)
+    host = torch.empty(n, d, dtype=dtype, pin_memory=True)
+    host.copy_(g)
+    del g
+    out = torch.empty(d, dtype=torch.float32, pin_memory=True)
+    for _ in range(a.warmup):
+        mb.mbulyan_aggregate_host(host, f, a.host_resident, mode=mode, host_out=out)
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        mb.mbulyan_aggregate_host(host, f, a.host_resident, mode=mode, host_out=out)   # blocks until out is written
+    sec = (time.perf_counter() - t0) / a.steps
+    eb = host.element_size()
+    print(json.dumps({
+        "metric": "multi-Bulyan aggregation GB/s of gradient input, gradients in pinned host memory (PCIe-inclusive)",
+        "value": round(eb * n * d / sec / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(sec * 1e3, 3), "higher_is_better": True, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"configs[{a.config - 1}] with d={d}: n={n} f={f} {a.input_dtype}, mode={a.mode}, host-resident, "
+                               f"chunks of {a.host_resident} coordinates"},
+        "pcie_bytes_per_step": int(2 * eb * n * d + 4 * d),
+        "pcie_GBps": round((2 * eb * n * d + 4 * d) / sec / 1e9, 2)}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--sweep", action="store_true", help="run the paper's (n, d) sweep on U(0,1) inputs instead")
@@ -88,6 +117,10 @@ def main():
                     help="also run one plain device copy of this many MiB before the timed region "
                          "(a kernel of known traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--cpu-sample", type=int, default=1 << 28, help="coordinates the oracle is timed on")
+    ap.add_argument("--host-resident", type=int, default=0, metavar="CHUNK_D",
+                    help="time mbulyan_aggregate_host instead: the workload in pinned HOST memory, uploaded twice in "
+                         "column chunks of CHUNK_D coordinates (a PCIe-inclusive rate: a line of its own, never the "
+                         "headline value)")
     a = ap.parse_args()
     if a.sweep:
         return sweep()
@@ -115,6 +148,9 @@ def main():
     in16 = a.input_dtype in ("bf16", "fp16")
     dt16 = torch.bfloat16 if a.input_dtype == "bf16" else torch.float16
     eb = 2.0 if in16 else 4.0
+
+    if a.host_resident:
+        return host_resident(a, mb, W, n, f, d, mode, dt16 if in16 else torch.float32)
 
     # ---- inputs resident in HBM before the timed region ----------------------
     bounds = [d * k // nchunks for k in range(nchunks + 1)]
@@ -193,7 +229,7 @@ def main():
         kname = f"gram_dma_kernel<{nb}, {a.input_dtype} input>"
     roofline = {"kernel": kname, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get((a.config, {"f32": "gram_bf16", "bf16": "in16"}.get(a.input_dtype)))
+                "traffic": MEASURED_TRAFFIC_BYTES.get((a.config, a.input_dtype))
                 if (bf16 and a.d is None) else None,
                 "algorithmic_bytes": dist_bytes,
                 "avg_launch_ms": round(dist_avg_s * 1e3, 4), "launches": dist_launches}
