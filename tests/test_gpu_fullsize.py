@@ -80,6 +80,7 @@ def test_full_size_single_buffer(cfg, dtype):
     sq = np.array([float(np.dot(G[r, :1 << 20].astype(np.float64), G[r, :1 << 20])) for r in range(n)]) * (d / (1 << 20))
     assert np.all(np.abs(Dg - D) <= 1e-7 * (sq[:, None] + sq[None, :]))
     rel = np.abs(Dg - D)[D > 0] / D[D > 0]
+    rel_norms = float(np.max(np.abs(Dg - D) / (sq[:, None] + sq[None, :])))
     t0 = time.time()
     worst = 0.0
     step = 1 << 24
@@ -87,7 +88,7 @@ def test_full_size_single_buffer(cfg, dtype):
         hi = min(d, lo + step)
         ref, scale = O.coordwise_selected(G[:, lo:hi], ext, beta, want_scale=True)
         worst = max(worst, check_chunk(got[lo:hi], ref, scale))
-    say(f"cfg {cfg} {dtype}: selected {ext.tolist()}, score gap {gap:.2e}, dist rel err max {rel.max():.2e}, "
+    say(f"cfg {cfg} {dtype}: selected {ext.tolist()}, score gap {gap:.2e}, dist err max {rel.max():.2e} of D, {rel_norms:.2e} of the norms, "
         f"out worst err/tol {worst:.3g}, oracle coordinate phase {time.time() - t0:.1f} s")
 
 
