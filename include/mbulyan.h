@@ -29,7 +29,12 @@
  *   - Calls that share a workspace (or the internal one) must not overlap.
  *     Host threads may call concurrently with workspaces of their own; the
  *     internal workspace is one per device and is shared by every call that
- *     passes none.
+ *     passes none.  It is allocated by the first such call on a device and
+ *     reallocated when a later call needs more; such a call synchronises the
+ *     device and allocates (so it cannot be captured into a HIP graph, and it
+ *     is not "enqueue and return").  Callers who need neither pass a workspace
+ *     of mbulyan_workspace_bytes(n, d) bytes or call mbulyan_aggregate_noalloc.
+ *     mbulyan_aggregate_host is the one call that blocks by design.
  */
 #ifndef MBULYAN_H
 #define MBULYAN_H

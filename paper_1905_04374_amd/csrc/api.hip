@@ -38,7 +38,8 @@ constexpr size_t kOffM = kOffSel + 256;                          // 64 int32
 constexpr size_t kOffSets = kOffM + 256;                         // 64*64 bytes
 constexpr size_t kOffPlan = kOffSets + 4096;                     // plan of the Algorithm-1 coordinate pass
 constexpr size_t kPlanBytes = 18 * 1024;
-constexpr size_t kOffPartials = kOffPlan + kPlanBytes;
+constexpr size_t kOffPrepIdx = kOffPlan + kPlanBytes;            // 2 x 64*64 bytes: neighbour by rank, rank by neighbour
+constexpr size_t kOffPartials = kOffPrepIdx + 2 * 4096;
 static_assert(mb::kPlanWords * sizeof(int32_t) <= kPlanBytes, "plan segment");
 static_assert(MB_STORE_FP32 == mb::kStoreFp32 && MB_STORE_BF16 == mb::kStoreBf16 && MB_STORE_FP16 == mb::kStoreFp16,
               "the public storage codes are the kernels' own");
@@ -60,6 +61,10 @@ struct Workspace {
     int32_t *m() const { return reinterpret_cast<int32_t *>(base + kOffM); }
     uint8_t *sets() const { return reinterpret_cast<uint8_t *>(base + kOffSets); }
     int32_t *plan() const { return reinterpret_cast<int32_t *>(base + kOffPlan); }
+    // the rows of the distance matrix in ascending order, as the second distance pass leaves them for the
+    // selection when a single matrix is aggregated (the matrix itself is then never written: same segment)
+    double *prep_ordered() const { return dist(); }
+    unsigned char *prep_idx() const { return reinterpret_cast<unsigned char *>(base + kOffPrepIdx); }
     double *partials() const { return reinterpret_cast<double *>(base + kOffPartials); }
 };
 
@@ -195,15 +200,18 @@ int run_dist_gram(const void *grads, int in16, bool bf16, int n, int64_t d, int6
         const double *first = pass ? ws.reduced() : nullptr;
         double *second_sums = pass ? ws.reduced2() : nullptr;
         int *gate = pass ? ws.gate() : nullptr;
+        const bool prepare = pass && defer && !accumulate;   // the selection kernel will take it from here
+        double *prep_ordered = prepare ? ws.prep_ordered() : nullptr;
+        unsigned char *prep_idx = prepare ? ws.prep_idx() : nullptr;
         int nblocks = 0;
         {
             StageTimer t(pass ? MB_STAGE_REFINE : MB_STAGE_DIST, s);
             if (in16)
                 MB_HIP(mb::launch_dist_gram_in16(static_cast<const uint16_t *>(grads), in16, n, d, ld, ws.partials(), room,
-                                                 &nblocks, first, second_sums, gate, s));
+                                                 &nblocks, first, second_sums, gate, prep_ordered, prep_idx, s));
             else
                 MB_HIP(mb::launch_dist_gram(static_cast<const float *>(grads), n, d, ld, ws.partials(), bf16, room,
-                                            &nblocks, first, second_sums, gate, s));
+                                            &nblocks, first, second_sums, gate, prep_ordered, prep_idx, s));
         }
         if (pass == 0) {
             StageTimer t(MB_STAGE_REDUCE, s);
@@ -478,7 +486,8 @@ static int aggregate_on(const Workspace &ws, const float *grads, int n, int f, i
         uint8_t *sets = mode == MB_MODE_ALG1 ? ws.sets() : nullptr;
         int32_t *plan = mode == MB_MODE_ALG1 ? ws.plan() : nullptr;   // written by the selection as well
         if (deferred)
-            MB_HIP(mb::launch_select_gram(ws.reduced(), ws.reduced2(), ws.gate(), n, f, theta, sel, sets, ws.m(), plan, s));
+            MB_HIP(mb::launch_select_gram(ws.reduced(), ws.reduced2(), ws.gate(), n, f, theta, sel, sets, ws.m(), plan,
+                                          ws.prep_ordered(), ws.prep_idx(), s));
         else
             MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, sel, sets, ws.m(), nullptr, plan, s));
     }
@@ -576,7 +585,8 @@ int multikrum_aggregate(const float *grads, int n, int f, int64_t d, int64_t ld,
     {
         StageTimer t(MB_STAGE_SELECT, s);
         if (deferred)
-            MB_HIP(mb::launch_select_gram(ws.reduced(), ws.reduced2(), ws.gate(), n, f, 1, ws.sel(), mask, ws.m(), nullptr, s));
+            MB_HIP(mb::launch_select_gram(ws.reduced(), ws.reduced2(), ws.gate(), n, f, 1, ws.sel(), mask, ws.m(), nullptr,
+                                          ws.prep_ordered(), ws.prep_idx(), s));
         else
             MB_HIP(mb::launch_select(ws.dist(), n, f, 1, nullptr, ws.sel(), mask, ws.m(), nullptr, nullptr, s));
     }
@@ -645,7 +655,8 @@ static int multikrum_aggregate_16(const uint16_t *grads, int fmt, int n, int f, 
     {
         StageTimer t(MB_STAGE_SELECT, s);
         if (deferred)
-            MB_HIP(mb::launch_select_gram(ws.reduced(), ws.reduced2(), ws.gate(), n, f, 1, ws.sel(), mask, ws.m(), nullptr, s));
+            MB_HIP(mb::launch_select_gram(ws.reduced(), ws.reduced2(), ws.gate(), n, f, 1, ws.sel(), mask, ws.m(), nullptr,
+                                          ws.prep_ordered(), ws.prep_idx(), s));
         else
             MB_HIP(mb::launch_select(ws.dist(), n, f, 1, nullptr, ws.sel(), mask, ws.m(), nullptr, nullptr, s));
     }
@@ -691,7 +702,8 @@ static int mbulyan_aggregate_16(const uint16_t *grads, int fmt, int n, int f, in
         uint8_t *sets = mode == MB_MODE_ALG1 ? ws.sets() : nullptr;
         int32_t *plan = mode == MB_MODE_ALG1 ? ws.plan() : nullptr;   // written by the selection as well
         if (deferred)
-            MB_HIP(mb::launch_select_gram(ws.reduced(), ws.reduced2(), ws.gate(), n, f, theta, sel, sets, ws.m(), plan, s));
+            MB_HIP(mb::launch_select_gram(ws.reduced(), ws.reduced2(), ws.gate(), n, f, theta, sel, sets, ws.m(), plan,
+                                          ws.prep_ordered(), ws.prep_idx(), s));
         else
             MB_HIP(mb::launch_select(ws.dist(), n, f, theta, nullptr, sel, sets, ws.m(), nullptr, plan, s));
     }

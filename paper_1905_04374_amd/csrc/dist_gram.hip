@@ -242,6 +242,49 @@ __device__ __forceinline__ int gram_gate(const double *__restrict__ R1, int n, d
     return *pick;
 }
 
+// What a workgroup of the second pass does when the first pass needs no second one (so that the
+// launch is not wasted): workgroup i prepares row i (and i + the grid size, ..) of the distance matrix for the selection
+// kernel, which otherwise does this for all rows on one compute unit.  The row is formed exactly
+// as finalize_gram_kernel and select_kernel form it from the first pass's tiles (copies of a row
+// take the distances of the first of them, a NaN becomes +inf), then ordered by (distance, index)
+// without the row itself: ordered[i][r] = the r-th smallest distance, idx[i][r] = that neighbour,
+// idx[64*64 + 64 i + j] = the rank of neighbour j.  Every thread of the workgroup calls it;
+// `scratch`: 64 doubles and 64 ints of LDS.
+template <int NTHREADS>
+__device__ __forceinline__ void prepare_row(const double *__restrict__ R1, int n, int i, double *scratch,
+                                            double *__restrict__ ordered, unsigned char *__restrict__ idx, int tid)
+{
+    double *v = scratch;
+    int *rep = reinterpret_cast<int *>(scratch + kMaxN);
+    __syncthreads();                       // the scratch may still be read as the gate's
+    if (tid < kMaxN) rep[tid] = tid;
+    __syncthreads();
+    for (int e = tid; e < n * n; e += NTHREADS) {
+        const int a = e / n, b = e % n;
+        if (a > b && gram_term(R1, a, b).same) atomicMin(&rep[a], b);
+    }
+    __syncthreads();
+    const double inf = __builtin_huge_val();
+    if (tid < n) {
+        const int a = rep[i], b = rep[tid];
+        double x = 0.0;
+        if (a != b) x = gram_pair_distance(R1, nullptr, false, a > b ? a : b, a > b ? b : a);
+        v[tid] = (x == x) ? x : inf;
+    }
+    __syncthreads();
+    if (tid < n && tid != i) {
+        const double mine = v[tid];
+        int rank = 0;
+        for (int j = 0; j < n; ++j) {
+            const double u = v[j];
+            rank += (j != i && (u < mine || (u == mine && j < tid))) ? 1 : 0;
+        }
+        ordered[i * kMaxN + rank] = mine;
+        idx[i * kMaxN + rank] = (unsigned char)tid;
+        idx[kMaxN * kMaxN + i * kMaxN + tid] = (unsigned char)rank;
+    }
+}
+
 // Second pass only: the workgroup that finishes last adds up the tiles of all workgroups, in
 // workgroup order (a function of the data alone), and leaves the sums where the reduction kernel
 // would have put them, so that no reduction launch has to follow a pass that mostly does not run.
@@ -291,7 +334,9 @@ __global__ __launch_bounds__(kThreads) void gram_kernel(const float *__restrict_
                                                         int64_t ld, int aligned,
                                                         double *__restrict__ partials,
                                                         const double *__restrict__ first_pass,
-                                                        double *__restrict__ second_sums, int *__restrict__ gate)
+                                                        double *__restrict__ second_sums, int *__restrict__ gate,
+                                                        double *__restrict__ prep_ordered,
+                                                        unsigned char *__restrict__ prep_idx)
 {
     constexpr int NT = NB * (NB + 1) / 2;
     constexpr int NR = NB + (CENTER ? 1 : 0);   // row blocks a lane loads: with CENTER, the pivot row as one more
@@ -313,7 +358,13 @@ __global__ __launch_bounds__(kThreads) void gram_kernel(const float *__restrict_
             gate[kGateFlag] = pivot >= 0 ? 1 : 0;
             gate[kGatePivot] = pivot >= 0 ? pivot : 0;
         }
-        if (pivot < 0) return;     // the same in every thread of every workgroup
+        if (pivot < 0) {           // the same in every thread of every workgroup
+            if (prep_ordered)
+                for (int row = (int)blockIdx.x; row < n; row += (int)gridDim.x)   // one row each, as a rule
+                    prepare_row<kThreads>(first_pass, n, row, reinterpret_cast<double *>(&stage[0][0]), prep_ordered,
+                                          prep_idx, tid);
+            return;
+        }
         __syncthreads();           // the scratch becomes the staging area
     }
 
@@ -588,7 +639,8 @@ template <int KIND> constexpr int tile_cols() { return 512 / elem_bytes<KIND>();
 template <int NB, int KIND, int L, bool CENTER, int S>
 __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_kernel(
     const void *__restrict__ Gv, int n, int64_t d, int64_t ld, int64_t ntiles, double *__restrict__ partials,
-    const double *__restrict__ first_pass, double *__restrict__ second_sums, int *__restrict__ gate)
+    const double *__restrict__ first_pass, double *__restrict__ second_sums, int *__restrict__ gate,
+    double *__restrict__ prep_ordered, unsigned char *__restrict__ prep_idx)
 {
     constexpr int NT = NB * (NB + 1) / 2;
     constexpr int EB = elem_bytes<KIND>();
@@ -614,7 +666,13 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
             gate[kGateFlag] = pivot >= 0 ? 1 : 0;
             gate[kGatePivot] = pivot >= 0 ? pivot : 0;
         }
-        if (pivot < 0) return;     // the same in every thread of every workgroup
+        if (pivot < 0) {           // the same in every thread of every workgroup
+            if (prep_ordered)
+                for (int row = (int)blockIdx.x; row < n; row += (int)gridDim.x)   // one row each, as a rule
+                    prepare_row<kThreads>(first_pass, n, row, reinterpret_cast<double *>(lds), prep_ordered, prep_idx,
+                                          tid);
+            return;
+        }
         __syncthreads();           // the scratch becomes the tile buffers
     }
 
@@ -858,6 +916,8 @@ struct SecondPass {
     const double *first_pass;
     double *sums;   // where its reduced tiles go
     int *gate;
+    double *prep_ordered;      // may be null: rows prepared for the selection when the pass has nothing to do
+    unsigned char *prep_idx;
 };
 
 template <int NB, int KIND, int L, bool CENTER, int S>
@@ -904,7 +964,8 @@ hipError_t launch_dma_s(const void *G, int n, int64_t d, int64_t ld, bool aligne
     *nblocks = (int)g;
     gram_dma_kernel<NB, KIND, L, CENTER, S><<<dim3((unsigned)g), dim3(kThreads), bytes, s>>>(
         G, n, d, ld, tiles, partials, second ? second->first_pass : nullptr, second ? second->sums : nullptr,
-        second ? second->gate : nullptr);
+        second ? second->gate : nullptr, second ? second->prep_ordered : nullptr,
+        second ? second->prep_idx : nullptr);
     return hipGetLastError();
 }
 
@@ -941,7 +1002,8 @@ hipError_t launch_one(const float *G, int n, int64_t d, int64_t ld, double *part
     const int aligned = ((uintptr_t)G % 16 == 0) && (ld % 4 == 0);
     gram_kernel<NB, BF16, DEPTH, CENTER><<<dim3(nblocks), dim3(kThreads), 0, s>>>(
         G, n, d, ld, aligned, partials, second ? second->first_pass : nullptr, second ? second->sums : nullptr,
-        second ? second->gate : nullptr);
+        second ? second->gate : nullptr, second ? second->prep_ordered : nullptr,
+        second ? second->prep_idx : nullptr);
     return hipGetLastError();
 }
 
@@ -997,11 +1059,11 @@ hipError_t launch_nb(const float *G, int n, int64_t d, int64_t ld, double *parti
 
 hipError_t launch_dist_gram_in16(const uint16_t *G, int fmt, int n, int64_t d, int64_t ld, double *partials,
                                  int max_blocks, int *nblocks, const double *first_pass, double *second_sums,
-                                 int *gate, hipStream_t s)
+                                 int *gate, double *prep_ordered, unsigned char *prep_idx, hipStream_t s)
 {
     if (max_blocks < 1 || (fmt != kStoreBf16 && fmt != kStoreFp16)) return hipErrorInvalidValue;
     if (max_blocks > kGramMaxBlocks) max_blocks = kGramMaxBlocks;
-    const SecondPass sp{first_pass, second_sums, gate}, *second = first_pass ? &sp : nullptr;
+    const SecondPass sp{first_pass, second_sums, gate, prep_ordered, prep_idx}, *second = first_pass ? &sp : nullptr;
     const bool aligned = ((uintptr_t)G % 16 == 0) && (ld % 8 == 0) && d >= tile_cols<kIn16>();
 #define MB_NB(K)                                                                                                 \
     switch (gram_blocks(n)) {                                                                                    \
@@ -1021,11 +1083,11 @@ hipError_t launch_dist_gram_in16(const uint16_t *G, int fmt, int n, int64_t d, i
 
 hipError_t launch_dist_gram(const float *G, int n, int64_t d, int64_t ld, double *partials, bool bf16,
                             int max_blocks, int *nblocks, const double *first_pass, double *second_sums, int *gate,
-                            hipStream_t s)
+                            double *prep_ordered, unsigned char *prep_idx, hipStream_t s)
 {
     if (max_blocks < 1) return hipErrorInvalidValue;
     if (max_blocks > kGramMaxBlocks) max_blocks = kGramMaxBlocks;
-    const SecondPass sp{first_pass, second_sums, gate}, *second = first_pass ? &sp : nullptr;
+    const SecondPass sp{first_pass, second_sums, gate, prep_ordered, prep_idx}, *second = first_pass ? &sp : nullptr;
     const int nb = gram_blocks(n);
     if (bf16) {
         switch (nb) {

@@ -43,13 +43,16 @@ hipError_t launch_dist_direct(const float *G, int n, int64_t d, int64_t ld, doub
 // the Gram tiles of the rows minus the pivot row: partial tiles into `partials`, and the workgroup
 // that finishes last adds them up into second_sums (so no reduction launch follows this pass).
 // gate[kGateTicket] must be 0 when the second pass starts: launch_reduce of the first pass sees to it.
+// prep_ordered, prep_idx (second pass only, may be null): when the pass finds that it is not needed,
+// its first n workgroups leave the rows of the distance matrix ordered for the selection kernel
+// (64 x 64 doubles; 2 x 64 x 64 bytes: neighbour by rank, then rank by neighbour) - see launch_select_gram.
 hipError_t launch_dist_gram(const float *G, int n, int64_t d, int64_t ld, double *partials, bool bf16,
                             int max_blocks, int *nblocks, const double *first_pass, double *second_sums, int *gate,
-                            hipStream_t s);
+                            double *prep_ordered, unsigned char *prep_idx, hipStream_t s);
 // the same for gradients stored as 16-bit words (fmt = kStoreBf16 / kStoreFp16, ld in elements)
 hipError_t launch_dist_gram_in16(const uint16_t *G, int fmt, int n, int64_t d, int64_t ld, double *partials,
                                  int max_blocks, int *nblocks, const double *first_pass, double *second_sums,
-                                 int *gate, hipStream_t s);
+                                 int *gate, double *prep_ordered, unsigned char *prep_idx, hipStream_t s);
 // partials[nblocks][stride] -> reduced[0..slots) (fixed summation order).  ticket (may be null): a
 // word the kernel sets to 0 (the ticket counter of the second pass that follows).
 hipError_t launch_reduce(const double *partials, int nblocks, int stride, int slots, double *reduced,
@@ -70,9 +73,12 @@ hipError_t launch_select(const double *dist, int n, int f, int rounds, const uin
                          hipStream_t s);
 // The same starting from the reduced Gram tiles of the distance pass: the kernel forms the distance
 // matrix itself (what launch_finalize_gram would write from the same arguments) and saves that launch.
+// prep_ordered, prep_idx (may be null): what the second pass was given under these names; used when
+// gate[kGateFlag] is 0 (then the second pass has filled them and the kernel skips forming and
+// ordering the matrix).
 hipError_t launch_select_gram(const double *reduced, const double *reduced2, const int *gate, int n, int f,
                               int rounds, int32_t *sel, uint8_t *agr_sets, int32_t *m_out, int32_t *plan,
-                              hipStream_t s);
+                              const double *prep_ordered, const unsigned char *prep_idx, hipStream_t s);
 
 // out[c] = mean over rows r with mask[r] of G[r][c]
 hipError_t launch_masked_mean(const float *G, int n, int64_t d, int64_t ld, const uint8_t *mask,

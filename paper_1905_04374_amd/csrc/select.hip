@@ -4,9 +4,10 @@
 // O(theta n^2) scalar work on an n x n matrix, n <= 64: one workgroup.
 // Eight waves first order every row of the distance matrix once (rank by
 // counting, keys (distance, index)); then a single wave, lane i = gradient i,
-// plays the rounds with its ordered row held in registers and a bit mask of the
-// ranks still active: add the q nearest distances in ascending order in fp64,
-// find the smallest (score, index) by a wave reduction, extract it.  When the
+// plays the rounds with a bit mask of the ranks of its ordered row that are still
+// active: the first score is the sum of the q nearest distances in ascending order
+// in fp64, later ones follow by one subtraction per round; find the smallest
+// (score, index) by a wave reduction, extract it.  When the
 // averaged sets are wanted every score has to be ranked in every round: the
 // scores go through LDS and all eight waves count, each over an eighth of the
 // gradients.
@@ -86,20 +87,34 @@ __device__ __forceinline__ void help_rounds(const Rounds &a, int wave, int i)
     }
 }
 
-// One wave, lane i = gradient i, ordered row in NV >= n - 1 registers.
+// Sum of the distances of one ordered row at the ranks set in `take`, added in ascending order.
+__device__ __forceinline__ double sum_taken(const double *rowD, unsigned long long take)
+{
+    double S = 0.0;
+    while (take) {
+        const int r = (int)__builtin_ctzll(take);
+        take &= take - 1ull;
+        S += rowD[r];
+    }
+    return S;
+}
+
+// One wave, lane i = gradient i, its ordered row in LDS.
 // `near`: bit r set while the r-th nearest neighbour of i is still active.
 // `take`: the q lowest set bits of `near`, the neighbours whose distances make up the score.
 // From one round to the next q drops by one and at most one neighbour leaves, so `take` loses
-// either the bit of the extracted gradient or its own top bit: no search after the first round.
-template <int NV>
+// either the bit of the extracted gradient or its own top bit: no search after the first round,
+// and the score follows by one subtraction.  The first round's scores are the plain sums in
+// ascending order.  Later ones carry the rounding of the subtractions (a few 1e-16 of the score),
+// except where exact ties live: a score of one distance (two gradients that are each other's last
+// neighbour hold the same one) is that distance, and copies of a gradient go through identical
+// operations on identical values.  A row with infinite distances is summed afresh (no inf - inf).
 __device__ __forceinline__ void play_rounds(const Rounds &a, int i)
 {
     const int n = a.n, f = a.f;
     const double inf = __builtin_huge_val();
     const int row = i < n ? i : 0;
-    double v[NV];
-#pragma unroll
-    for (int r = 0; r < NV; ++r) v[r] = (r < n - 1) ? a.sD[row * kMaxN + r] : 0.0;
+    const double *rowD = a.sD + row * kMaxN;
 
     unsigned long long act = 0;   // active gradients, same value in every lane
     for (int j = 0; j < n; ++j)
@@ -128,20 +143,22 @@ __device__ __forceinline__ void play_rounds(const Rounds &a, int i)
         }
         take = near & (lo >= 64 ? ~0ull : ((1ull << lo) - 1ull));
     }
+    double sum = 0.0;   // over `take`, ascending; eight reads in flight
+    for (int r0 = 0; r0 < n - 1; r0 += 8) {
+        double u[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) u[q] = rowD[(r0 + q) & (kMaxN - 1)];
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            if ((take >> (r0 + q)) & 1ull) sum += u[q];
+    }
 
     for (int t = 0; t < a.rounds; ++t) {
         const int k = __popcll(act);
         int q = k - f - 2;
         q = q < 0 ? 0 : q;
         const bool mine = i < n && ((act >> i) & 1ull);
-        const unsigned tlo = (unsigned)take, thi = (unsigned)(take >> 32);
-        double S = 0.0;   // added in ascending order of distance
-#pragma unroll
-        for (int r = 0; r < NV; ++r) {
-            const bool in = r < 32 ? (tlo & (1u << (r & 31))) != 0 : (thi & (1u << (r & 31))) != 0;
-            S += in ? v[r] : 0.0;
-        }
-        if (!mine) S = inf;
+        const double S = mine ? sum : inf;
         if (t == 0 && a.scores_out && i < n) a.scores_out[i] = S;
 
         int w;            // the first of the active gradients in the order (score, index)
@@ -181,8 +198,11 @@ __device__ __forceinline__ void play_rounds(const Rounds &a, int i)
             int qn = k - 1 - f - 2;
             qn = qn < 0 ? 0 : qn;
             if (qn < q && take) {
-                if (take & wbit) take &= ~wbit;
-                else take &= ~(1ull << (63 - __builtin_clzll(take)));
+                const int gone = (take & wbit) ? rw : 63 - (int)__builtin_clzll(take);
+                take &= ~(1ull << gone);
+                const double x = rowD[gone];
+                if ((take & (take - 1ull)) == 0ull || !(x < inf)) sum = sum_taken(rowD, take);
+                else sum -= x;
             }
         }
     }
@@ -197,7 +217,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const double *__restrict__ dist, const double *__restrict__ gram, const double *__restrict__ gram2,
     const int *__restrict__ gate, int n, int f, int rounds,
     const uint8_t *__restrict__ active_in, int32_t *__restrict__ sel, uint8_t *__restrict__ agr_sets,
-    int32_t *__restrict__ m_out, double *__restrict__ scores_out, int32_t *__restrict__ plan)
+    int32_t *__restrict__ m_out, double *__restrict__ scores_out, int32_t *__restrict__ plan,
+    const double *__restrict__ prep_ordered, const unsigned char *__restrict__ prep_idx)
 {
     __shared__ double sD[kMaxN * kMaxN];        // first dist[i][j], then row i in ascending order
     __shared__ unsigned char sJ[kMaxN * kMaxN]; // neighbour index by rank within row i
@@ -210,7 +231,28 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
     const int tid = threadIdx.x;
     const double inf = __builtin_huge_val();
 
-    if (dist) {
+    // the ordered rows as the second distance pass has left them (it had nothing else to do)
+    const bool prepared = !dist && prep_ordered && gate && gate[kGateFlag] == 0;
+    if (prepared) {
+        double x[kPerThread];
+        unsigned char bj[kPerThread], br[kPerThread];
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) {
+            const int e = tid + k * kSelThreads;         // entry (row e / 64, column e % 64) of the padded arrays
+            const bool in = (e >> 6) < n && (e & 63) < n;
+            x[k] = in ? prep_ordered[e] : 0.0;
+            bj[k] = in ? prep_idx[e] : 0;
+            br[k] = in ? prep_idx[kMaxN * kMaxN + e] : 0;
+        }
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) {
+            const int e = tid + k * kSelThreads;
+            sD[e] = x[k];
+            sJ[e] = bj[k];
+            sR[e] = br[k];
+        }
+        __syncthreads();
+    } else if (dist) {
         double x[kPerThread];
 #pragma unroll
         for (int k = 0; k < kPerThread; ++k) {
@@ -263,59 +305,55 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
         __syncthreads();
     }
 
-    // rank of j among the neighbours of i (everything but i itself), keys (distance, index)
-    double myv[kPerThread];
-    int myrank[kPerThread];
-#pragma unroll
-    for (int k = 0; k < kPerThread; ++k) {
-        const int e = tid + k * kSelThreads;
-        myrank[k] = -1;
-        myv[k] = 0.0;
-        if (e < n * n) {
-            const int i = e / n, j = e % n;
-            if (i != j) {
-                const double v = sD[i * kMaxN + j];
-                int rank = 0;
-                // one wave per SIMD, nothing else hides the LDS latency: eight reads in flight
-                // (entries past n in the padded row are never counted)
-                for (int j0 = 0; j0 < n; j0 += 8) {
-                    double u[8];
-#pragma unroll
-                    for (int q = 0; q < 8; ++q) u[q] = sD[i * kMaxN + ((j0 + q) & (kMaxN - 1))];
-#pragma unroll
-                    for (int q = 0; q < 8; ++q) {
-                        const int jj = j0 + q;
-                        rank += (jj < n && jj != i && (u[q] < v || (u[q] == v && jj < j))) ? 1 : 0;
+    if (!prepared) {
+        // rank of j among the neighbours of i (everything but i itself), keys (distance, index)
+        double myv[kPerThread];
+        int myrank[kPerThread];
+    #pragma unroll
+        for (int k = 0; k < kPerThread; ++k) {
+            const int e = tid + k * kSelThreads;
+            myrank[k] = -1;
+            myv[k] = 0.0;
+            if (e < n * n) {
+                const int i = e / n, j = e % n;
+                if (i != j) {
+                    const double v = sD[i * kMaxN + j];
+                    int rank = 0;
+                    // one wave per SIMD, nothing else hides the LDS latency: eight reads in flight
+                    // (entries past n in the padded row are never counted)
+                    for (int j0 = 0; j0 < n; j0 += 8) {
+                        double u[8];
+    #pragma unroll
+                        for (int q = 0; q < 8; ++q) u[q] = sD[i * kMaxN + ((j0 + q) & (kMaxN - 1))];
+    #pragma unroll
+                        for (int q = 0; q < 8; ++q) {
+                            const int jj = j0 + q;
+                            rank += (jj < n && jj != i && (u[q] < v || (u[q] == v && jj < j))) ? 1 : 0;
+                        }
                     }
+                    myrank[k] = rank;
+                    myv[k] = v;
                 }
-                myrank[k] = rank;
-                myv[k] = v;
             }
         }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < kPerThread; ++k) {
-        const int e = tid + k * kSelThreads;
-        if (myrank[k] >= 0) {
-            const int i = e / n, j = e % n;
-            sD[i * kMaxN + myrank[k]] = myv[k];
-            sJ[i * kMaxN + myrank[k]] = (unsigned char)j;
-            sR[i * kMaxN + j] = (unsigned char)myrank[k];
+        __syncthreads();
+    #pragma unroll
+        for (int k = 0; k < kPerThread; ++k) {
+            const int e = tid + k * kSelThreads;
+            if (myrank[k] >= 0) {
+                const int i = e / n, j = e % n;
+                sD[i * kMaxN + myrank[k]] = myv[k];
+                sJ[i * kMaxN + myrank[k]] = (unsigned char)j;
+                sR[i * kMaxN + j] = (unsigned char)myrank[k];
+            }
         }
+        __syncthreads();
     }
-    __syncthreads();
     const Rounds rd{sD, sJ, sR, n, f, rounds, active_in, sel, agr_sets, m_out, scores_out, sS, &sAct, sCnt};
     if (tid >= 64) {   // one wave plays the rounds; the others only help to rank the scores for the sets
         if (agr_sets) help_rounds(rd, tid >> 6, tid & 63);
-    } else if (n <= 16) {
-        play_rounds<15>(rd, tid);
-    } else if (n <= 32) {
-        play_rounds<31>(rd, tid);
-    } else if (n <= 48) {
-        play_rounds<47>(rd, tid);
     } else {
-        play_rounds<63>(rd, tid);
+        play_rounds(rd, tid);
     }
     if (!plan) return;
     __syncthreads();   // sel and agr_sets as the first wave has written them
@@ -330,17 +368,17 @@ hipError_t launch_select(const double *dist, int n, int f, int rounds, const uin
 {
     if (plan && !(sel && agr_sets)) return hipErrorInvalidValue;
     select_kernel<<<dim3(1), dim3(kSelThreads), 0, s>>>(dist, nullptr, nullptr, nullptr, n, f, rounds, active_in, sel,
-                                                        agr_sets, m_out, scores_out, plan);
+                                                        agr_sets, m_out, scores_out, plan, nullptr, nullptr);
     return hipGetLastError();
 }
 
 hipError_t launch_select_gram(const double *reduced, const double *reduced2, const int *gate, int n, int f,
                               int rounds, int32_t *sel, uint8_t *agr_sets, int32_t *m_out, int32_t *plan,
-                              hipStream_t s)
+                              const double *prep_ordered, const unsigned char *prep_idx, hipStream_t s)
 {
     if (plan && !(sel && agr_sets)) return hipErrorInvalidValue;
     select_kernel<<<dim3(1), dim3(kSelThreads), 0, s>>>(nullptr, reduced, reduced2, gate, n, f, rounds, nullptr, sel,
-                                                        agr_sets, m_out, nullptr, plan);
+                                                        agr_sets, m_out, nullptr, plan, prep_ordered, prep_idx);
     return hipGetLastError();
 }
 
