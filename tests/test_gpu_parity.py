@@ -182,6 +182,37 @@ def test_selection_handles_nan_distances():
     assert sel_g.cpu().numpy().tolist() == O.multikrum_select(Di, 2, 7)[0].tolist()
 
 
+@pytest.mark.parametrize("n,f,d", [(3, 0, 7), (4, 0, 130), (11, 2, 5), (39, 9, 700), (64, 15, 130), (64, 15, 5000),
+                                   (51, 12, 100_003), (27, 6, 65_536)])
+def test_selection_from_rows_ordered_by_the_distance_pass(n, f, d):
+    """A single-matrix aggregation lets the second distance pass order the rows of the distance matrix (one
+    workgroup per row; several rows per workgroup when the launch has fewer workgroups than n, as for the
+    short rows here) and the selection kernel start from them; the step entry points form and order the
+    matrix inside the selection kernel.  Both ways give the same lists, with copies and a non-finite row in."""
+    say("prepared rows", n, f, d)
+    rng = np.random.default_rng(1000 * n + d)
+    G = rng.standard_normal((n, d)).astype(np.float32)
+    if n >= 11:
+        G[n - 1] = G[n - 3]                    # copies: exact ties between scores
+        G[n - 2] = G[n - 3]
+        G[5, d // 2] = np.nan                  # a row at distance +inf from every other
+    Gt = gpu(G)
+    D = mb.pairwise_sqdist(Gt)
+    for mode in (mb.MODE_SELECTED, mb.MODE_ALG1):
+        theta, beta = mb.mbulyan_params(n, f, mode)
+        if theta < 1 or beta < 1:
+            continue
+        out, sel = mb.mbulyan_aggregate_ex(Gt, f, mode=mode)
+        sel2, sets2, _ = mb.multikrum_select(D, f, theta)
+        assert sel.cpu().numpy().tolist() == sel2.cpu().numpy().tolist(), mode
+        out2 = mb.coordwise_trimmed_avg(Gt, sel2, beta, agr_sets=sets2 if mode == mb.MODE_ALG1 else None)
+        assert torch.equal(out, out2) or np.array_equal(out.cpu().numpy(), out2.cpu().numpy(), equal_nan=True)
+    if n >= 2 * f + 3:
+        _, mask = mb.multikrum_aggregate(Gt, f)
+        _, sets1, _ = mb.multikrum_select(D, f, 1)
+        assert np.array_equal(mask.cpu().numpy(), sets1.cpu().numpy()[0])
+
+
 # ----------------------------------------------------------- coordinate pass
 @pytest.mark.parametrize("theta,beta,d", [
     (1, 1, 100), (2, 1, 1000), (2, 2, 1000), (3, 1, 1000), (3, 3, 1024), (4, 2, 4097), (5, 3, 999),
