@@ -124,12 +124,27 @@ __global__ __launch_bounds__(256) void coord_selected_kernel(
     if constexpr (FMT != kStoreFp32) {
         static_assert(VEC <= 2, "16-bit input: one or two coordinates per lane");
         if (VEC == 2 && full) {
+            // one word holds the lane's two coordinates: they are sorted side by side, as two 16-bit
+            // keys per register (half the comparator instructions), and only what the window around
+            // the median needs is widened afterwards
+            typedef Sortable16<FMT> Key;
+            typename Key::type k[THETA];
 #pragma unroll
-            for (int t = 0; t < THETA; ++t) {
-                const unsigned x = __builtin_nontemporal_load(reinterpret_cast<const unsigned *>(G16 + roff[t] + c0));
-                v[0][t] = widen16<FMT>(x, false);
-                v[1 % VEC][t] = widen16<FMT>(x, true);
+            for (int t = 0; t < THETA; ++t)
+                k[t] = Key::from_word(__builtin_nontemporal_load(reinterpret_cast<const unsigned *>(G16 + roff[t] + c0)));
+            sort_registers<THETA>(k);
+            float res2[2];
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                float w[THETA];
+#pragma unroll
+                for (int t = 0; t < THETA; ++t) w[t] = widen16<FMT>(Key::to_word(k[t]), e == 1);
+                res2[e] = closest_sum<THETA, WIN>(w, K, median_only != 0) * scale;
+                if (bad) res2[e] = __int_as_float(0x7fc00000);
             }
+            const floatx2 o = {res2[0], res2[1]};
+            __builtin_nontemporal_store(o, reinterpret_cast<floatx2 *>(out + c0));
+            return;
         } else {
 #pragma unroll
             for (int t = 0; t < THETA; ++t)

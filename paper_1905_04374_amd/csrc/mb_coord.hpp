@@ -26,6 +26,30 @@ __device__ __forceinline__ float widen16(unsigned w, bool hi)
     }
 }
 
+// A word of two 16-bit values as two keys that sort like the values, and back.  fp16: the values
+// themselves (packed half min / max).  bf16 has no packed min / max: sign-magnitude bits become
+// two's-complement integers of the same order (negative values get their magnitude bits inverted);
+// the map is its own inverse.  (-0 sorts before +0: equal values either way.)
+template <int FMT>
+struct Sortable16;
+template <>
+struct Sortable16<kStoreFp16> {
+    typedef _Float16 type __attribute__((ext_vector_type(2)));
+    static __device__ __forceinline__ type from_word(unsigned w) { return __builtin_bit_cast(type, w); }
+    static __device__ __forceinline__ unsigned to_word(type k) { return __builtin_bit_cast(unsigned, k); }
+};
+template <>
+struct Sortable16<kStoreBf16> {
+    typedef short type __attribute__((ext_vector_type(2)));
+    static __device__ __forceinline__ type flip(type x)
+    {
+        const type mask = {0x7fff, 0x7fff};
+        return x ^ ((x >> 15) & mask);
+    }
+    static __device__ __forceinline__ type from_word(unsigned w) { return flip(__builtin_bit_cast(type, w)); }
+    static __device__ __forceinline__ unsigned to_word(type k) { return __builtin_bit_cast(unsigned, flip(k)); }
+};
+
 // ---- coordinate pass -----------------------------------------------------
 struct CoordArgs {
     const void *G;       // fp32, or raw 16-bit words when in16 is kStoreBf16 / kStoreFp16
