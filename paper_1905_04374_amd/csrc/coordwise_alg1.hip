@@ -54,6 +54,20 @@ struct RawOps<floatx2> {   // fp32 gradients
     }
     static __device__ __forceinline__ floatx2 zero() { return floatx2{0.0f, 0.0f}; }
     static __device__ __forceinline__ float widen(floatx2 r, int k) { return r[k]; }
+    // median of coordinate k of the THETA rows, k < VEC
+    template <int THETA, int VEC>
+    static __device__ __forceinline__ void medians(const floatx2 (&r)[THETA], float (&med)[VEC])
+    {
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            float es[THETA];
+#pragma unroll
+            for (int t = 0; t < THETA; ++t) es[t] = r[t][k];
+            sort_registers<THETA>(es);
+            if constexpr (THETA & 1) med[k] = es[THETA / 2];
+            else med[k] = 0.5f * (es[THETA / 2 - 1] + es[THETA / 2]);
+        }
+    }
 };
 
 template <>
@@ -70,12 +84,33 @@ struct RawOps<unsigned> {   // 16-bit gradients: one word holds both
     {
         return widen16<(MB_IN16 == 2 ? kStoreFp16 : kStoreBf16)>(r, k != 0);
     }
+    // the same, both coordinates of the words at once: sorted as two 16-bit keys per register
+    // (half the comparator instructions), only the middle widened
+    template <int THETA, int VEC>
+    static __device__ __forceinline__ void medians(const unsigned (&r)[THETA], float (&med)[VEC])
+    {
+        typedef Sortable16<(MB_IN16 == 2 ? kStoreFp16 : kStoreBf16)> Key;
+        typename Key::type ks[THETA];
+#pragma unroll
+        for (int t = 0; t < THETA; ++t) ks[t] = Key::from_word(r[t]);
+        sort_registers<THETA>(ks);
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            if constexpr (THETA & 1) med[k] = widen(Key::to_word(ks[THETA / 2]), k);
+            else med[k] = 0.5f * (widen(Key::to_word(ks[THETA / 2 - 1]), k) + widen(Key::to_word(ks[THETA / 2]), k));
+        }
+    }
 };
 
 typedef typename std::conditional<kIn16, unsigned, floatx2>::type Raw;
 __device__ __forceinline__ Raw load_raw(const Elem *p, bool pair, bool two) { return RawOps<Raw>::load(p, pair, two); }
 __device__ __forceinline__ Raw raw_zero() { return RawOps<Raw>::zero(); }
 __device__ __forceinline__ float widen(Raw r, int k) { return RawOps<Raw>::widen(r, k); }   // coordinate k as fp32
+template <int THETA, int VEC>
+__device__ __forceinline__ void medians(const Raw (&r)[THETA], float (&med)[VEC])
+{
+    RawOps<Raw>::template medians<THETA, VEC>(r, med);
+}
 
 // average of the beta values a[.] closest to med (closeness |a - med| in fp32, ties to the smaller value)
 template <int THETA>
@@ -218,18 +253,13 @@ __global__ __launch_bounds__(kThreads) void coord_alg1_kernel(const Elem *__rest
     // more rows than that (only with a theta below the default or a membership matrix of one's own)
     more_slots<THETA + kBatch, VEC>(U, load, apply);
 
-    float res[VEC];
+    float res[VEC], meds[VEC];
+    medians<THETA, VEC>(er, meds);   // of the winners' values (Algorithm 1: the median of G^ext)
 #pragma unroll
     for (int k = 0; k < VEC; ++k) {
         float S = 0.0f;
+        const float med = meds[k];
         if constexpr (B1) {
-            float es[THETA];
-#pragma unroll
-            for (int t = 0; t < THETA; ++t) es[t] = e[k][t];
-            sort_registers<THETA>(es);
-            float med;
-            if constexpr (THETA & 1) med = es[THETA / 2];
-            else med = 0.5f * (es[THETA / 2 - 1] + es[THETA / 2]);
             float best = 0.0f, bd = __builtin_huge_valf();
 #pragma unroll
             for (int t = 0; t < THETA; ++t) {
@@ -248,10 +278,6 @@ __global__ __launch_bounds__(kThreads) void coord_alg1_kernel(const Elem *__rest
                 S += P[k][t];
                 a[t] = S * inv_m[t];
             }
-            sort_registers<THETA>(e[k]);
-            float med;
-            if constexpr (THETA & 1) med = e[k][THETA / 2];
-            else med = 0.5f * (e[k][THETA / 2 - 1] + e[k][THETA / 2]);
             res[k] = pick_closest<THETA>(a, med, beta);
         }
     }
@@ -312,16 +338,11 @@ __global__ __launch_bounds__(kThreads) void coord_alg1_nested_kernel(
 #pragma unroll
             for (int k = 0; k < VEC; ++k) S[k] += widen(xr[j], k);
     }
-    float res[VEC];
+    float res[VEC], meds[VEC];
+    medians<THETA, VEC>(er, meds);
 #pragma unroll
     for (int k = 0; k < VEC; ++k) {
-        float es[THETA];
-#pragma unroll
-        for (int t = 0; t < THETA; ++t) es[t] = e[k][t];
-        sort_registers<THETA>(es);
-        float med;
-        if constexpr (THETA & 1) med = es[THETA / 2];
-        else med = 0.5f * (es[THETA / 2 - 1] + es[THETA / 2]);
+        const float med = meds[k];
         float best = 0.0f, bd = __builtin_huge_valf();
 #pragma unroll
         for (int t = THETA - 1; t >= 0; --t) {
