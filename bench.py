@@ -18,7 +18,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch of the distance kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
 # scaled by what the same counter reads for a 4 GiB device copy (FETCH_SIZE reads half the bytes
 # of the copy, WRITE_SIZE all of them); see profiles/gram_dma_kernel_cfg4_n39_d250M_hbm_traffic.md
-MEASURED_TRAFFIC_BYTES = {(4, "f32"): 2 * 19043030 * 1024 + 9216 * 1024,
+MEASURED_TRAFFIC_BYTES = {(4, "f32"): 2 * 19043016 * 1024 + 9216 * 1024,
                           (4, "bf16"): 2 * 9521538 * 1024 + 9216 * 1024,
                           (4, "fp16"): 2 * 9521540 * 1024 + 9216 * 1024,
                           (5, "f32"): 2 * 24924287 * 1024 + 10240 * 1024}
