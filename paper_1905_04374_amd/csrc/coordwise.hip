@@ -9,7 +9,8 @@
 // floats per coordinate and fits the register file for theta <= 64.
 //
 // This file is compiled once per group of 8 values of theta (-DMB_GROUP=g), and again with
-// -DMB_IN16=1 for gradients stored as bf16 and -DMB_IN16=2 for fp16.
+// -DMB_IN16=1 for gradients stored as bf16 and -DMB_IN16=2 for fp16; there a lane's two
+// coordinates arrive in one word and are sorted side by side as two 16-bit keys per register.
 #include <hip/hip_runtime.h>
 
 #include "mb_coord.hpp"
