@@ -127,20 +127,23 @@ __device__ __forceinline__ float pick_closest(float (&a)[THETA], float med, int 
         }
         return best;
     }
-    sort_registers<THETA>(a);
-    float dlt[THETA];
+    // ordered by (closeness, value): the first beta are the ones to average.  One 64-bit key per
+    // average: the bits of its (non-negative) closeness above an image of its own bits that orders
+    // like the values (sign bit flipped for positive values, all bits for negative ones).
+    unsigned long long key[THETA];
 #pragma unroll
-    for (int p = 0; p < THETA; ++p) dlt[p] = fabsf(a[p] - med);
+    for (int p = 0; p < THETA; ++p) {
+        const unsigned ua = __float_as_uint(a[p]);
+        const unsigned img = ua ^ ((unsigned)((int)ua >> 31) | 0x80000000u);
+        key[p] = ((unsigned long long)__float_as_uint(fabsf(a[p] - med)) << 32) | img;
+    }
+    sort_registers<THETA>(key);
     float sum = 0.0f;
 #pragma unroll
     for (int p = 0; p < THETA; ++p) {
-        int rank = 0;
-#pragma unroll
-        for (int o = 0; o < THETA; ++o) {
-            if (o < p) rank += (dlt[o] <= dlt[p]) ? 1 : 0;
-            if (o > p) rank += (dlt[o] < dlt[p]) ? 1 : 0;
-        }
-        sum += (rank < beta) ? a[p] : 0.0f;
+        const unsigned img = (unsigned)key[p];
+        const unsigned ua = img ^ ((img >> 31) ? 0x80000000u : 0xffffffffu);
+        sum += (p < beta) ? __uint_as_float(ua) : 0.0f;
     }
     return sum / (float)beta;
 }
