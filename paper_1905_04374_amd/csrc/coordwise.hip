@@ -66,23 +66,34 @@ __device__ __forceinline__ float closest_sum(const float (&v)[THETA], int K, boo
                 }
             }
         } else {
-            // Rank of every left candidate in the merged order, by counting.  The ranks are a
-            // permutation and both sides are sorted, so the K closest are the first `na` on the left
-            // and the first K - na on the right.
-            float dL[H], dR[H];
+            // How many of the K closest lie on the left.  Both sides are ordered by their distance to
+            // the median, so left candidate a is among the K closest iff fewer than K - a right ones
+            // are strictly closer, i.e. iff a < K and not dR[K-1-a] < dL[a] (a right candidate past
+            // the end counts as infinitely far).  K is the same for every lane: E[a] = dR[K-1-a] is
+            // the right-hand distances reversed and shifted by a uniform amount, done by a barrel
+            // shifter of log2(2H) stages of selects on a scalar condition - O(H log H) where
+            // counting over all pairs takes H^2.
+            constexpr int N2 = 2 * H;
+            constexpr int STAGES = N2 <= 2 ? 1 : N2 <= 4 ? 2 : N2 <= 8 ? 3 : N2 <= 16 ? 4 : N2 <= 32 ? 5 : N2 <= 64 ? 6 : 7;
+            float dL[H], Y[N2 + (1 << STAGES)];
 #pragma unroll
-            for (int a = 0; a < H; ++a) {
-                dL[a] = med - v[H - 1 - a];
-                dR[a] = v[H + (ODD ? 1 : 0) + a] - med;
+            for (int a = 0; a < H; ++a) dL[a] = med - v[H - 1 - a];
+            // Y[j] = X[2H-1-j], X[m] = dR[m] for m < H and +inf beyond; E[a] = X[K-1-a] = Y[a + (2H - K)]
+#pragma unroll
+            for (int j = 0; j < N2 + (1 << STAGES); ++j) {
+                const int m = N2 - 1 - j;
+                Y[j] = (m >= 0 && m < H) ? v[H + (ODD ? 1 : 0) + m] - med : kInf;
+            }
+            const int shift = N2 - K;            // 0 .. 2H, uniform
+#pragma unroll
+            for (int st = 0; st < STAGES; ++st) {
+                const bool on = ((shift >> st) & 1) != 0;
+#pragma unroll
+                for (int j = 0; j < N2; ++j) Y[j] = on ? Y[j + (1 << st)] : Y[j];
             }
             int na = 0;
 #pragma unroll
-            for (int a = 0; a < H; ++a) {
-                int rank = a;
-#pragma unroll
-                for (int b = 0; b < H; ++b) rank += (dR[b] < dL[a]) ? 1 : 0;
-                na += (rank < K) ? 1 : 0;
-            }
+            for (int a = 0; a < H; ++a) na += (a < K && !(Y[a] < dL[a])) ? 1 : 0;
             const int nb = K - na;
 #pragma unroll
             for (int a = 0; a < H; ++a) sum += (a < na) ? v[H - 1 - a] : 0.0f;
@@ -214,6 +225,9 @@ hipError_t launch_theta(const CoordArgs &a, hipStream_t s)
         const dim3 grid((unsigned)((a.d + 511) / 512));
         if (K <= 2 && H > 2)
             coord_selected_kernel<THETA, 2, 2, FMT><<<grid, block, 0, s>>>(a.G, a.n, a.d, a.ld, a.sel, K,
+                                                                            a.median_only, scale, a.out);
+        else if (K <= 4 && H > 4)   // beta = 4 or 5 (n = 4f + 4, 4f + 5): still a window of the network's middle
+            coord_selected_kernel<THETA, 2, 4, FMT><<<grid, block, 0, s>>>(a.G, a.n, a.d, a.ld, a.sel, K,
                                                                             a.median_only, scale, a.out);
         else
             coord_selected_kernel<THETA, 2, (H > 0 ? H : 1), FMT><<<grid, block, 0, s>>>(
