@@ -20,7 +20,7 @@
 //         coordinate take exactly as long as the 156 bytes take from HBM: on the ridge.
 //  bf16:  every fp32 value is split exactly into three bf16 pieces x = hi + mid + lo (8
 //         significand bits each, each the remainder so far rounded to nearest, so the
-//         remainders are exact).  A product x*y is the sum of nine piece products, each exact
+//         remainders are exact; seven vector instructions for two values).  A product x*y is the sum of nine piece products, each exact
 //         in fp32; the six largest (hi*hi, hi*mid, mid*hi, hi*lo, lo*hi, mid*mid) are
 //         accumulated, the dropped ones (mid*lo, lo*mid, lo*lo) are below 2^-26 of x*y each and
 //         of either sign from one coordinate to the next.  v_mfma_f32_16x16x32_bf16 consumes a whole step
@@ -64,32 +64,52 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b)
     return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
 }
 
+// x minus one half of a packed bf16 pair, in one instruction: v_dot2c_f32_bf16 adds the two
+// products of its bf16 pairs to x, and the second pair is (-1, 0) or (0, -1).  The result is exact
+// wherever the subtraction is (checked against it bit for bit on 2e9 random pairs, both levels of
+// the split).  The selecting pairs are handed over in scalar registers and kept opaque to the
+// compiler: written as immediates they would be encoded as inline constants, which this
+// instruction reads as fp32 words, i.e. with the -1 in the upper half either way.
+struct HalfSel {
+    unsigned lo, hi;   // selects the lower / the upper half of the pair
+};
+__device__ __forceinline__ HalfSel half_sel()
+{
+    unsigned lo = 0x0000bf80u, hi = 0xbf800000u;
+    asm volatile("" : "+s"(lo), "+s"(hi));
+    return HalfSel{lo, hi};
+}
+__device__ __forceinline__ float minus_half(float x, unsigned pair, unsigned sel)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pair), __builtin_bit_cast(bf16x2, sel), x, false);
+}
+
 // two floats -> one packed word of each piece.  Every piece is the remainder so far rounded to
 // nearest, so the remainders are exact, of either sign, and at most half an ulp of the piece
 // before: |mid| <= 2^-9 |x|, |lo| <= 2^-18 |x|, and lo has at most 7 significant bits left.
 // (Truncation would do as well for exactness, but its remainders all carry the sign of x: the
 // dropped products mid*lo then have the sign of x_i*x_j in every coordinate and add up to a
 // bias of about 6e-8 of |G_ij|, i.e. 1.2e-7 of the norms in the distance of two rows that point in
-// opposite directions.)
-__device__ __forceinline__ void split_pair(float a, float b, unsigned &hi, unsigned &mid, unsigned &lo)
+// opposite directions.)  Seven instructions for two values.
+__device__ __forceinline__ void split_pair(float a, float b, const HalfSel &hs, unsigned &hi, unsigned &mid,
+                                           unsigned &lo)
 {
-    constexpr unsigned kTop = 0xffff0000u;
     hi = pack_bf16(a, b);
-    const float ra = a - __uint_as_float(hi << 16);
-    const float rb = b - __uint_as_float(hi & kTop);
+    const float ra = minus_half(a, hi, hs.lo);
+    const float rb = minus_half(b, hi, hs.hi);
     mid = pack_bf16(ra, rb);
-    const float sa = ra - __uint_as_float(mid << 16);
-    const float sb = rb - __uint_as_float(mid & kTop);
+    const float sa = minus_half(ra, mid, hs.lo);
+    const float sb = minus_half(rb, mid, hs.hi);
     lo = pack_bf16(sa, sb);
 }
 
-__device__ __forceinline__ Pieces split8(const float4 &u, const float4 &w)
+__device__ __forceinline__ Pieces split8(const float4 &u, const float4 &w, const HalfSel &hs)
 {
     unsigned h[4], m[4], l[4];
-    split_pair(u.x, u.y, h[0], m[0], l[0]);
-    split_pair(u.z, u.w, h[1], m[1], l[1]);
-    split_pair(w.x, w.y, h[2], m[2], l[2]);
-    split_pair(w.z, w.w, h[3], m[3], l[3]);
+    split_pair(u.x, u.y, hs, h[0], m[0], l[0]);
+    split_pair(u.z, u.w, hs, h[1], m[1], l[1]);
+    split_pair(w.x, w.y, hs, h[2], m[2], l[2]);
+    split_pair(w.z, w.w, hs, h[3], m[3], l[3]);
     Pieces p;
     p.hi = uintx4{h[0], h[1], h[2], h[3]};
     p.mid = uintx4{m[0], m[1], m[2], m[3]};
@@ -344,6 +364,7 @@ __global__ __launch_bounds__(kThreads) void gram_kernel(const float *__restrict_
     static_assert(!CENTER || sizeof(stage) >= (16 * NB * (16 * NB + 1)) * sizeof(double) + 2 * sizeof(int),
                   "the gate's scratch fits the staging area");
     const int tid = threadIdx.x;
+    const HalfSel hs = half_sel();
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int r = lane & 15;   // row within a block of 16
@@ -420,7 +441,7 @@ __global__ __launch_bounds__(kThreads) void gram_kernel(const float *__restrict_
         if constexpr (BF16) {
             Pieces p[NB];
 #pragma unroll
-            for (int I = 0; I < NB; ++I) p[I] = split8(x[I].u, x[I].w);
+            for (int I = 0; I < NB; ++I) p[I] = split8(x[I].u, x[I].w, hs);
             tiles.mac_bf16(p);
         } else {
             tiles.mac_fp32(x);
@@ -651,6 +672,7 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
     extern __shared__ __attribute__((aligned(16))) float lds[];
     const char *G = static_cast<const char *>(Gv);
     const int tid = threadIdx.x;
+    const HalfSel hs = half_sel();
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int r = lane & 15;
@@ -746,7 +768,7 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
         if constexpr (KIND == kSplit) {
             Pieces p[NB];
 #pragma unroll
-            for (int I = 0; I < NB; ++I) p[I] = split8(x[I].u, x[I].w);
+            for (int I = 0; I < NB; ++I) p[I] = split8(x[I].u, x[I].w, hs);
             tiles.mac_bf16(p);
         } else if constexpr (KIND == kIn16) {
             tiles.mac_in16(x);
@@ -768,13 +790,13 @@ __global__ __launch_bounds__(kThreads, DmaShape<NB>::min_blocks) void gram_dma_k
 #pragma unroll
             for (int I = 0; I < NB; ++I) {
                 const Raw y = raw_minus(widen8<FMT>(x[I].u), p0);
-                p[I] = split8(y.u, y.w);
+                p[I] = split8(y.u, y.w, hs);
             }
             tiles.mac_bf16(p);
 #pragma unroll
             for (int I = 0; I < NB; ++I) {
                 const Raw y = raw_minus(widen8<FMT>(x[I].w), p1);
-                p[I] = split8(y.u, y.w);
+                p[I] = split8(y.u, y.w, hs);
             }
             tiles.mac_bf16(p);
         } else {
