@@ -112,6 +112,21 @@ __device__ __forceinline__ void medians(const Raw (&r)[THETA], float (&med)[VEC]
     RawOps<Raw>::template medians<THETA, VEC>(r, med);
 }
 
+// One 64-bit key per average, ordered like (closeness to the median, value): the bits of the
+// (non-negative) closeness above an image of the value's own bits that orders like the values
+// (sign bit flipped for positive values, all bits for negative ones).
+__device__ __forceinline__ unsigned long long closeness_key(float a, float med)
+{
+    const unsigned ua = __float_as_uint(a);
+    const unsigned img = ua ^ ((unsigned)((int)ua >> 31) | 0x80000000u);
+    return ((unsigned long long)__float_as_uint(fabsf(a - med)) << 32) | img;
+}
+__device__ __forceinline__ float key_value(unsigned long long key)
+{
+    const unsigned img = (unsigned)key;
+    return __uint_as_float(img ^ ((img >> 31) ? 0x80000000u : 0xffffffffu));
+}
+
 // average of the beta values a[.] closest to med (closeness |a - med| in fp32, ties to the smaller value)
 template <int THETA>
 __device__ __forceinline__ float pick_closest(float (&a)[THETA], float med, int beta)
@@ -127,24 +142,14 @@ __device__ __forceinline__ float pick_closest(float (&a)[THETA], float med, int 
         }
         return best;
     }
-    // ordered by (closeness, value): the first beta are the ones to average.  One 64-bit key per
-    // average: the bits of its (non-negative) closeness above an image of its own bits that orders
-    // like the values (sign bit flipped for positive values, all bits for negative ones).
+    // ordered by (closeness, value): the first beta are the ones to average
     unsigned long long key[THETA];
 #pragma unroll
-    for (int p = 0; p < THETA; ++p) {
-        const unsigned ua = __float_as_uint(a[p]);
-        const unsigned img = ua ^ ((unsigned)((int)ua >> 31) | 0x80000000u);
-        key[p] = ((unsigned long long)__float_as_uint(fabsf(a[p] - med)) << 32) | img;
-    }
+    for (int p = 0; p < THETA; ++p) key[p] = closeness_key(a[p], med);
     sort_registers<THETA>(key);
     float sum = 0.0f;
 #pragma unroll
-    for (int p = 0; p < THETA; ++p) {
-        const unsigned img = (unsigned)key[p];
-        const unsigned ua = img ^ ((img >> 31) ? 0x80000000u : 0xffffffffu);
-        sum += (p < beta) ? __uint_as_float(ua) : 0.0f;
-    }
+    for (int p = 0; p < THETA; ++p) sum += (p < beta) ? key_value(key[p]) : 0.0f;
     return sum / (float)beta;
 }
 
@@ -156,7 +161,8 @@ __device__ __forceinline__ float pick_closest(float (&a)[THETA], float med, int 
 // time, so the changes are multiply-adds by -1, 0 or +1 held in scalar registers.  In the usual
 // case (each round's set = the previous one minus its winner) round 0 touches every slot and every
 // later round one.  The running sums S_t = P_0 + .. + P_t times 1 / |set_t| are the averages.
-// B1: beta = 1, the one average closest to the median is picked while the running sums are formed
+// SMALL = 1: beta = 1, the one average closest to the median is picked while the running sums are formed
+// (SMALL = 3: beta = 2 or 3, i.e. n = 4f + 4 or 4f + 5 with the default theta: the three closest are kept)
 // and a lane owns two neighbouring coordinates (8-byte loads when the rows allow it).
 constexpr int kThreads = 256;
 constexpr int kBatch = 16;
@@ -183,13 +189,13 @@ __device__ __forceinline__ void more_slots(int U, Load &load, Apply &apply)
     }
 }
 
-template <int THETA, bool B1>
+template <int THETA, int SMALL>
 __global__ __launch_bounds__(kThreads) void coord_alg1_kernel(const Elem *__restrict__ G, int64_t d, int64_t ld,
                                                               int beta, const int32_t *__restrict__ plan,
                                                               int unless_nested, float *__restrict__ out)
 {
     if (unless_nested && plan[kPlanNested]) return;   // coord_alg1_nested_kernel takes the call
-    constexpr int VEC = B1 ? 2 : 1;
+    constexpr int VEC = SMALL ? 2 : 1;
     const int64_t c = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * VEC;
     if (c >= d) return;
     const bool two = VEC == 2 && c + 1 < d;
@@ -262,7 +268,7 @@ __global__ __launch_bounds__(kThreads) void coord_alg1_kernel(const Elem *__rest
     for (int k = 0; k < VEC; ++k) {
         float S = 0.0f;
         const float med = meds[k];
-        if constexpr (B1) {
+        if constexpr (SMALL == 1) {
             float best = 0.0f, bd = __builtin_huge_valf();
 #pragma unroll
             for (int t = 0; t < THETA; ++t) {
@@ -274,6 +280,23 @@ __global__ __launch_bounds__(kThreads) void coord_alg1_kernel(const Elem *__rest
                 bd = take ? dt : bd;
             }
             res[k] = best;
+        } else if constexpr (SMALL == 3) {
+            // the three smallest keys so far, in order; a new one is passed down the three and what
+            // falls out at the end is dropped (the same keys, hence the same choice and the same
+            // order of addition, as the network of pick_closest)
+            unsigned long long k0 = ~0ull, k1 = ~0ull, k2 = ~0ull;
+#pragma unroll
+            for (int t = 0; t < THETA; ++t) {
+                S += P[k][t];
+                unsigned long long x = closeness_key(S * inv_m[t], med);
+                cswap(k0, x);
+                cswap(k1, x);
+                cswap(k2, x);
+            }
+            float sum = key_value(k0);
+            if (THETA > 1) sum += key_value(k1);
+            if (THETA > 2 && beta > 2) sum += key_value(k2);
+            res[k] = sum / (float)beta;
         } else {
             float a[THETA];
 #pragma unroll
@@ -378,11 +401,15 @@ hipError_t launch_theta(const CoordAlg1Args &a, hipStream_t s)
         if (both)
             coord_alg1_nested_kernel<THETA><<<dim3((unsigned)blocks), dim3(kThreads), 0, s>>>(static_cast<const Elem *>(a.G), a.d, a.ld, a.beta,
                                                                                              a.plan, a.out);
-        coord_alg1_kernel<THETA, true><<<dim3((unsigned)blocks), dim3(kThreads), 0, s>>>(static_cast<const Elem *>(a.G), a.d, a.ld, a.beta,
+        coord_alg1_kernel<THETA, 1><<<dim3((unsigned)blocks), dim3(kThreads), 0, s>>>(static_cast<const Elem *>(a.G), a.d, a.ld, a.beta,
                                                                                        a.plan, both, a.out);
+    } else if (a.beta <= 3 && THETA >= 3) {
+        const int64_t blocks = (a.d + 2 * kThreads - 1) / (2 * kThreads);
+        coord_alg1_kernel<THETA, 3><<<dim3((unsigned)blocks), dim3(kThreads), 0, s>>>(static_cast<const Elem *>(a.G), a.d, a.ld, a.beta,
+                                                                                    a.plan, 0, a.out);
     } else {
         const int64_t blocks = (a.d + kThreads - 1) / kThreads;
-        coord_alg1_kernel<THETA, false><<<dim3((unsigned)blocks), dim3(kThreads), 0, s>>>(static_cast<const Elem *>(a.G), a.d, a.ld, a.beta,
+        coord_alg1_kernel<THETA, 0><<<dim3((unsigned)blocks), dim3(kThreads), 0, s>>>(static_cast<const Elem *>(a.G), a.d, a.ld, a.beta,
                                                                                         a.plan, 0, a.out);
     }
     return hipGetLastError();
