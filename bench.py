@@ -73,9 +73,12 @@ def sweep():
 
 
 def host_resident(a, mb, W, n, f, d, mode, dtype):
-    """Gradients that stay in (pinned) host memory: every step uploads them twice (the selection needs the
-    distances over all coordinates before any coordinate can be aggregated) and downloads the result."""
+    """Gradients that stay in (pinned) host memory: every step uploads them (once if they fit the device; twice
+    if not, or with --host-two-sweeps: the selection needs the distances over all coordinates before any
+    coordinate can be aggregated) and downloads the result."""
     import torch
+    mb.mbulyan_host_resident_limit(0 if a.host_two_sweeps else -1)
+    uploads = 2 if a.host_two_sweeps else 1
     g = torch.empty(n, d, device="cuda:0", dtype=torch.float32)
     W.fill(a.config, g, 0)
     host = torch.empty(n, d, dtype=dtype, pin_memory=True)
@@ -94,9 +97,9 @@ def host_resident(a, mb, W, n, f, d, mode, dtype):
         "value": round(eb * n * d / sec / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": round(sec * 1e3, 3), "higher_is_better": True, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"configs[{a.config - 1}] with d={d}: n={n} f={f} {a.input_dtype}, mode={a.mode}, host-resident, "
-                               f"chunks of {a.host_resident} coordinates"},
-        "pcie_bytes_per_step": int(2 * eb * n * d + 4 * d),
-        "pcie_GBps": round((2 * eb * n * d + 4 * d) / sec / 1e9, 2)}), flush=True)
+                               f"chunks of {a.host_resident} coordinates, uploaded {'twice' if uploads == 2 else 'once'}"},
+        "pcie_bytes_per_step": int(uploads * eb * n * d + 4 * d),
+        "pcie_GBps": round((uploads * eb * n * d + 4 * d) / sec / 1e9, 2)}), flush=True)
 
 
 def main():
@@ -121,6 +124,9 @@ def main():
                     help="time mbulyan_aggregate_host instead: the workload in pinned HOST memory, uploaded twice in "
                          "column chunks of CHUNK_D coordinates (a PCIe-inclusive rate: a line of its own, never the "
                          "headline value)")
+    ap.add_argument("--host-two-sweeps", action="store_true",
+                    help="with --host-resident: force the path of a matrix beyond the device (two uploads) although "
+                         "this one fits and would be uploaded once")
     a = ap.parse_args()
     if a.sweep:
         return sweep()

@@ -332,10 +332,18 @@ int mbulyan_aggregate_chunked_fp16(const uint16_t *const *chunks, int nchunks,
  * allocates and frees device memory (its chunk buffers) and RETURNS ONLY WHEN THE
  * RESULT IS IN host_out.  The rate is that of the host link, twice over: the
  * device-resident entry points are the ones to time.
+ * A matrix that fits the device is uploaded once instead: the first sweep leaves
+ * its chunks in one device matrix (n d values plus d floats and a workspace, for
+ * the length of the call) and the coordinate pass runs over it in one go.  It
+ * "fits" if that is within mbulyan_host_resident_limit: by default three quarters
+ * of the device memory free when the call starts; 0 = always two sweeps; any
+ * other value = that many bytes; negative = the default again.  Process-wide,
+ * host only.  Same results either way.
  */
 #define MB_STORE_FP32 0
 #define MB_STORE_BF16 1
 #define MB_STORE_FP16 2
+int mbulyan_host_resident_limit(long long bytes);
 int mbulyan_aggregate_host(const void *host_grads, int storage, int n, int f,
                            int64_t d, int64_t ld, int mode, int64_t chunk_d,
                            float *host_out, int32_t *host_selected_idx,

@@ -31,7 +31,7 @@ EXPORTS = [
     "mbulyan_aggregate_noalloc",
     "pairwise_sqdist_fp16", "coordwise_trimmed_avg_fp16", "mbulyan_aggregate_fp16",
     "mbulyan_aggregate_chunked_fp16", "multikrum_aggregate_fp16", "coordwise_median_fp16",
-    "mbulyan_aggregate_host",
+    "mbulyan_aggregate_host", "mbulyan_host_resident_limit",
 ]
 
 
@@ -58,6 +58,7 @@ def _load() -> C.CDLL:
     lib.mbulyan_aggregate.argtypes = [vp, ci, ci, i64, vp, vp, vp]
     lib.mbulyan_aggregate_ex.argtypes = [vp, ci, ci, i64, i64, ci, ci, ci, vp, vp, vp, sz, vp]
     lib.mbulyan_aggregate_host.argtypes = [vp, ci, ci, ci, i64, i64, ci, i64, vp, vp, vp]
+    lib.mbulyan_host_resident_limit.argtypes = [C.c_longlong]
     lib.mbulyan_aggregate_noalloc.argtypes = [vp, ci, ci, i64, i64, ci, vp, vp, vp]
     lib.mbulyan_aggregate_chunked.argtypes = [C.POINTER(vp), ci, C.POINTER(i64), C.POINTER(i64), ci, ci, ci,
                                               C.POINTER(vp), vp, vp, sz, vp]
@@ -210,6 +211,12 @@ def mbulyan_aggregate_noalloc(grads, f, out, selected_idx=None, mode=MODE_SELECT
                                          _dev(selected_idx, torch.int32, "selected_idx", theta, grads),
                                          _stream(stream)))
     return out, selected_idx
+
+
+def mbulyan_host_resident_limit(nbytes: int):
+    """Host matrices up to this many bytes are uploaded once by mbulyan_aggregate_host (0: never; negative: the
+    default, three quarters of the free device memory)."""
+    _check(lib.mbulyan_host_resident_limit(int(nbytes)))
 
 
 def mbulyan_aggregate_host(host_grads, f, chunk_d, mode=MODE_SELECTED, host_out=None, stream=None):

@@ -233,9 +233,18 @@ hipError_t launch_theta(const CoordArgs &a, hipStream_t s)
             coord_selected_kernel<THETA, 2, (H > 0 ? H : 1), FMT><<<grid, block, 0, s>>>(
                 a.G, a.n, a.d, a.ld, a.sel, K, a.median_only, scale, a.out);
     } else {
+        // one coordinate per lane, element loads; the same windows as above, so that a result does
+        // not depend on how the matrix happens to be aligned (the windows add in different orders)
         const dim3 grid((unsigned)((a.d + 255) / 256));
-        coord_selected_kernel<THETA, 1, (H > 0 ? H : 1), FMT><<<grid, block, 0, s>>>(
-            a.G, a.n, a.d, a.ld, a.sel, K, a.median_only, scale, a.out);
+        if (K <= 2 && H > 2)
+            coord_selected_kernel<THETA, 1, 2, FMT><<<grid, block, 0, s>>>(a.G, a.n, a.d, a.ld, a.sel, K,
+                                                                            a.median_only, scale, a.out);
+        else if (K <= 4 && H > 4)
+            coord_selected_kernel<THETA, 1, 4, FMT><<<grid, block, 0, s>>>(a.G, a.n, a.d, a.ld, a.sel, K,
+                                                                            a.median_only, scale, a.out);
+        else
+            coord_selected_kernel<THETA, 1, (H > 0 ? H : 1), FMT><<<grid, block, 0, s>>>(
+                a.G, a.n, a.d, a.ld, a.sel, K, a.median_only, scale, a.out);
     }
     return hipGetLastError();
 }

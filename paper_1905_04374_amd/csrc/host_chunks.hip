@@ -6,16 +6,23 @@
 // coordinates (Algorithm 1 computes them over whole gradients) before any coordinate can be
 // aggregated.  Sweep 1: upload, distance pass accumulating into one n x n matrix.  Then the
 // selection.  Sweep 2: upload again, coordinate pass, download of that chunk's part of the result.
+// A matrix that fits the device next to everything else is uploaded once instead: sweep 1 leaves the
+// chunks in one device matrix and the coordinate pass runs over it in one go (half the bytes over
+// the link).  "Fits": n d values within mbulyan_host_resident_limit (default: three quarters of the
+// device memory that is free when the call starts; 0 switches the single upload off).
 // Everything the kernels do goes through the library's own entry points (pairwise_sqdist with
 // accumulate, multikrum_select, coordwise_trimmed_avg); this file only moves data and orders events.
 // Copies run on a stream of their own (default priority), kernels on the caller's stream.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
 
 #include "../../include/mbulyan.h"
 
 namespace {
+
+std::atomic<long long> g_resident_limit{-1};   // bytes; -1: three quarters of the free device memory
 
 struct Guard {   // frees what the call allocated, whatever way it ends
     void *dev[8] = {};
@@ -71,20 +78,99 @@ int dist_chunk(const void *buf, int storage, int n, int64_t w, double *dist, int
     }
 }
 
-int coord_chunk(const void *buf, int storage, int n, int64_t w, const int32_t *sel, int theta, int beta,
+int coord_chunk(const void *buf, int storage, int n, int64_t w, int64_t ld, const int32_t *sel, int theta, int beta,
                 const uint8_t *sets, float *out, hipStream_t s)
 {
     switch (storage) {
         case MB_STORE_FP32:
-            return coordwise_trimmed_avg(static_cast<const float *>(buf), n, w, w, sel, theta, beta, sets, out, s);
+            return coordwise_trimmed_avg(static_cast<const float *>(buf), n, w, ld, sel, theta, beta, sets, out, s);
         case MB_STORE_BF16:
-            return coordwise_trimmed_avg_bf16(static_cast<const uint16_t *>(buf), n, w, w, sel, theta, beta, sets, out, s);
+            return coordwise_trimmed_avg_bf16(static_cast<const uint16_t *>(buf), n, w, ld, sel, theta, beta, sets, out, s);
         default:
-            return coordwise_trimmed_avg_fp16(static_cast<const uint16_t *>(buf), n, w, w, sel, theta, beta, sets, out, s);
+            return coordwise_trimmed_avg_fp16(static_cast<const uint16_t *>(buf), n, w, ld, sel, theta, beta, sets, out, s);
     }
 }
 
+
+// d small enough for the device: chunks are uploaded into one n x d device matrix (row stride d)
+// while the distance pass follows them chunk by chunk; the coordinate pass then takes the whole
+// matrix at once.
+int aggregate_uploaded_once(const void *host_grads, int storage, int n, int f, int64_t d, int64_t ld, int mode,
+                            int64_t chunk_d, int theta, int beta, float *host_out, int32_t *host_selected_idx,
+                            hipStream_t compute)
+{
+    const size_t eb = storage == MB_STORE_FP32 ? 4 : 2;
+    // chunks start on 16-byte boundaries of the device rows (the fast load path of the distance pass)
+    const int64_t per16 = (int64_t)(16 / eb);
+    if (chunk_d % per16) chunk_d += per16 - chunk_d % per16;
+    const int64_t nchunks = (d + chunk_d - 1) / chunk_d;
+    const int64_t ldd = (d + per16 - 1) / per16 * per16;   // device rows start on 16-byte boundaries as well
+    Guard g;
+    g.compute = compute;
+    size_t ws_bytes = 0;
+    HC_MB(mbulyan_workspace_bytes(n, d, &ws_bytes));
+    void *whole = nullptr, *ws = nullptr;
+    double *dist = nullptr;
+    float *out = nullptr;
+    int32_t *sel = nullptr;
+    uint8_t *sets = nullptr;
+    HC_HIP(g.alloc(&whole, eb * (size_t)n * (size_t)ldd));
+    HC_HIP(g.alloc(&ws, ws_bytes));
+    HC_HIP(g.alloc(reinterpret_cast<void **>(&dist), sizeof(double) * (size_t)n * n));
+    HC_HIP(g.alloc(reinterpret_cast<void **>(&out), sizeof(float) * (size_t)d));
+    HC_HIP(g.alloc(reinterpret_cast<void **>(&sel), 2 * sizeof(int32_t) * (size_t)theta));
+    HC_HIP(g.alloc(reinterpret_cast<void **>(&sets), (size_t)theta * (size_t)n));
+    int32_t *m = sel + theta;
+    HC_HIP(hipStreamCreateWithFlags(&g.copy, hipStreamNonBlocking));   // default priority
+    hipEvent_t start, uploaded[2];
+    HC_HIP(g.event(&start));
+    HC_HIP(g.event(&uploaded[0]));
+    HC_HIP(g.event(&uploaded[1]));
+    g.launched = true;
+    HC_HIP(hipEventRecord(start, compute));      // the caller's earlier work on its stream comes first
+    HC_HIP(hipStreamWaitEvent(g.copy, start, 0));
+    const char *src = static_cast<const char *>(host_grads);
+    char *dst = static_cast<char *>(whole);
+    for (int64_t c = 0; c < nchunks; ++c) {
+        const int64_t c0 = c * chunk_d, w = (c0 + chunk_d <= d) ? chunk_d : d - c0;
+        const int k = (int)(c & 1);
+        HC_HIP(hipMemcpy2DAsync(dst + eb * (size_t)c0, eb * (size_t)ldd, src + eb * (size_t)c0, eb * (size_t)ld,
+                                eb * (size_t)w, (size_t)n, hipMemcpyHostToDevice, g.copy));
+        // an event may be recorded again once the wait on its last record has been enqueued: two in turn
+        HC_HIP(hipEventRecord(uploaded[k], g.copy));
+        HC_HIP(hipStreamWaitEvent(compute, uploaded[k], 0));
+        const void *chunk = dst + eb * (size_t)c0;
+        switch (storage) {
+            case MB_STORE_FP32:
+                HC_MB(pairwise_sqdist(static_cast<const float *>(chunk), n, w, ldd, dist, c > 0, MB_DIST_AUTO, ws, ws_bytes,
+                                      compute));
+                break;
+            case MB_STORE_BF16:
+                HC_MB(pairwise_sqdist_bf16(static_cast<const uint16_t *>(chunk), n, w, ldd, dist, c > 0, ws, ws_bytes,
+                                           compute));
+                break;
+            default:
+                HC_MB(pairwise_sqdist_fp16(static_cast<const uint16_t *>(chunk), n, w, ldd, dist, c > 0, ws, ws_bytes,
+                                           compute));
+        }
+    }
+    HC_MB(multikrum_select(dist, n, f, theta, sel, sets, m, compute));
+    HC_MB(coord_chunk(whole, storage, n, d, ldd, sel, theta, beta, mode == MB_MODE_ALG1 ? sets : nullptr, out, compute));
+    HC_HIP(hipMemcpyAsync(host_out, out, sizeof(float) * (size_t)d, hipMemcpyDeviceToHost, compute));
+    if (host_selected_idx)
+        HC_HIP(hipMemcpyAsync(host_selected_idx, sel, sizeof(int32_t) * (size_t)theta, hipMemcpyDeviceToHost, compute));
+    HC_HIP(hipStreamSynchronize(g.copy));
+    HC_HIP(hipStreamSynchronize(compute));
+    return MB_OK;
+}
+
 }  // namespace
+
+extern "C" int mbulyan_host_resident_limit(long long bytes)
+{
+    g_resident_limit.store(bytes < 0 ? -1 : bytes);
+    return MB_OK;
+}
 
 extern "C" int mbulyan_aggregate_host(const void *host_grads, int storage, int n, int f, int64_t d, int64_t ld, int mode,
                                       int64_t chunk_d, float *host_out, int32_t *host_selected_idx, void *stream)
@@ -97,6 +183,22 @@ extern "C" int mbulyan_aggregate_host(const void *host_grads, int storage, int n
     const size_t eb = storage == MB_STORE_FP32 ? 4 : 2;
     const int64_t nchunks = (d + chunk_d - 1) / chunk_d;
     hipStream_t compute = (hipStream_t)stream;
+
+    // the whole matrix on the device, if it fits: one upload
+    {
+        long long limit = g_resident_limit.load();
+        if (limit < 0) {
+            size_t free_b = 0, total_b = 0;
+            HC_HIP(hipMemGetInfo(&free_b, &total_b));
+            limit = (long long)(free_b / 4 * 3);
+        }
+        size_t whole_ws = 0;
+        HC_MB(mbulyan_workspace_bytes(n, d, &whole_ws));
+        const double need = (double)eb * n * ((double)d + 8.0) + 4.0 * (double)d + (double)whole_ws + 65536.0;
+        if (need <= (double)limit)
+            return aggregate_uploaded_once(host_grads, storage, n, f, d, ld, mode, chunk_d, theta, beta, host_out,
+                                           host_selected_idx, compute);
+    }
 
     Guard g;
     g.compute = compute;
@@ -151,7 +253,7 @@ extern "C" int mbulyan_aggregate_host(const void *host_grads, int storage, int n
                 HC_MB(dist_chunk(buf[k], storage, n, w, dist, c > 0, ws, ws_bytes, compute));
             } else {
                 if (wrote[k]) HC_HIP(hipStreamWaitEvent(compute, produced[k], 0));   // out[k] has been downloaded
-                HC_MB(coord_chunk(buf[k], storage, n, w, sel, theta, beta, mode == MB_MODE_ALG1 ? sets : nullptr, out[k],
+                HC_MB(coord_chunk(buf[k], storage, n, w, w, sel, theta, beta, mode == MB_MODE_ALG1 ? sets : nullptr, out[k],
                                   compute));
             }
             HC_HIP(hipEventRecord(consumed[k], compute));

@@ -1,7 +1,8 @@
-"""mbulyan_aggregate_host: gradients that stay in host memory, uploaded in column chunks (two sweeps, the
-upload of one chunk overlapping the kernels of the one before).  The kernels are those of the chunked
-device-resident entry point on the same chunk boundaries, so the extracted list and the output must be
-bit-identical to it; and the whole is compared with the oracle."""
+"""mbulyan_aggregate_host: gradients that stay in host memory, uploaded in column chunks (the upload of one
+chunk overlapping the kernels of the one before; once if the matrix fits the device, else in two sweeps).
+The distances accumulate over the same chunk boundaries as in the chunked device-resident entry point and
+the coordinate kernels are the same, so the extracted list and the output must be bit-identical to it;
+and the whole is compared with the oracle."""
 import sys
 
 import numpy as np
@@ -19,11 +20,21 @@ DEV = "cuda:0"
 
 
 
+@pytest.fixture(autouse=True)
+def default_limit_afterwards():
+    yield
+    mb.mbulyan_host_resident_limit(-1)
+
+
+@pytest.mark.parametrize("uploads", ["once", "twice"])
 @pytest.mark.parametrize("pinned", [True, False])
 @pytest.mark.parametrize("mode", [mb.MODE_SELECTED, mb.MODE_ALG1])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
-def test_host_resident_gradients(dtype, mode, pinned):
-    say("host chunks", dtype, mode, pinned)
+def test_host_resident_gradients(dtype, mode, pinned, uploads):
+    """uploads: the matrix fits the device and is uploaded once (the default for this size), or the two-sweep
+    path that a matrix beyond the device takes, forced by a limit of 0."""
+    say("host chunks", dtype, mode, pinned, uploads)
+    mb.mbulyan_host_resident_limit(-1 if uploads == "once" else 0)
     s = W.spec(3)
     n, f = s["n"], s["f"]
     d, chunk_d = 700_013, 160_000                     # 5 chunks, the last one short and oddly sized

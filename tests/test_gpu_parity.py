@@ -435,6 +435,32 @@ def test_aggregate_chunked_alg1_mode(in16):
     assert torch.equal(sel, sel2) and torch.equal(torch.cat(outs), torch.cat(outs2))
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("n,f", [(11, 2), (13, 2), (17, 2), (39, 9), (40, 9)])   # beta 3, 5, 9, 3, 4 (selected)
+def test_result_does_not_depend_on_alignment(n, f, dtype):
+    """The same gradients in a contiguous, 16-byte aligned matrix and in one whose rows start at odd element
+    offsets take different kernels (vector loads of two or four coordinates per lane, or element loads); the
+    extracted list and every output bit must be the same, in both readings, also for the multi-Krum
+    average and the median."""
+    say("alignment", n, f, dtype)
+    d = 40_001
+    rng = np.random.default_rng(7 * n + f)
+    mu = rng.standard_normal(d).astype(np.float32)
+    G = np.stack([mu + 0.3 * (1 + 0.03 * w) * rng.standard_normal(d).astype(np.float32) for w in range(n)])
+    A = gpu(G).to(dtype)
+    wide = torch.zeros(n, d + 7, device=DEV, dtype=dtype)
+    B = wide[:, 3:3 + d]                                # odd row stride, rows start 3 elements in
+    B.copy_(A)
+    for mode in (mb.MODE_SELECTED, mb.MODE_ALG1):
+        oa, sa = mb.mbulyan_aggregate_ex(A, f, mode=mode)
+        ob, sb = mb.mbulyan_aggregate_ex(B, f, mode=mode)
+        assert torch.equal(sa, sb) and torch.equal(oa, ob), mode
+    ma, ka = mb.multikrum_aggregate(A, f)
+    mbb, kb = mb.multikrum_aggregate(B, f)
+    assert torch.equal(ka, kb) and torch.equal(ma, mbb)
+    assert torch.equal(mb.coordwise_median(A), mb.coordwise_median(B))
+
+
 @pytest.mark.parametrize("in16", [False, True])
 @pytest.mark.parametrize("mode", ["selected", "alg1"])
 def test_scaling_by_a_power_of_two_is_exact(mode, in16):
