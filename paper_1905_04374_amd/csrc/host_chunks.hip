@@ -23,6 +23,7 @@
 namespace {
 
 std::atomic<long long> g_resident_limit{-1};   // bytes; -1: three quarters of the free device memory
+constexpr int kTwoSweepsInstead = -1000;        // internal: the device matrix could not be allocated after all
 
 struct Guard {   // frees what the call allocated, whatever way it ends
     void *dev[8] = {};
@@ -114,7 +115,10 @@ int aggregate_uploaded_once(const void *host_grads, int storage, int n, int f, i
     float *out = nullptr;
     int32_t *sel = nullptr;
     uint8_t *sets = nullptr;
-    HC_HIP(g.alloc(&whole, eb * (size_t)n * (size_t)ldd));
+    if (g.alloc(&whole, eb * (size_t)n * (size_t)ldd) != hipSuccess) {   // free memory, but not in one piece
+        (void)hipGetLastError();
+        return kTwoSweepsInstead;
+    }
     HC_HIP(g.alloc(&ws, ws_bytes));
     HC_HIP(g.alloc(reinterpret_cast<void **>(&dist), sizeof(double) * (size_t)n * n));
     HC_HIP(g.alloc(reinterpret_cast<void **>(&out), sizeof(float) * (size_t)d));
@@ -195,9 +199,11 @@ extern "C" int mbulyan_aggregate_host(const void *host_grads, int storage, int n
         size_t whole_ws = 0;
         HC_MB(mbulyan_workspace_bytes(n, d, &whole_ws));
         const double need = (double)eb * n * ((double)d + 8.0) + 4.0 * (double)d + (double)whole_ws + 65536.0;
-        if (need <= (double)limit)
-            return aggregate_uploaded_once(host_grads, storage, n, f, d, ld, mode, chunk_d, theta, beta, host_out,
-                                           host_selected_idx, compute);
+        if (need <= (double)limit) {
+            const int rc = aggregate_uploaded_once(host_grads, storage, n, f, d, ld, mode, chunk_d, theta, beta, host_out,
+                                                   host_selected_idx, compute);
+            if (rc != kTwoSweepsInstead) return rc;
+        }
     }
 
     Guard g;
